@@ -1,0 +1,423 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test states the passage it checks.  None of them re-types the oracle's
+own formulas as the expected value: expectations are brute force on exact
+integer data, textbook softmax attention, closed forms, published
+known-answer vectors, or statistical laws the lemmas assert.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle.subgen_oracle import OracleStream, exact_attention, philox4x32_10, uniform24
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# --------------------------------------------------------------------------
+# random numbers (the coin flips of Algorithm 1)
+# --------------------------------------------------------------------------
+def test_philox_known_answer_vectors():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        v = [int(x, 16) for x in r]
+        assert philox4x32_10(v[0:4], v[4:6]) == v[6:10]
+
+
+def test_uniform24_counter_layout_and_range():
+    # slot j uses word j%4 of the block with counter (j//4, token lo, token hi, stream), key = seed
+    seed, stream, token = 0x0123456789ABCDEF, 77, (5 << 32) + 9
+    for slot in [0, 1, 2, 3, 4, 7, 1023]:
+        words = philox4x32_10([slot // 4, token & 0xFFFFFFFF, token >> 32, stream],
+                              [seed & 0xFFFFFFFF, seed >> 32])
+        expect = (words[slot % 4] >> 8) / 2.0 ** 24
+        got = uniform24(seed, stream, token, slot)
+        assert got == expect and 0.0 <= got < 1.0
+
+
+def test_uniform24_is_uniform_and_slots_are_independent():
+    u = np.array([[uniform24(3, 1, t, j) for j in range(8)] for t in range(20000)])
+    # chi-square on 16 bins per slot, 15 dof: 99.99% quantile is ~44
+    for j in range(8):
+        h, _ = np.histogram(u[:, j], bins=16, range=(0, 1))
+        chi = ((h - 1250.0) ** 2 / 1250.0).sum()
+        assert chi < 50.0
+    # serial pairs (neighbouring slots, neighbouring tokens): correlation ~ N(0, 1/n)
+    assert abs(np.corrcoef(u[:, 0], u[:, 1])[0, 1]) < 0.04
+    assert abs(np.corrcoef(u[:-1, 2], u[1:, 2])[0, 1]) < 0.04
+    # different streams / seeds give different sequences
+    assert uniform24(3, 1, 5, 0) != uniform24(3, 2, 5, 0)
+    assert uniform24(3, 1, 5, 0) != uniform24(4, 1, 5, 0)
+
+
+# --------------------------------------------------------------------------
+# clustering (UpdateSoftmaxNormalizer, Lemma 2, Definition 1)
+# --------------------------------------------------------------------------
+def brute_force_clusters(keys, delta):
+    """Greedy threshold clustering in exact integer arithmetic (pure Python)."""
+    centers, counts, assign = [], [], []
+    for k in keys:
+        best, arg = None, -1
+        for i, x in enumerate(centers):
+            dist2 = sum((int(a) - int(b)) ** 2 for a, b in zip(x, k))
+            if best is None or dist2 < best:
+                best, arg = dist2, i
+        if arg >= 0 and best <= delta * delta:
+            counts[arg] += 1
+            assign.append(arg)
+        else:
+            centers.append(list(k))
+            counts.append(1)
+            assign.append(len(centers) - 1)
+    return centers, counts, assign
+
+
+@pytest.mark.parametrize("seed,d,delta", [(0, 1, 2), (1, 2, 3), (2, 3, 4), (3, 4, 5), (4, 4, 0)])
+def test_clustering_matches_integer_brute_force(seed, d, delta):
+    r = rng(seed)
+    keys = r.integers(-8, 9, size=(64, d))
+    o = OracleStream(d, delta, s=4, w=0)
+    o.ingest(keys, r.normal(size=(64, d)))
+    centers, counts, assign = brute_force_clusters(keys, delta)
+    assert o.m == len(centers)
+    assert o.centers.astype(int).tolist() == centers
+    assert o.counts.tolist() == counts
+    assert o.assign.tolist() == assign
+
+
+def test_threshold_is_inclusive_and_ties_go_to_lowest_index():
+    # 3-4-5 triangle: distance exactly 5 joins at delta = 5, not at delta just below
+    for delta, m_expect in [(5.0, 1), (np.nextafter(np.float32(5.0), np.float32(0.0)), 2)]:
+        o = OracleStream(2, delta, s=1, w=0)
+        o.ingest([[0, 0], [3, 4]], [[1, 0], [1, 0]])
+        assert o.m == m_expect
+    # two representatives at equal distance from the third key: the older one wins
+    o = OracleStream(1, 2.0, s=1, w=0)
+    o.ingest([[0.0], [4.0], [2.0]], np.ones((3, 1)))
+    assert o.m == 2 and o.counts.tolist() == [2, 1] and o.assign.tolist() == [0, 1, 0]
+    o = OracleStream(1, 2.0, s=1, w=0)
+    o.ingest([[4.0], [0.0], [2.0]], np.ones((3, 1)))
+    assert o.centers[:, 0].tolist() == [4.0, 0.0] and o.counts.tolist() == [2, 1]
+
+
+def test_nearest_not_first_within_threshold():
+    # both representatives are within delta; the nearer (later) one must win
+    o = OracleStream(1, 3.0, s=1, w=0)
+    o.ingest([[0.0], [4.0], [2.5]], np.ones((3, 1)))
+    assert o.assign.tolist() == [0, 1, 1]
+
+
+@pytest.mark.parametrize("w", [0, 5])
+def test_lemma2_invariants_on_random_stream(w):
+    r = rng(10 + w)
+    n, d, delta = 600, 8, 2.5
+    comp = r.integers(0, 12, size=n)
+    cent = r.normal(size=(12, d)) * 3
+    K = (cent[comp] + 0.5 * r.normal(size=(n, d))).astype(np.float32)
+    o = OracleStream(d, delta, s=8, w=w)
+    o.ingest(K, r.normal(size=(n, d)))
+    X, cnt, a = o.centers.astype(np.float64), o.counts, o.assign
+    ev = K[: n - w].astype(np.float64)        # evicted tokens, in order
+    assert o.n_evicted == n - w and len(a) == n - w
+    # (2) counts are cluster sizes; they add up to the evicted tokens; window holds the rest
+    assert np.array_equal(cnt, np.bincount(a, minlength=o.m))
+    assert cnt.min() >= 1 and cnt.sum() + o.window_fill == o.n_seen == n
+    # (1) the representative is the first key assigned to its cluster
+    for j in range(o.m):
+        assert np.array_equal(X[j], ev[np.flatnonzero(a == j)[0]])
+    # (3) every key within delta of its representative
+    assert (np.linalg.norm(ev - X[a], axis=1) <= delta).all()
+    # (4) representatives pairwise more than delta apart
+    D = np.linalg.norm(X[:, None] - X[None], axis=-1) + 1e9 * np.eye(o.m)
+    assert (D > delta).all()
+    # created flag marks exactly the first member of each cluster
+    assert o.created.sum() == o.m
+
+
+def test_separated_groups_give_exactly_m_centers_for_any_order():
+    # Definition 1 + pigeonhole argument of Theorem 1: m groups of diameter <= delta whose
+    # members are > delta away from every other group's members give exactly m clusters
+    r = rng(5)
+    m, d, delta = 7, 6, 1.0
+    base = r.normal(size=(m, d))
+    base *= 10.0 / np.linalg.norm(base, axis=1, keepdims=True) * np.arange(1, m + 1)[:, None]
+    sizes = r.integers(3, 30, size=m)
+    pts, lab = [], []
+    for j in range(m):
+        off = r.normal(size=(sizes[j], d))
+        off *= (0.49 * delta * r.random((sizes[j], 1))) / np.linalg.norm(off, axis=1, keepdims=True)
+        pts.append(base[j] + off)
+        lab += [j] * sizes[j]
+    pts, lab = np.concatenate(pts).astype(np.float32), np.array(lab)
+    for trial in range(5):
+        perm = r.permutation(len(pts))
+        o = OracleStream(d, delta, s=2, w=0)
+        o.ingest(pts[perm], np.ones((len(pts), d)))
+        assert o.m == m
+        # each cluster is one group: counts equal group sizes
+        got = sorted(o.counts.tolist())
+        assert got == sorted(sizes.tolist())
+        first_lab = [lab[perm][np.flatnonzero(o.assign == j)[0]] for j in range(m)]
+        assert sorted(first_lab) == list(range(m))
+
+
+def test_capacity_overflow_joins_nearest():
+    o = OracleStream(1, 0.5, s=1, w=0, max_centers=2)
+    o.ingest([[0.0], [10.0], [20.0], [4.0]], np.ones((4, 1)))
+    assert o.m == 2 and o.overflowed
+    assert o.assign.tolist() == [0, 1, 1, 0] and o.counts.tolist() == [2, 2]
+
+
+# --------------------------------------------------------------------------
+# sampling (UpdateMatrixProduct, Lemma 1)
+# --------------------------------------------------------------------------
+def test_mu_and_first_token_fill():
+    r = rng(1)
+    V = r.normal(size=(40, 5)).astype(np.float32)
+    o = OracleStream(5, 1.0, s=16, w=3)
+    for t in range(40):
+        o.update(r.normal(size=5), V[t])
+        if t < 3:
+            assert (o.sample_idx == -1).all() and o.mu == 0.0
+        if t == 3:      # first eviction: all slots hold token 0 (Section 2.2)
+            assert (o.sample_idx == 0).all()
+            assert np.array_equal(o.sample_v, np.tile(V[0], (16, 1)))
+    vn = (V[:37].astype(np.float64) ** 2).sum(1).astype(np.float32).astype(np.float64)
+    assert o.mu == pytest.approx(vn.sum(), rel=1e-14)
+    # stored per-slot squared norms and rows are those of the token the slot names
+    idx = o.sample_idx
+    assert np.array_equal(o.sample_vn, vn[idx].astype(np.float32))
+    assert np.array_equal(o.sample_v, V[idx])
+
+
+def test_second_token_probability_uses_mu_before_update():
+    # two tokens with ||v1||^2 = 1, ||v2||^2 = 3: each slot must hold token 2 w.p. 3/4
+    # (it would be 3/7 if mu were bumped before the coin flips)
+    s = 40000
+    o = OracleStream(1, 1.0, s=s, w=0, seed=9)
+    o.update([0.0], [1.0])
+    o.update([5.0], [math.sqrt(3.0)])
+    frac = (o.sample_idx == 1).mean()
+    assert abs(frac - 0.75) < 5 * math.sqrt(0.75 * 0.25 / s)
+
+
+def test_lemma1_sampling_frequencies_and_slot_independence():
+    r = rng(2)
+    n, s, d = 12, 6, 3
+    V = (r.normal(size=(n, d)) * r.uniform(0.3, 2.0, size=(n, 1))).astype(np.float32)
+    K = r.normal(size=(n, d)).astype(np.float32)
+    pr = (V.astype(np.float64) ** 2).sum(1)
+    pr /= pr.sum()
+    seeds = 6000
+    hist = np.zeros((s, n))
+    joint = np.zeros((n, n))
+    for seed in range(seeds):
+        o = OracleStream(d, 1.0, s=s, w=0, seed=seed)
+        o.ingest(K, V)
+        idx = o.sample_idx
+        hist[np.arange(s), idx] += 1
+        joint[idx[0], idx[1]] += 1
+    # chi-square per slot, n-1 = 11 dof: 99.99% quantile ~ 39
+    for j in range(s):
+        chi = ((hist[j] - seeds * pr) ** 2 / (seeds * pr)).sum()
+        assert chi < 45.0, (j, chi)
+    # slots 0 and 1 independent: chi-square on the joint table, 120 dof + slack
+    exp = seeds * np.outer(pr, pr)
+    mask = exp > 5
+    chi = ((joint - exp) ** 2 / exp)[mask].sum()
+    assert chi < mask.sum() + 6 * math.sqrt(2 * mask.sum())
+
+
+def test_zero_norm_values():
+    o = OracleStream(2, 1.0, s=8, w=0)
+    o.update([1.0, 0.0], [0.0, 0.0])          # first token, zero value: fills slots, mu stays 0
+    assert (o.sample_idx == 0).all() and o.mu == 0.0
+    q = np.array([0.3, 0.1], dtype=np.float32)
+    assert np.array_equal(o.attend(q), np.zeros(2))
+    o.update([1.0, 0.0], [2.0, 0.0])          # mu == 0 still: p = 1
+    assert (o.sample_idx == 1).all() and o.mu == 4.0
+    o.update([1.0, 0.0], [0.0, 0.0])          # zero value later: never sampled
+    assert (o.sample_idx == 1).all() and o.mu == 4.0
+
+
+# --------------------------------------------------------------------------
+# query (QueryStreamAttn) — closed forms, exact special cases, statistics
+# --------------------------------------------------------------------------
+def test_single_token_returns_its_value():
+    for w in [0, 1, 4]:
+        o = OracleStream(3, 1.0, s=5, w=w)
+        o.update([0.5, -1.0, 2.0], [1.5, -2.0, 0.25])
+        out = o.attend([0.1, 0.2, 0.3])
+        assert np.allclose(out, [1.5, -2.0, 0.25], rtol=1e-15)
+
+
+def test_window_only_equals_textbook_attention():
+    # n <= w: nothing is compressed, the answer is softmax(K q)^T V
+    r = rng(3)
+    n, d = 37, 16
+    K, V = r.normal(size=(n, d)).astype(np.float32), r.normal(size=(n, d)).astype(np.float32)
+    o = OracleStream(d, 0.7, s=4, w=64)
+    for t in range(n):
+        o.update(K[t], V[t])
+        q = r.normal(size=d).astype(np.float32)
+        assert np.allclose(o.attend(q), exact_attention(K[: t + 1], V[: t + 1], q), rtol=1e-12, atol=1e-14)
+    assert o.m == 0 and o.n_evicted == 0
+
+
+@pytest.mark.parametrize("w", [0, 7])
+def test_delta_zero_denominator_is_exact_partition_function(w):
+    r = rng(4)
+    n, d = 200, 8
+    K = r.normal(size=(40, d)).astype(np.float32)[r.integers(0, 40, size=n)]   # many exact duplicates
+    V = r.normal(size=(n, d)).astype(np.float32)
+    o = OracleStream(d, 0.0, s=8, w=w)
+    o.ingest(K, V)
+    assert o.m <= 40 and o.counts.sum() == n - w
+    q = r.normal(size=d).astype(np.float32)
+    _, den, mx = o.attend(q, return_den=True)
+    Z = np.exp(K.astype(np.float64) @ q.astype(np.float64)).sum()
+    assert den * math.exp(mx) == pytest.approx(Z, rel=1e-12)
+
+
+def test_denominator_within_exp_delta_r_of_partition_function():
+    # Lemma 2 (3) + Cauchy-Schwarz (as in the proof of Theorem 1): every key is within delta of
+    # its representative, so tau / Z lies in [e^{-delta |q|}, e^{+delta |q|}]
+    r = rng(6)
+    n, d, delta = 500, 8, 1.5
+    K = (r.normal(size=(10, d))[r.integers(0, 10, size=n)] * 3 + 0.4 * r.normal(size=(n, d))).astype(np.float32)
+    o = OracleStream(d, delta, s=4, w=16)
+    o.ingest(K, r.normal(size=(n, d)))
+    assert o.m < n // 4
+    for _ in range(10):
+        q = (r.normal(size=d) / math.sqrt(d)).astype(np.float32)
+        _, den, mx = o.attend(q, return_den=True)
+        ratio = den * math.exp(mx) / np.exp(K.astype(np.float64) @ q.astype(np.float64)).sum()
+        bound = math.exp(delta * np.linalg.norm(q.astype(np.float64)))
+        assert 1.0 / bound <= ratio <= bound
+        assert ratio != 1.0
+
+
+def test_identical_keys_one_center():
+    n, d = 50, 4
+    k = np.array([0.5, -0.25, 1.0, 2.0], dtype=np.float32)
+    r = rng(7)
+    o = OracleStream(d, 0.3, s=8, w=0)
+    o.ingest(np.tile(k, (n, 1)), r.normal(size=(n, d)))
+    q = np.array([0.2, 0.1, -0.3, 0.05], dtype=np.float32)
+    _, den, mx = o.attend(q, return_den=True)
+    assert o.m == 1 and o.counts.tolist() == [n]
+    assert den * math.exp(mx) == pytest.approx(n * math.exp(float(k.astype(np.float64) @ q.astype(np.float64))),
+                                               rel=1e-13)
+
+
+def test_identical_values_closed_form():
+    # all v equal: weights are n_evicted/s, so out = v * (sum_W e^a + n_ev/s sum_M e^c) / den
+    r = rng(8)
+    n, d, s, w = 120, 6, 16, 10
+    K = r.normal(size=(n, d)).astype(np.float32)
+    v = r.normal(size=d).astype(np.float32)
+    o = OracleStream(d, 0.0, s=s, w=w)       # delta = 0: den is exact
+    o.ingest(K, np.tile(v, (n, 1)))
+    q = (r.normal(size=d) * 0.3).astype(np.float32)
+    out = o.attend(q)
+    K64, q64 = K.astype(np.float64), q.astype(np.float64)
+    sampled = K64[o.sample_idx]
+    numer = np.exp(K64[n - w:] @ q64).sum() + (n - w) / s * np.exp(sampled @ q64).sum()
+    Z = np.exp(K64 @ q64).sum()
+    assert np.allclose(out, v.astype(np.float64) * numer / Z, rtol=1e-11)
+
+
+def test_estimator_is_unbiased_with_delta_zero():
+    # Lemma 1 + row-norm sampling: E[z] = exp(K q)^T V; with delta = 0 tau is exact, so the
+    # mean of the output over seeds converges to exact attention at rate 1/sqrt(seeds)
+    r = rng(9)
+    n, d, s, w = 60, 4, 8, 4
+    K = r.normal(size=(n, d)).astype(np.float32)
+    V = (r.normal(size=(n, d)) * r.uniform(0.5, 1.5, size=(n, 1))).astype(np.float32)
+    q = (r.normal(size=d) * 0.5).astype(np.float32)
+    exact = exact_attention(K, V, q)
+    seeds = 4000
+    outs = np.empty((seeds, d))
+    for seed in range(seeds):
+        o = OracleStream(d, 0.0, s=s, w=w, seed=seed)
+        o.ingest(K, V)
+        outs[seed] = o.attend(q)
+    mean, sem = outs.mean(0), outs.std(0) / math.sqrt(seeds)
+    assert (np.abs(mean - exact) < 4.5 * sem).all()
+    # the single-seed error is not small (this is an estimator, not the exact value) ...
+    assert np.abs(outs[0] - exact).max() > 10 * sem.max()
+    # ... and averaging m seeds shrinks it like 1/sqrt(m)
+    e1 = np.linalg.norm(outs[:40].mean(0) - exact)
+    e2 = np.linalg.norm(mean - exact)
+    assert e2 < e1
+
+
+def test_numerator_error_shrinks_with_sample_budget():
+    # approximate matrix product: error ~ 1/sqrt(s) (Theorem 1 takes s = Omega(d / eps^2))
+    r = rng(11)
+    n, d = 400, 8
+    K = (r.normal(size=(n, d)) * 0.7).astype(np.float32)
+    V = r.normal(size=(n, d)).astype(np.float32)
+    q = (r.normal(size=d) * 0.5).astype(np.float32)
+    exact = exact_attention(K, V, q)
+    err = {}
+    for s in [16, 1024]:
+        es = []
+        for seed in range(24):
+            o = OracleStream(d, 0.0, s=s, w=0, seed=seed)
+            o.ingest(K, V)
+            es.append(np.linalg.norm(o.attend(q) - exact))
+        err[s] = np.mean(es)
+    assert 4.0 < err[16] / err[1024] < 16.0      # sqrt(64) = 8 expected
+
+
+def test_query_sees_the_token_of_its_own_step():
+    # main loop of Algorithm 1: update first, then query
+    r = rng(12)
+    d = 4
+    o = OracleStream(d, 0.0, s=4, w=2)
+    K, V = r.normal(size=(2, d)).astype(np.float32), r.normal(size=(2, d)).astype(np.float32)
+    o.update(K[0], V[0])
+    o.update(K[1], V[1])
+    q = r.normal(size=d).astype(np.float32)
+    assert np.allclose(o.attend(q), exact_attention(K, V, q), rtol=1e-13)
+
+
+def test_ingest_and_decode_are_loops_of_update_and_attend():
+    r = rng(13)
+    n, d = 90, 8
+    K, V = r.normal(size=(n, d)).astype(np.float32), r.normal(size=(n, d)).astype(np.float32)
+    Q = r.normal(size=(20, 2, d)).astype(np.float32)
+    a = OracleStream(d, 2.0, s=8, w=6, seed=5, stream=3)
+    b = OracleStream(d, 2.0, s=8, w=6, seed=5, stream=3)
+    a.ingest(K[:50], V[:50])
+    a.ingest(K[50:70], V[50:70])
+    outs = a.decode(K[70:], V[70:], Q)
+    ref = np.empty_like(outs)
+    for t in range(n):
+        b.update(K[t], V[t])
+        if t >= 70:
+            for h in range(2):
+                ref[t - 70, h] = b.attend(Q[t - 70, h])
+    assert np.array_equal(outs, ref)
+    assert np.array_equal(a.sample_idx, b.sample_idx) and np.array_equal(a.counts, b.counts)
+    # a different stream id draws different coins
+    c = OracleStream(d, 2.0, s=8, w=6, seed=5, stream=4)
+    c.ingest(K, V)
+    assert not np.array_equal(c.sample_idx, b.sample_idx)
+
+
+def test_exact_attention_against_library_softmax_and_uniform_case():
+    import torch
+    r = rng(14)
+    K, V, q = r.normal(size=(33, 5)), r.normal(size=(33, 5)), r.normal(size=5)
+    ref = torch.softmax(torch.from_numpy(K) @ torch.from_numpy(q), 0) @ torch.from_numpy(V)
+    assert np.allclose(exact_attention(K, V, q), ref.numpy(), rtol=1e-12)
+    assert np.allclose(exact_attention(np.zeros((7, 3)), V[:7, :3], q[:3]), V[:7, :3].mean(0), rtol=1e-13)
