@@ -1,0 +1,195 @@
+/*
+ * subgen.h — C ABI of the SubGen decode-step library for AMD MI355X (gfx950).
+ *
+ * SubGen (Zandieh, Han, Mirrokni, Karbasi: "SubGen: Token Generation in
+ * Sublinear Time and Memory") keeps, per attention stream, a compressed KV
+ * cache made of
+ *   D  — an online threshold clustering of the keys: representatives x_i and
+ *        counts n_i (Algorithm 1, procedure UpdateSoftmaxNormalizer; Lemma 2),
+ *   M  — s slots of (k, v) pairs sampled with probability proportional to
+ *        ||v||^2, and mu = sum ||v||^2 (procedure UpdateMatrixProduct; Lemma 1),
+ *   W  — the w most recent tokens, kept exactly (Section 3.2, sliding window),
+ * and answers a query q with z / tau (procedure QueryStreamAttn).
+ *
+ * A "stream" is one (sequence, layer, KV head).  All streams of a context
+ * advance in lock-step, one token per call.  Every entry point below runs on
+ * the GPU in hand-written HIP kernels; there is no host fallback.
+ *
+ * Conventions
+ *   - Pointers named K*, V*, Q*, out are DEVICE pointers owned by the caller,
+ *     16-byte aligned, valid until the work enqueued by the call has run
+ *     (calls are asynchronous on the context's HIP stream).  Host pointers
+ *     are marked "host".
+ *   - Element type (fp32 or bf16) is fixed per context; rows are stored as
+ *     verbatim copies of the inputs.
+ *   - No 1/sqrt(d) is applied: the paper's attention is softmax(K q) (Eq. 1);
+ *     callers pre-scale q.
+ *   - Every function returns SUBGEN_OK (0) or a negative error code; nothing
+ *     aborts, throws or prints.  A context is not thread-safe; distinct
+ *     contexts are independent.
+ *   - Semantics of the window: a token is held exactly while it is among the
+ *     last w; when it leaves the window it is clustered and offered to the
+ *     sampler.  So counts, samples and mu cover the tokens that left the
+ *     window ("evicted"), window tokens contribute exact terms, nothing is
+ *     counted twice:  sum_i n_i + |W| = tokens seen.
+ */
+#ifndef SUBGEN_H
+#define SUBGEN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct subgen_ctx subgen_ctx; /* opaque; owned by the library from create to destroy */
+
+enum {
+    SUBGEN_OK = 0,
+    SUBGEN_EINVAL = -1,    /* bad argument (null, misaligned, unsupported shape, non-finite delta) */
+    SUBGEN_ENOMEM = -2,    /* device or host allocation failed                                     */
+    SUBGEN_EHIP = -3,      /* a HIP call failed; see subgen_last_hip_error                         */
+    SUBGEN_EEMPTY = -4,    /* attend before any token                                              */
+    SUBGEN_ECAPACITY = -5  /* a per-context capacity would be exceeded (assignment log, sizes)     */
+};
+
+enum { SUBGEN_F32 = 0, SUBGEN_BF16 = 1 };
+
+/* bits of the sticky per-stream flag word (subgen_stats, subgen_export_state) */
+enum {
+    SUBGEN_FLAG_CENTER_OVERFLOW = 1u /* the center table was full: a token joined its nearest center regardless of delta */
+};
+
+/* Options of subgen_create.  Zero-initialise, set struct_size = sizeof(subgen_opts), then override. */
+typedef struct subgen_opts {
+    uint32_t struct_size;
+    int32_t dtype;          /* SUBGEN_F32 (default) or SUBGEN_BF16: element type of K, V, Q and stored rows */
+    int32_t q_per_stream;   /* g: queries answered per stream per attend (GQA group size); 0 -> 1; 1, 2 or 4 */
+    int32_t max_centers;    /* per-stream capacity of the center table; 0 -> 4096                          */
+    int64_t assign_log_tokens; /* if > 0: record the center index of the first this-many evicted tokens of every stream */
+    uint64_t seed;          /* key of the counter-based generator behind the sampling coin flips           */
+    void *hip_stream;       /* hipStream_t every call enqueues on; NULL = the default stream               */
+    int32_t device;         /* HIP device ordinal; -1 (or struct zeroed with device_set = 0) = current     */
+    int32_t device_set;     /* non-zero: use `device`                                                      */
+} subgen_opts;
+
+/*
+ * subgen_create — allocate the state of `streams` independent streams (Section 2.1: the data
+ * structure of the streaming attention problem; Algorithm 1, initialisation: mu = 0, D empty,
+ * M all null).
+ *   d              head dimension; row bytes (d * element size) must be 128, 256, 512 or 1024
+ *   delta          cluster threshold (Definition 1; Algorithm 1 joins iff ||k - x|| <= delta), >= 0
+ *   sample_budget  s >= 1, number of slots of M
+ *   window         w >= 0, recent tokens kept exactly (Section 3.2)
+ *   opts           may be NULL (all defaults)
+ * All device memory of the context is allocated here and released by subgen_destroy.
+ */
+int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int32_t sample_budget,
+                  int32_t window, const subgen_opts *opts);
+
+void subgen_destroy(subgen_ctx *ctx);
+
+/*
+ * subgen_update — one new token per stream (Algorithm 1, main loop: UpdateSoftmaxNormalizer,
+ * UpdateMatrixProduct, mu += ||v||^2, applied to the token the window pushes out).
+ *   K_t, V_t   device, [streams, d] contiguous, context dtype.
+ */
+int subgen_update(subgen_ctx *ctx, const void *K_t, const void *V_t);
+
+/*
+ * subgen_attend — QueryStreamAttn (Algorithm 1) plus the exact window terms:
+ *   den = sum_{j in W} e^{<q,k_j>} + sum_i n_i e^{<q,x_i>}
+ *   num = sum_{j in W} e^{<q,k_j>} v_j + sum_{j in M} mu / (s ||v_j||^2) e^{<q,k_j>} v_j
+ *   out = num / den      (a common maximum is subtracted from every exponent; fp32 accumulation)
+ *   Q_t   device, [streams, g, d] contiguous, context dtype
+ *   out   device, [streams, g, d] contiguous, fp32, fully overwritten
+ * Returns SUBGEN_EEMPTY if no token has been given yet.
+ */
+int subgen_attend(subgen_ctx *ctx, const void *Q_t, void *out);
+
+/*
+ * subgen_step — one decode step of Algorithm 1 (update with (K_t, V_t), then query with Q_t) in a
+ * single pass over the center table.  State and output equal subgen_update followed by subgen_attend.
+ */
+int subgen_step(subgen_ctx *ctx, const void *K_t, const void *V_t, const void *Q_t, void *out);
+
+/*
+ * subgen_ingest_prefix — stream n prompt tokens per stream through the update (the paper counts
+ * prompt and generated tokens alike, Section 1.2); equals n calls of subgen_update in order, and
+ * may be called repeatedly with consecutive chunks.
+ *   K, V            device; token t of stream j starts at element j*stream_stride + t*token_stride
+ *   stream_stride, token_stride   in elements; rows must stay 16-byte aligned; token_stride >= d
+ */
+int subgen_ingest_prefix(subgen_ctx *ctx, const void *K, const void *V, int64_t n, int64_t stream_stride,
+                         int64_t token_stride);
+
+/*
+ * subgen_exact_attend — exact full-KV decode attention softmax(K q)^T V (Eq. 1), for context
+ * numbers beside the compressed path.  Independent of any context.
+ *   K, V       device, [streams, n, d] contiguous, `dtype`
+ *   Q          device, [streams, g, d]; out device [streams, g, d] fp32
+ *   workspace  device scratch of at least subgen_exact_workspace_bytes(streams, n, d, g) bytes
+ *   hip_stream hipStream_t or NULL
+ */
+size_t subgen_exact_workspace_bytes(int64_t streams, int64_t n, int32_t d, int32_t g);
+int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, int64_t streams, int64_t n,
+                        int32_t d, int32_t g, int32_t dtype, void *workspace, size_t workspace_bytes,
+                        void *hip_stream);
+
+/* Aggregate counters; synchronises the context's stream. */
+typedef struct subgen_stats_t {
+    uint32_t struct_size;
+    uint32_t flags_or;        /* OR of all streams' sticky flag words           */
+    int64_t streams;
+    int64_t n_seen;           /* tokens given so far (same for every stream)    */
+    int64_t n_evicted;        /* tokens that left the window, per stream        */
+    int64_t total_centers;    /* sum over streams of m                          */
+    int32_t min_centers, max_centers;
+    int64_t flagged_streams;  /* streams with a non-zero flag word              */
+} subgen_stats_t;
+
+int subgen_stats(subgen_ctx *ctx, subgen_stats_t *host_out);
+
+/* Per-stream number of centers; host_m is a host array of `streams` int32.  Synchronises. */
+int subgen_center_counts(subgen_ctx *ctx, int32_t *host_m);
+
+/*
+ * subgen_export_state — copy one stream's state to host buffers (parity checks, checkpointing).
+ * Scalars are always filled.  Each buffer pointer may be NULL (skipped); otherwise it must hold
+ * the stated number of entries.  Rows are in the context dtype.  Synchronises.
+ */
+typedef struct subgen_state_view {
+    uint32_t struct_size;
+    uint32_t flags;           /* out: sticky flag word of the stream                      */
+    int32_t m;                /* out: number of centers                                   */
+    int32_t window_fill;      /* out: min(n_seen, w)                                      */
+    int64_t n_seen;           /* out                                                      */
+    int64_t n_evicted;        /* out                                                      */
+    double mu;                /* out: sum of ||v||^2 over evicted tokens                  */
+    int64_t centers_cap;      /* in: rows the two arrays below can hold (>= m else EINVAL) */
+    void *centers;            /* host [centers_cap, d]                                    */
+    int32_t *counts;          /* host [centers_cap]                                       */
+    void *sample_K, *sample_V;/* host [s, d]                                              */
+    int32_t *sample_idx;      /* host [s]: token index held by each slot, -1 = null       */
+    float *sample_vn;         /* host [s]: ||v||^2 of that token                          */
+    void *window_K, *window_V;/* host [w, d], ring order: slot = token index mod w        */
+    int64_t assign_cap;       /* in: entries assign can hold                              */
+    int32_t *assign;          /* host: center index of evicted token 0.. (needs assign_log_tokens > 0) */
+    int64_t assign_len;       /* out: entries written                                     */
+} subgen_state_view;
+
+int subgen_export_state(subgen_ctx *ctx, int64_t stream, subgen_state_view *host_view);
+
+/* Block until everything enqueued on the context's stream has run. */
+int subgen_sync(subgen_ctx *ctx);
+
+const char *subgen_strerror(int code);
+
+/* hipError_t of the last failing HIP call on this context (0 if none). */
+int subgen_last_hip_error(const subgen_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SUBGEN_H */

@@ -1,0 +1,127 @@
+// Exact full-KV decode attention softmax(K q)^T V (Eq. 1 of the paper) for
+// gfx950: split over the sequence, online softmax in fp32, partials combined
+// by a second kernel.  Same row mapping as the compressed path: LPR lanes read
+// one row with a 16-byte load each.
+#pragma once
+#include "subgen_device.hpp"
+
+namespace sg {
+
+struct ExactCall {
+    const char *K, *V;   // [S][n][d]
+    const char *Q;       // [S][G][d]
+    float *out;          // [S][G][d]
+    float *ws;           // [S][splits][G][d + 2]
+    int64_t n;
+    int32_t splits;
+};
+
+template <bool BF16, int LPR, int G>
+__global__ __launch_bounds__(kWG) void exact_partial_kernel(const ExactCall c)
+{
+    constexpr int VEC = BF16 ? 8 : 4;
+    constexpr int RPW = 64 / LPR, RPB = RPW * kWaves;
+    constexpr size_t ROWB = (size_t)LPR * 16;
+    constexpr int D = LPR * VEC;
+    __shared__ float wmx[kWaves][G], wden[kWaves][G], wacc[kWaves][G][D];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane % LPR, sub = lane / LPR;
+    const size_t sid = blockIdx.y;
+    const int split = blockIdx.x;
+    const int64_t per = (c.n + c.splits - 1) / c.splits;
+    const int64_t t0 = split * per, t1 = (t0 + per < c.n) ? t0 + per : c.n;
+    const char *K = c.K + sid * (size_t)c.n * ROWB;
+    const char *V = c.V + sid * (size_t)c.n * ROWB;
+
+    float q[G][VEC];
+#pragma unroll
+    for (int g = 0; g < G; ++g) unpack<BF16>(ld16(c.Q + (sid * G + g) * ROWB + col * 16), q[g]);
+    Partial<VEC> part[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) part[g].init();
+
+    for (int64_t r0 = t0 + wave * RPW; r0 < t1; r0 += RPB) {
+        const int64_t r = r0 + sub;
+        const bool valid = r < t1;
+        const int64_t rr = valid ? r : t1 - 1;
+        float kx[VEC], vx[VEC];
+        unpack<BF16>(ld16(K + (size_t)rr * ROWB + col * 16), kx);
+        unpack<BF16>(ld16(V + (size_t)rr * ROWB + col * 16), vx);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float a = 0.f;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) a = fmaf(q[g][v], kx[v], a);
+            const float b = group_sum<LPR>(a);
+            if (valid) {
+                part[g].raise(b);
+                const float e = __expf(b - part[g].mx);
+                part[g].den += e;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) part[g].acc[v] = fmaf(e, vx[v], part[g].acc[v]);
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) {
+            const float omx = __shfl_xor(part[g].mx, o);
+            const float oden = __shfl_xor(part[g].den, o);
+            float oacc[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) oacc[v] = __shfl_xor(part[g].acc[v], o);
+            part[g].merge(omx, oden, oacc);
+        }
+        if (sub == 0) {
+            if (col == 0) {
+                wmx[wave][g] = part[g].mx;
+                wden[wave][g] = part[g].den;
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) wacc[wave][g][col * VEC + v] = part[g].acc[v];
+        }
+    }
+    __syncthreads();
+    float *ws = c.ws + (sid * c.splits + split) * (size_t)G * (D + 2);
+    for (int i = tid; i < G * (D + 2); i += kWG) {
+        const int g = i / (D + 2), e = i % (D + 2);
+        float M = wmx[0][g];
+#pragma unroll
+        for (int wv = 1; wv < kWaves; ++wv) M = fmaxf(M, wmx[wv][g]);
+        float val = 0.f;
+        if (e == D) {
+            val = M;
+        } else {
+#pragma unroll
+            for (int wv = 0; wv < kWaves; ++wv) {
+                const float wm = wmx[wv][g];
+                const float sc = (wm == -INFINITY) ? 0.f : __expf(wm - M);
+                val = fmaf(e == D + 1 ? wden[wv][g] : wacc[wv][g][e], sc, val);
+            }
+        }
+        ws[(size_t)g * (D + 2) + e] = val;
+    }
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(kWG) void exact_combine_kernel(const ExactCall c)
+{
+    const size_t sid = blockIdx.x;
+    const float *ws = c.ws + sid * c.splits * (size_t)G * (D + 2);
+    for (int i = threadIdx.x; i < G * D; i += kWG) {
+        const int g = i / D, e = i % D;
+        float M = -INFINITY;
+        for (int sp = 0; sp < c.splits; ++sp) M = fmaxf(M, ws[((size_t)sp * G + g) * (D + 2) + D]);
+        float num = 0.f, den = 0.f;
+        for (int sp = 0; sp < c.splits; ++sp) {
+            const float *p = ws + ((size_t)sp * G + g) * (D + 2);
+            const float sc = (p[D] == -INFINITY) ? 0.f : __expf(p[D] - M);
+            num = fmaf(p[e], sc, num);
+            den = fmaf(p[D + 1], sc, den);
+        }
+        c.out[(sid * G + g) * D + e] = num / den;
+    }
+}
+
+}  // namespace sg

@@ -1,0 +1,438 @@
+// Host side of the SubGen C ABI (see include/subgen.h): argument checks, state
+// allocation in HBM, kernel dispatch.  No arithmetic of the method runs here.
+#include "../../include/subgen.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "exact_device.hpp"
+#include "subgen_device.hpp"
+
+using sg::Call;
+using sg::State;
+
+struct subgen_ctx {
+    State st{};
+    int64_t S = 0;
+    int32_t d = 0, s = 0, w = 0, Mcap = 0, G = 1;
+    int32_t dtype = SUBGEN_F32;
+    int32_t esz = 4;       // element bytes
+    int32_t LPR = 0;       // lanes per row = row bytes / 16
+    float delta = 0.f;
+    int64_t n_seen = 0;
+    hipStream_t stream = nullptr;
+    int device = 0;
+    int last_hip = 0;
+    std::vector<void *> allocs;
+};
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) == hipSuccess && prev != dev) switched = hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard()
+    {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+int fail_hip(subgen_ctx *c, hipError_t e)
+{
+    if (c) c->last_hip = (int)e;
+    return e == hipErrorOutOfMemory ? SUBGEN_ENOMEM : SUBGEN_EHIP;
+}
+
+template <typename T>
+int dev_alloc(subgen_ctx *c, T **p, size_t count, int fill_byte)
+{
+    void *q = nullptr;
+    const size_t bytes = (count ? count : 1) * sizeof(T);
+    hipError_t e = hipMalloc(&q, bytes);
+    if (e != hipSuccess) return fail_hip(c, e);
+    c->allocs.push_back(q);
+    e = hipMemsetAsync(q, fill_byte, bytes, c->stream);
+    if (e != hipSuccess) return fail_hip(c, e);
+    *p = reinterpret_cast<T *>(q);
+    return SUBGEN_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+enum Mode { MODE_UPDATE, MODE_ATTEND, MODE_STEP };
+
+template <bool BF16, int LPR, int G>
+void launch_mode(Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    switch (mode) {
+        case MODE_UPDATE:
+            hipLaunchKernelGGL((sg::decode_kernel<BF16, LPR, 1, true, false>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+        case MODE_ATTEND:
+            hipLaunchKernelGGL((sg::decode_kernel<BF16, LPR, G, false, true>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+        case MODE_STEP:
+            hipLaunchKernelGGL((sg::decode_kernel<BF16, LPR, G, true, true>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+    }
+}
+
+template <bool BF16, int LPR>
+void launch_g(int G, Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    if (G == 1) launch_mode<BF16, LPR, 1>(mode, grid, s, st, call);
+    else if (G == 2) launch_mode<BF16, LPR, 2>(mode, grid, s, st, call);
+    else launch_mode<BF16, LPR, 4>(mode, grid, s, st, call);
+}
+
+template <bool BF16>
+void launch_lpr(int LPR, int G, Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    if (LPR == 8) launch_g<BF16, 8>(G, mode, grid, s, st, call);
+    else if (LPR == 16) launch_g<BF16, 16>(G, mode, grid, s, st, call);
+    else launch_g<BF16, 32>(G, mode, grid, s, st, call);
+}
+
+int launch_decode(subgen_ctx *c, Mode mode, const Call &call)
+{
+    const dim3 grid((unsigned)c->S);
+    if (c->dtype == SUBGEN_BF16) launch_lpr<true>(c->LPR, c->G, mode, grid, c->stream, c->st, call);
+    else launch_lpr<false>(c->LPR, c->G, mode, grid, c->stream, c->st, call);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+}
+
+template <bool BF16>
+void launch_ingest_lpr(int LPR, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    if (LPR == 8) hipLaunchKernelGGL((sg::ingest_kernel<BF16, 8>), grid, dim3(sg::kWG), 0, s, st, call);
+    else if (LPR == 16) hipLaunchKernelGGL((sg::ingest_kernel<BF16, 16>), grid, dim3(sg::kWG), 0, s, st, call);
+    else hipLaunchKernelGGL((sg::ingest_kernel<BF16, 32>), grid, dim3(sg::kWG), 0, s, st, call);
+}
+
+bool row_bytes_ok(int64_t rb) { return rb == 128 || rb == 256 || rb == 512; }
+
+int exact_splits(int64_t streams, int64_t n)
+{
+    int64_t want = (4096 + streams - 1) / streams;          // aim for >= 4096 workgroups
+    int64_t most = (n + 255) / 256;                          // at least 256 rows per split
+    if (want > most) want = most;
+    if (want < 1) want = 1;
+    if (want > 1024) want = 1024;
+    return (int)want;
+}
+
+template <bool BF16, int LPR, int G>
+void launch_exact(const sg::ExactCall &c, int64_t streams, hipStream_t s)
+{
+    constexpr int D = LPR * (BF16 ? 8 : 4);
+    hipLaunchKernelGGL((sg::exact_partial_kernel<BF16, LPR, G>), dim3(c.splits, (unsigned)streams), dim3(sg::kWG), 0,
+                       s, c);
+    hipLaunchKernelGGL((sg::exact_combine_kernel<D, G>), dim3((unsigned)streams), dim3(sg::kWG), 0, s, c);
+}
+
+template <bool BF16, int LPR>
+void launch_exact_g(int g, const sg::ExactCall &c, int64_t streams, hipStream_t s)
+{
+    if (g == 1) launch_exact<BF16, LPR, 1>(c, streams, s);
+    else if (g == 2) launch_exact<BF16, LPR, 2>(c, streams, s);
+    else launch_exact<BF16, LPR, 4>(c, streams, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int32_t sample_budget,
+                  int32_t window, const subgen_opts *opts)
+{
+    if (!out) return SUBGEN_EINVAL;
+    *out = nullptr;
+    subgen_opts o;
+    std::memset(&o, 0, sizeof(o));
+    if (opts) {
+        if (opts->struct_size < sizeof(uint32_t) || opts->struct_size > sizeof(subgen_opts)) return SUBGEN_EINVAL;
+        std::memcpy(&o, opts, opts->struct_size);
+    }
+    const int32_t G = o.q_per_stream == 0 ? 1 : o.q_per_stream;
+    const int32_t Mcap = o.max_centers == 0 ? 4096 : o.max_centers;
+    if (o.dtype != SUBGEN_F32 && o.dtype != SUBGEN_BF16) return SUBGEN_EINVAL;
+    const int32_t esz = o.dtype == SUBGEN_BF16 ? 2 : 4;
+    if (streams < 1 || streams > 0x7fffffffLL || d < 1 || !row_bytes_ok((int64_t)d * esz)) return SUBGEN_EINVAL;
+    if (!(delta >= 0.f) || !std::isfinite(delta)) return SUBGEN_EINVAL;
+    if (sample_budget < 1 || sample_budget > (1 << 20) || window < 0 || window > (1 << 20)) return SUBGEN_EINVAL;
+    if (G != 1 && G != 2 && G != 4) return SUBGEN_EINVAL;
+    if (Mcap < 1 || Mcap > (1 << 24) || o.assign_log_tokens < 0) return SUBGEN_EINVAL;
+
+    subgen_ctx *c = new (std::nothrow) subgen_ctx();
+    if (!c) return SUBGEN_ENOMEM;
+    hipError_t e;
+    if (o.device_set) {
+        c->device = o.device;
+    } else if ((e = hipGetDevice(&c->device)) != hipSuccess) {
+        delete c;
+        return SUBGEN_EHIP;
+    }
+    DeviceGuard guard(c->device);
+    c->S = streams; c->d = d; c->s = sample_budget; c->w = window; c->Mcap = Mcap; c->G = G;
+    c->dtype = o.dtype; c->esz = esz; c->LPR = d * esz / 16; c->delta = delta;
+    c->stream = reinterpret_cast<hipStream_t>(o.hip_stream);
+
+    State &st = c->st;
+    st.Mcap = Mcap; st.s = sample_budget; st.w = window; st.d = d;
+    st.delta2 = (double)delta * (double)delta;
+    st.seed_lo = (uint32_t)o.seed; st.seed_hi = (uint32_t)(o.seed >> 32);
+    st.assign_cap = o.assign_log_tokens;
+    const size_t S = (size_t)streams, rowb = (size_t)d * esz;
+    int rc = SUBGEN_OK;
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.X, S * Mcap * rowb, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.cnt, S * Mcap, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.m, S, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Ks, S * sample_budget * rowb, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Vs, S * sample_budget * rowb, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.sidx, S * sample_budget, 0xFF);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.svn, S * sample_budget, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Kw, S * window * rowb, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Vw, S * window * rowb, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.mu, S, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.flags, S, 0);
+    if (rc == SUBGEN_OK && st.assign_cap > 0) rc = dev_alloc(c, &st.assign, S * (size_t)st.assign_cap, 0xFF);
+    if (rc != SUBGEN_OK) {
+        subgen_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return SUBGEN_OK;
+}
+
+void subgen_destroy(subgen_ctx *c)
+{
+    if (!c) return;
+    DeviceGuard guard(c->device);
+    (void)hipStreamSynchronize(c->stream);
+    for (void *p : c->allocs) (void)hipFree(p);
+    delete c;
+}
+
+int subgen_update(subgen_ctx *c, const void *K_t, const void *V_t)
+{
+    if (!c || !K_t || !V_t || !aligned16(K_t) || !aligned16(V_t)) return SUBGEN_EINVAL;
+    DeviceGuard guard(c->device);
+    Call call{};
+    call.K = (const char *)K_t; call.V = (const char *)V_t;
+    call.stream_stride = (int64_t)c->d * c->esz; call.token_stride = call.stream_stride;
+    call.n_tokens = 1; call.n_seen = c->n_seen;
+    const int rc = launch_decode(c, MODE_UPDATE, call);
+    if (rc == SUBGEN_OK) c->n_seen += 1;
+    return rc;
+}
+
+int subgen_attend(subgen_ctx *c, const void *Q_t, void *out)
+{
+    if (!c || !Q_t || !out || !aligned16(Q_t) || !aligned16(out)) return SUBGEN_EINVAL;
+    if (c->n_seen == 0) return SUBGEN_EEMPTY;
+    DeviceGuard guard(c->device);
+    Call call{};
+    call.Q = (const char *)Q_t; call.out = (float *)out; call.n_seen = c->n_seen;
+    return launch_decode(c, MODE_ATTEND, call);
+}
+
+int subgen_step(subgen_ctx *c, const void *K_t, const void *V_t, const void *Q_t, void *out)
+{
+    if (!c || !K_t || !V_t || !Q_t || !out) return SUBGEN_EINVAL;
+    if (!aligned16(K_t) || !aligned16(V_t) || !aligned16(Q_t) || !aligned16(out)) return SUBGEN_EINVAL;
+    DeviceGuard guard(c->device);
+    Call call{};
+    call.K = (const char *)K_t; call.V = (const char *)V_t;
+    call.stream_stride = (int64_t)c->d * c->esz; call.token_stride = call.stream_stride;
+    call.n_tokens = 1; call.Q = (const char *)Q_t; call.out = (float *)out; call.n_seen = c->n_seen;
+    const int rc = launch_decode(c, MODE_STEP, call);
+    if (rc == SUBGEN_OK) c->n_seen += 1;
+    return rc;
+}
+
+int subgen_ingest_prefix(subgen_ctx *c, const void *K, const void *V, int64_t n, int64_t stream_stride,
+                         int64_t token_stride)
+{
+    if (!c || n < 0) return SUBGEN_EINVAL;
+    if (n == 0) return SUBGEN_OK;
+    if (!K || !V || !aligned16(K) || !aligned16(V)) return SUBGEN_EINVAL;
+    if (token_stride < c->d || stream_stride < 0) return SUBGEN_EINVAL;
+    if ((token_stride * c->esz) % 16 != 0 || (stream_stride * c->esz) % 16 != 0) return SUBGEN_EINVAL;
+    if (c->S > 1 && stream_stride < c->d) return SUBGEN_EINVAL;
+    DeviceGuard guard(c->device);
+    // bounded launches: a kernel walks at most kChunk tokens of every stream
+    constexpr int64_t kChunk = 2048;
+    for (int64_t t0 = 0; t0 < n; t0 += kChunk) {
+        Call call{};
+        call.stream_stride = stream_stride * c->esz; call.token_stride = token_stride * c->esz;
+        call.K = (const char *)K + t0 * call.token_stride; call.V = (const char *)V + t0 * call.token_stride;
+        call.n_tokens = (n - t0 < kChunk) ? n - t0 : kChunk;
+        call.n_seen = c->n_seen;
+        const dim3 grid((unsigned)c->S);
+        if (c->dtype == SUBGEN_BF16) launch_ingest_lpr<true>(c->LPR, grid, c->stream, c->st, call);
+        else launch_ingest_lpr<false>(c->LPR, grid, c->stream, c->st, call);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail_hip(c, e);
+        c->n_seen += call.n_tokens;
+    }
+    return SUBGEN_OK;
+}
+
+/* ------------------------------------------------------------------ exact attention */
+
+size_t subgen_exact_workspace_bytes(int64_t streams, int64_t n, int32_t d, int32_t g)
+{
+    if (streams < 1 || n < 1 || d < 1 || g < 1) return 0;
+    return (size_t)streams * exact_splits(streams, n) * g * (d + 2) * sizeof(float);
+}
+
+int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, int64_t streams, int64_t n,
+                        int32_t d, int32_t g, int32_t dtype, void *workspace, size_t workspace_bytes,
+                        void *hip_stream)
+{
+    if (!K || !V || !Q || !out || !workspace) return SUBGEN_EINVAL;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(Q) || !aligned16(out) || !aligned16(workspace))
+        return SUBGEN_EINVAL;
+    if (dtype != SUBGEN_F32 && dtype != SUBGEN_BF16) return SUBGEN_EINVAL;
+    const int esz = dtype == SUBGEN_BF16 ? 2 : 4;
+    if (streams < 1 || streams > 65535 * 64LL || n < 1 || d < 1 || !row_bytes_ok((int64_t)d * esz))
+        return SUBGEN_EINVAL;
+    if (g != 1 && g != 2 && g != 4) return SUBGEN_EINVAL;
+    if (workspace_bytes < subgen_exact_workspace_bytes(streams, n, d, g)) return SUBGEN_ECAPACITY;
+    sg::ExactCall c{};
+    c.K = (const char *)K; c.V = (const char *)V; c.Q = (const char *)Q; c.out = (float *)out;
+    c.ws = (float *)workspace; c.n = n; c.splits = exact_splits(streams, n);
+    hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+    const int LPR = d * esz / 16;
+    if (dtype == SUBGEN_BF16) {
+        if (LPR == 8) launch_exact_g<true, 8>(g, c, streams, s);
+        else if (LPR == 16) launch_exact_g<true, 16>(g, c, streams, s);
+        else launch_exact_g<true, 32>(g, c, streams, s);
+    } else {
+        if (LPR == 8) launch_exact_g<false, 8>(g, c, streams, s);
+        else if (LPR == 16) launch_exact_g<false, 16>(g, c, streams, s);
+        else launch_exact_g<false, 32>(g, c, streams, s);
+    }
+    return hipGetLastError() == hipSuccess ? SUBGEN_OK : SUBGEN_EHIP;
+}
+
+/* ------------------------------------------------------------------ introspection */
+
+int subgen_sync(subgen_ctx *c)
+{
+    if (!c) return SUBGEN_EINVAL;
+    DeviceGuard guard(c->device);
+    const hipError_t e = hipStreamSynchronize(c->stream);
+    return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+}
+
+static int64_t evicted(const subgen_ctx *c)
+{
+    if (c->w == 0) return c->n_seen;
+    return c->n_seen > c->w ? c->n_seen - c->w : 0;
+}
+
+int subgen_center_counts(subgen_ctx *c, int32_t *host_m)
+{
+    if (!c || !host_m) return SUBGEN_EINVAL;
+    DeviceGuard guard(c->device);
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e == hipSuccess) e = hipMemcpy(host_m, c->st.m, (size_t)c->S * sizeof(int32_t), hipMemcpyDeviceToHost);
+    return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+}
+
+int subgen_stats(subgen_ctx *c, subgen_stats_t *o)
+{
+    if (!c || !o) return SUBGEN_EINVAL;
+    std::vector<int32_t> m((size_t)c->S);
+    std::vector<uint32_t> fl((size_t)c->S);
+    int rc = subgen_center_counts(c, m.data());
+    if (rc != SUBGEN_OK) return rc;
+    DeviceGuard guard(c->device);
+    const hipError_t e = hipMemcpy(fl.data(), c->st.flags, (size_t)c->S * sizeof(uint32_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(c, e);
+    std::memset(o, 0, sizeof(*o));
+    o->struct_size = sizeof(*o);
+    o->streams = c->S; o->n_seen = c->n_seen; o->n_evicted = evicted(c);
+    o->min_centers = m[0]; o->max_centers = m[0];
+    for (int64_t i = 0; i < c->S; ++i) {
+        o->total_centers += m[i];
+        if (m[i] < o->min_centers) o->min_centers = m[i];
+        if (m[i] > o->max_centers) o->max_centers = m[i];
+        o->flags_or |= fl[i];
+        if (fl[i]) o->flagged_streams += 1;
+    }
+    return SUBGEN_OK;
+}
+
+int subgen_export_state(subgen_ctx *c, int64_t stream, subgen_state_view *v)
+{
+    if (!c || !v || stream < 0 || stream >= c->S) return SUBGEN_EINVAL;
+    if (v->struct_size != sizeof(subgen_state_view)) return SUBGEN_EINVAL;
+    DeviceGuard guard(c->device);
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return fail_hip(c, e);
+    const State &st = c->st;
+    const size_t sid = (size_t)stream, rowb = (size_t)c->d * c->esz;
+#define SG_D2H(dst, src, bytes)                                                       \
+    do {                                                                              \
+        if ((dst) != nullptr && (bytes) > 0) {                                        \
+            e = hipMemcpy((dst), (src), (bytes), hipMemcpyDeviceToHost);              \
+            if (e != hipSuccess) return fail_hip(c, e);                               \
+        }                                                                             \
+    } while (0)
+    int32_t m = 0;
+    SG_D2H(&m, st.m + sid, sizeof(int32_t));
+    SG_D2H(&v->mu, st.mu + sid, sizeof(double));
+    SG_D2H(&v->flags, st.flags + sid, sizeof(uint32_t));
+    v->m = m;
+    v->n_seen = c->n_seen;
+    v->n_evicted = evicted(c);
+    v->window_fill = (int32_t)(c->n_seen < c->w ? c->n_seen : c->w);
+    if ((v->centers || v->counts) && v->centers_cap < m) return SUBGEN_EINVAL;
+    SG_D2H(v->centers, st.X + sid * c->Mcap * rowb, (size_t)m * rowb);
+    SG_D2H(v->counts, st.cnt + sid * c->Mcap, (size_t)m * sizeof(int32_t));
+    SG_D2H(v->sample_K, st.Ks + sid * c->s * rowb, (size_t)c->s * rowb);
+    SG_D2H(v->sample_V, st.Vs + sid * c->s * rowb, (size_t)c->s * rowb);
+    SG_D2H(v->sample_idx, st.sidx + sid * c->s, (size_t)c->s * sizeof(int32_t));
+    SG_D2H(v->sample_vn, st.svn + sid * c->s, (size_t)c->s * sizeof(float));
+    SG_D2H(v->window_K, st.Kw + sid * c->w * rowb, (size_t)c->w * rowb);
+    SG_D2H(v->window_V, st.Vw + sid * c->w * rowb, (size_t)c->w * rowb);
+    v->assign_len = 0;
+    if (v->assign != nullptr) {
+        if (st.assign == nullptr) return SUBGEN_EINVAL;
+        int64_t len = v->n_evicted < st.assign_cap ? v->n_evicted : st.assign_cap;
+        if (len > v->assign_cap) len = v->assign_cap;
+        SG_D2H(v->assign, st.assign + sid * (size_t)st.assign_cap, (size_t)len * sizeof(int32_t));
+        v->assign_len = len;
+    }
+#undef SG_D2H
+    return SUBGEN_OK;
+}
+
+const char *subgen_strerror(int code)
+{
+    switch (code) {
+        case SUBGEN_OK: return "ok";
+        case SUBGEN_EINVAL: return "invalid argument";
+        case SUBGEN_ENOMEM: return "out of memory";
+        case SUBGEN_EHIP: return "HIP runtime error";
+        case SUBGEN_EEMPTY: return "attend before any token";
+        case SUBGEN_ECAPACITY: return "capacity exceeded";
+        default: return "unknown error";
+    }
+}
+
+int subgen_last_hip_error(const subgen_ctx *c) { return c ? c->last_hip : 0; }
+
+}  // extern "C"

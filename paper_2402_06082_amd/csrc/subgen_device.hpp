@@ -1,0 +1,534 @@
+// Device code of the SubGen decode step for gfx950 (wave64).
+//
+// One workgroup of 256 lanes (4 wavefronts) owns one stream for the whole
+// kernel, so no two workgroups ever touch the same state.  Rows (centers,
+// sampled keys/values, window keys/values) are d contiguous elements; a row is
+// read by LPR consecutive lanes with one 16-byte load each, so one wavefront
+// load instruction fetches 64/LPR complete rows, fully coalesced.  Dot
+// products and squared distances are reduced across the LPR lanes of a row
+// group with cross-lane shuffles.  The softmax is kept online (running
+// maximum, denominator, fp32 accumulator) per row group and merged at the end.
+//
+// Decisions that produce integers (nearest center, threshold test, sampling
+// coin flips) are taken in double precision from the exactly converted
+// inputs, so they do not depend on the summation order beyond the last bits
+// of a double.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sg {
+
+constexpr int kWG = 256;
+constexpr int kWaves = 4;
+constexpr int kQueue = 1024;  // sample slots handled per round of the sampling update
+
+// Pointers into the context's structure-of-arrays state (all device memory).
+struct State {
+    char *X;            // [S][Mcap][d]   cluster representatives x_i
+    int32_t *cnt;       // [S][Mcap]      cluster sizes n_i
+    int32_t *m;         // [S]            number of clusters
+    char *Ks, *Vs;      // [S][s][d]      sampled pairs M
+    int32_t *sidx;      // [S][s]         token index held by each slot (-1 = null)
+    float *svn;         // [S][s]         ||v||^2 of that token
+    char *Kw, *Vw;      // [S][w][d]      window ring, slot = token index mod w
+    double *mu;         // [S]            sum of ||v||^2 over evicted tokens
+    uint32_t *flags;    // [S]            sticky flag word
+    int32_t *assign;    // [S][assign_cap] or null
+    int64_t assign_cap;
+    int32_t Mcap, s, w, d;
+    double delta2;      // delta^2
+    uint32_t seed_lo, seed_hi;
+};
+
+struct Call {
+    const char *K, *V;        // new tokens; token t of stream j at K + j*stream_stride + t*token_stride (bytes)
+    int64_t stream_stride, token_stride;
+    int64_t n_tokens;         // tokens per stream in this call (1 for update / step)
+    const char *Q;            // [S][G][d] or null
+    float *out;               // [S][G][d] fp32 or null
+    int64_t n_seen;           // tokens seen by every stream before this call
+};
+
+// ---------------------------------------------------------------------------
+// Philox-4x32, 10 rounds (Salmon et al., SC'11), written from the published
+// description.  Counter (slot block, token lo, token hi, stream), key = seed.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                               uint32_t k1, uint32_t (&r)[4])
+{
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+        const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+        c0 = h1 ^ c1 ^ k0;
+        c1 = l1;
+        c2 = h0 ^ c3 ^ k1;
+        c3 = l0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    r[0] = c0; r[1] = c1; r[2] = c2; r[3] = c3;
+}
+
+// ---------------------------------------------------------------------------
+// 16-byte row chunks
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint4 ld16(const char *p) { return *reinterpret_cast<const uint4 *>(p); }
+__device__ __forceinline__ void st16(char *p, uint4 v) { *reinterpret_cast<uint4 *>(p) = v; }
+
+template <bool BF16>
+__device__ __forceinline__ void unpack(const uint4 &r, float *f)
+{
+    if constexpr (BF16) {
+        f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+        f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+        f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+        f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+    } else {
+        f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+        f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+    }
+}
+
+template <int LPR, typename T>
+__device__ __forceinline__ T group_sum(T v)
+{
+#pragma unroll
+    for (int o = 1; o < LPR; o <<= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// online-softmax partial of one row group for one query
+template <int VEC>
+struct Partial {
+    float mx, den;
+    float acc[VEC];
+    __device__ __forceinline__ void init()
+    {
+        mx = -INFINITY;
+        den = 0.f;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+    }
+    // bring the running maximum up to at least b
+    __device__ __forceinline__ void raise(float b)
+    {
+        if (b > mx) {
+            const float sc = __expf(mx - b);  // mx = -inf gives 0
+            den *= sc;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] *= sc;
+            mx = b;
+        }
+    }
+    __device__ __forceinline__ void merge(float omx, float oden, const float *oacc)
+    {
+        const float M = fmaxf(mx, omx);
+        const float a = (mx == -INFINITY) ? 0.f : __expf(mx - M);
+        const float b = (omx == -INFINITY) ? 0.f : __expf(omx - M);
+        den = den * a + oden * b;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] = acc[v] * a + oacc[v] * b;
+        mx = M;
+    }
+};
+
+template <int LPR, int G, int VEC>
+struct Smem {
+    double wbest[kWaves];
+    int widx[kWaves];
+    float wbsc[kWaves][G];
+    float wmx[kWaves][G], wden[kWaves][G];
+    float wacc[kWaves][G][LPR * VEC];
+    int qn;
+    int queue[kQueue];
+};
+
+// ---------------------------------------------------------------------------
+// One token of one stream: window push/evict, cluster update, sampling update
+// (UPD) and/or the attention estimate for G queries (ATT).  Called by every
+// lane of the workgroup with block-uniform arguments; m and mu are carried by
+// the caller (block-uniform) and written back by it.
+// ---------------------------------------------------------------------------
+template <bool BF16, int LPR, int G, bool UPD, bool ATT>
+__device__ __forceinline__ void token_step(const State &st, const size_t sid, const char *krow, const char *vrow,
+                                           const char *qrows, float *outrows, const int64_t n_seen, int &m,
+                                           double &mu, Smem<LPR, G, (BF16 ? 8 : 4)> &sm)
+{
+    constexpr int VEC = BF16 ? 8 : 4;
+    constexpr int RPW = 64 / LPR;        // rows per wavefront load
+    constexpr int RPB = RPW * kWaves;    // rows per workgroup iteration
+    constexpr size_t ROWB = (size_t)LPR * 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane % LPR, sub = lane / LPR;
+    const int grp = wave * RPW + sub;
+
+    char *const X = st.X + sid * (size_t)st.Mcap * ROWB;
+    int32_t *const cnt = st.cnt + sid * (size_t)st.Mcap;
+    char *const Ks = st.Ks + sid * (size_t)st.s * ROWB;
+    char *const Vs = st.Vs + sid * (size_t)st.s * ROWB;
+    char *const Kw = st.Kw + sid * (size_t)st.w * ROWB;
+    char *const Vw = st.Vw + sid * (size_t)st.w * ROWB;
+
+    // ---- window push; the token that leaves the window is the one that is compressed
+    bool evict = false;
+    int64_t etoken = 0;
+    uint4 ek = make_uint4(0, 0, 0, 0), ev = make_uint4(0, 0, 0, 0);
+    if constexpr (UPD) {
+        if (st.w == 0) {
+            evict = true;
+            etoken = n_seen;
+            ek = ld16(krow + col * 16);
+            ev = ld16(vrow + col * 16);
+        } else {
+            const int slot = (int)(n_seen % st.w);
+            char *kw = Kw + (size_t)slot * ROWB, *vw = Vw + (size_t)slot * ROWB;
+            if (n_seen >= st.w) {
+                evict = true;
+                etoken = n_seen - st.w;
+                ek = ld16(kw + col * 16);
+                ev = ld16(vw + col * 16);
+            }
+            __syncthreads();  // every lane holds the evicted row before the slot is overwritten
+            if (tid < LPR) {
+                st16(kw + tid * 16, ld16(krow + tid * 16));
+                st16(vw + tid * 16, ld16(vrow + tid * 16));
+            }
+        }
+    }
+    const int64_t n_after = UPD ? n_seen + 1 : n_seen;
+    const int64_t n_evicted_after = st.w == 0 ? n_after : (n_after > st.w ? n_after - st.w : 0);
+
+    float q[G][VEC];
+    if constexpr (ATT) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) unpack<BF16>(ld16(qrows + (size_t)g * ROWB + col * 16), q[g]);
+    }
+    double ekd[VEC];
+    float bnew[G];  // <q, evicted key>: score of the cluster this token would open
+    if constexpr (UPD) {
+        float ekf[VEC];
+        unpack<BF16>(ek, ekf);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) ekd[v] = (double)ekf[v];
+        if constexpr (ATT) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float a = 0.f;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) a = fmaf(q[g][v], ekf[v], a);
+                bnew[g] = group_sum<LPR>(a);
+            }
+        }
+    }
+
+    Partial<VEC> part[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) part[g].init();
+
+    // ---- one pass over the representatives: squared distance to the evicted key (double)
+    //      and count-weighted exp(<q, x_i>) for the softmax normaliser
+    double best = INFINITY;
+    int bidx = -1;
+    float bsc[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) bsc[g] = 0.f;
+
+    if ((UPD && evict) || ATT) {
+        for (int r0 = wave * RPW; r0 < m; r0 += RPB) {
+            const int r = r0 + sub;
+            const bool valid = r < m;
+            const int rr = valid ? r : m - 1;
+            float x[VEC];
+            unpack<BF16>(ld16(X + (size_t)rr * ROWB + col * 16), x);
+            double dist = 0.0;
+            if constexpr (UPD) {
+                if (evict) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) {
+                        const double df = (double)x[v] - ekd[v];
+                        dist = fma(df, df, dist);
+                    }
+                    dist = group_sum<LPR>(dist);
+                }
+            }
+            float b[G];
+            if constexpr (ATT) {
+                const float c = (float)cnt[rr];
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float a = 0.f;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) a = fmaf(q[g][v], x[v], a);
+                    b[g] = group_sum<LPR>(a);
+                    if (valid) {
+                        part[g].raise(b[g]);
+                        part[g].den += c * __expf(b[g] - part[g].mx);
+                    }
+                }
+            }
+            if constexpr (UPD) {
+                if (evict && valid && dist < best) {
+                    best = dist;
+                    bidx = r;
+                    if constexpr (ATT) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) bsc[g] = b[g];
+                    }
+                }
+            }
+        }
+    }
+
+    if constexpr (UPD) {
+        if (evict) {
+            // ---- nearest representative over the workgroup (lowest index on ties)
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) {
+                const double ob = __shfl_xor(best, o);
+                const int oi = __shfl_xor(bidx, o);
+                float osc[G];
+#pragma unroll
+                for (int g = 0; g < G; ++g) osc[g] = __shfl_xor(bsc[g], o);
+                if (ob < best || (ob == best && (uint32_t)oi < (uint32_t)bidx)) {
+                    best = ob;
+                    bidx = oi;
+#pragma unroll
+                    for (int g = 0; g < G; ++g) bsc[g] = osc[g];
+                }
+            }
+            if (lane == 0) {
+                sm.wbest[wave] = best;
+                sm.widx[wave] = bidx;
+#pragma unroll
+                for (int g = 0; g < G; ++g) sm.wbsc[wave][g] = bsc[g];
+            }
+            __syncthreads();
+            best = sm.wbest[0];
+            bidx = sm.widx[0];
+            int bw = 0;
+#pragma unroll
+            for (int wv = 1; wv < kWaves; ++wv) {
+                const double ob = sm.wbest[wv];
+                const int oi = sm.widx[wv];
+                if (ob < best || (ob == best && (uint32_t)oi < (uint32_t)bidx)) {
+                    best = ob;
+                    bidx = oi;
+                    bw = wv;
+                }
+            }
+            // ---- join iff ||k - x_i*||^2 <= delta^2, else open a cluster (or force-join when full)
+            const bool join = bidx >= 0 && best <= st.delta2;
+            const bool forced = !join && bidx >= 0 && m >= st.Mcap;
+            const bool created = !join && !forced;
+            const int target = created ? m : bidx;
+            if (created) {
+                if (tid < LPR) st16(X + (size_t)m * ROWB + tid * 16, ek);
+                if (tid == 0) cnt[m] = 1;
+            } else if (tid == 0) {
+                cnt[target] += 1;
+                if (forced) st.flags[sid] |= 1u;
+            }
+            if (tid == 0 && st.assign != nullptr && etoken < st.assign_cap)
+                st.assign[sid * (size_t)st.assign_cap + etoken] = target;
+            if constexpr (ATT) {
+                // the count bump (or the new cluster) adds one more term to the normaliser;
+                // every lane of one row group takes it so the group's partial stays consistent
+                if (grp == 0) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const float bx = created ? bnew[g] : sm.wbsc[bw][g];
+                        part[g].raise(bx);
+                        part[g].den += __expf(bx - part[g].mx);
+                    }
+                }
+            }
+            if (created) m += 1;
+
+            // ---- sampling update: p from the old mu, one coin per slot, then mu += ||v||^2
+            float vf[VEC];
+            unpack<BF16>(ev, vf);
+            double a = 0.0;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) a = fma((double)vf[v], (double)vf[v], a);
+            a = group_sum<LPR>(a);
+            const float vn = (float)a;
+            float p;
+            if (mu == 0.0) p = 1.f;
+            else if (vn == 0.f) p = 0.f;
+            else p = (float)((double)vn / (mu + (double)vn));
+
+            for (int base = 0; base < st.s; base += kQueue) {
+                if (tid == 0) sm.qn = 0;
+                __syncthreads();
+                const int j0 = base + tid * 4;
+                if (j0 < st.s && p > 0.f) {
+                    uint32_t r[4];
+                    philox4x32_10((uint32_t)(j0 >> 2), (uint32_t)etoken, (uint32_t)((uint64_t)etoken >> 32),
+                                  (uint32_t)sid, st.seed_lo, st.seed_hi, r);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float u = (float)(r[i] >> 8) * (1.0f / 16777216.0f);
+                        if (j0 + i < st.s && u < p) sm.queue[atomicAdd(&sm.qn, 1)] = j0 + i;
+                    }
+                }
+                __syncthreads();
+                const int nq = sm.qn;
+                for (int e = grp; e < nq; e += RPB) {
+                    const int j = sm.queue[e];
+                    st16(Ks + (size_t)j * ROWB + col * 16, ek);
+                    st16(Vs + (size_t)j * ROWB + col * 16, ev);
+                    if (col == 0) {
+                        st.sidx[sid * (size_t)st.s + j] = (int32_t)etoken;
+                        st.svn[sid * (size_t)st.s + j] = vn;
+                    }
+                }
+                __syncthreads();
+            }
+            mu += (double)vn;
+        }
+        __syncthreads();  // window slot, center row and sample rows are visible to the whole workgroup
+    }
+
+    if constexpr (ATT) {
+        // ---- sampled pairs: numerator terms  mu/(s ||v_j||^2) e^{<q,k_j>} v_j
+        if (n_evicted_after > 0) {
+            const float wmul = (float)(mu / (double)st.s);
+            const float *svn = st.svn + sid * (size_t)st.s;
+            for (int r0 = wave * RPW; r0 < st.s; r0 += RPB) {
+                const int r = r0 + sub;
+                const bool valid = r < st.s;
+                const int rr = valid ? r : st.s - 1;
+                float kx[VEC], vx[VEC];
+                unpack<BF16>(ld16(Ks + (size_t)rr * ROWB + col * 16), kx);
+                unpack<BF16>(ld16(Vs + (size_t)rr * ROWB + col * 16), vx);
+                const float vnj = svn[rr];
+                const float wgt = vnj > 0.f ? wmul / vnj : 0.f;
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float a = 0.f;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) a = fmaf(q[g][v], kx[v], a);
+                    const float b = group_sum<LPR>(a);
+                    if (valid) {
+                        part[g].raise(b);
+                        const float e = wgt * __expf(b - part[g].mx);
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) part[g].acc[v] = fmaf(e, vx[v], part[g].acc[v]);
+                    }
+                }
+            }
+        }
+        // ---- window: exact terms in numerator and normaliser
+        const int fill = (int)(n_after < st.w ? n_after : st.w);
+        for (int r0 = wave * RPW; r0 < fill; r0 += RPB) {
+            const int r = r0 + sub;
+            const bool valid = r < fill;
+            const int rr = valid ? r : fill - 1;
+            float kx[VEC], vx[VEC];
+            unpack<BF16>(ld16(Kw + (size_t)rr * ROWB + col * 16), kx);
+            unpack<BF16>(ld16(Vw + (size_t)rr * ROWB + col * 16), vx);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float a = 0.f;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) a = fmaf(q[g][v], kx[v], a);
+                const float b = group_sum<LPR>(a);
+                if (valid) {
+                    part[g].raise(b);
+                    const float e = __expf(b - part[g].mx);
+                    part[g].den += e;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) part[g].acc[v] = fmaf(e, vx[v], part[g].acc[v]);
+                }
+            }
+        }
+        // ---- merge row groups inside the wavefront, then the wavefronts through LDS
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) {
+                const float omx = __shfl_xor(part[g].mx, o);
+                const float oden = __shfl_xor(part[g].den, o);
+                float oacc[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) oacc[v] = __shfl_xor(part[g].acc[v], o);
+                part[g].merge(omx, oden, oacc);
+            }
+            if (sub == 0) {
+                if (col == 0) {
+                    sm.wmx[wave][g] = part[g].mx;
+                    sm.wden[wave][g] = part[g].den;
+                }
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) sm.wacc[wave][g][col * VEC + v] = part[g].acc[v];
+            }
+        }
+        __syncthreads();
+        const int d = LPR * VEC;
+        for (int i = tid; i < G * d; i += kWG) {
+            const int g = i / d, c = i % d;
+            float M = sm.wmx[0][g];
+#pragma unroll
+            for (int wv = 1; wv < kWaves; ++wv) M = fmaxf(M, sm.wmx[wv][g]);
+            float den = 0.f, num = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < kWaves; ++wv) {
+                const float wm = sm.wmx[wv][g];
+                const float sc = (wm == -INFINITY) ? 0.f : __expf(wm - M);
+                den = fmaf(sm.wden[wv][g], sc, den);
+                num = fmaf(sm.wacc[wv][g][c], sc, num);
+            }
+            outrows[(size_t)g * d + c] = num / den;
+        }
+    }
+    __syncthreads();  // LDS and state are reusable by the next token
+}
+
+// ---------------------------------------------------------------------------
+// Kernels: grid = streams, block = 256
+// ---------------------------------------------------------------------------
+template <bool BF16, int LPR, int G, bool UPD, bool ATT>
+__global__ __launch_bounds__(kWG) void decode_kernel(const State st, const Call call)
+{
+    constexpr int VEC = BF16 ? 8 : 4;
+    __shared__ Smem<LPR, G, VEC> sm;
+    const size_t sid = blockIdx.x;
+    int m = st.m[sid];
+    double mu = st.mu[sid];
+    const size_t rowb = (size_t)LPR * 16;
+    const char *krow = UPD ? call.K + sid * call.stream_stride : nullptr;
+    const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
+    const char *qrows = ATT ? call.Q + sid * G * rowb : nullptr;
+    float *outrows = ATT ? call.out + sid * (size_t)G * LPR * VEC : nullptr;
+    token_step<BF16, LPR, G, UPD, ATT>(st, sid, krow, vrow, qrows, outrows, call.n_seen, m, mu, sm);
+    if constexpr (UPD) {
+        if (threadIdx.x == 0) {
+            st.m[sid] = m;
+            st.mu[sid] = mu;
+        }
+    }
+}
+
+// Prefix ingest: the same per-token update, tokens of a stream taken in order.
+template <bool BF16, int LPR>
+__global__ __launch_bounds__(kWG) void ingest_kernel(const State st, const Call call)
+{
+    constexpr int VEC = BF16 ? 8 : 4;
+    __shared__ Smem<LPR, 1, VEC> sm;
+    const size_t sid = blockIdx.x;
+    int m = st.m[sid];
+    double mu = st.mu[sid];
+    const char *kbase = call.K + sid * call.stream_stride;
+    const char *vbase = call.V + sid * call.stream_stride;
+    for (int64_t t = 0; t < call.n_tokens; ++t)
+        token_step<BF16, LPR, 1, true, false>(st, sid, kbase + t * call.token_stride, vbase + t * call.token_stride,
+                                              nullptr, nullptr, call.n_seen + t, m, mu, sm);
+    if (threadIdx.x == 0) {
+        st.m[sid] = m;
+        st.mu[sid] = mu;
+    }
+}
+
+}  // namespace sg

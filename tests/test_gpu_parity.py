@@ -1,0 +1,280 @@
+"""GPU parity: the HIP library (through the C ABI binding) against the CPU oracle on the same bytes.
+
+Bars (benchmark definition): center assignments, counts and sampled indices bit-exact, except
+assignments whose decision margin is below 1e-5 relative (counted and reported); attention
+outputs within 2e-3 relative L2.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle.subgen_oracle import exact_attention
+from paper_2402_06082_amd.workloads import CONFIGS, Workload
+from tests.parity_util import REL_L2_TOL, compare_state, make_oracles, rel_l2, to_f32_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def binding():
+    from paper_2402_06082_amd import binding as b
+    return b
+
+
+def run_config(cfg, streams, delta, prefix, steps, *, fused=True, ingest_chunk=None, oracle_ids=None, seed=0,
+               max_centers=0):
+    """Prefix ingest + decode steps on the GPU and in the oracle; returns (gpu outs, oracle outs, sg, oracles)."""
+    b = binding()
+    wl = Workload(cfg, device=DEV, streams=streams)
+    S = wl.S
+    ids = list(range(S)) if oracle_ids is None else list(oracle_ids)
+    sg = b.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=cfg.g,
+                  max_centers=max_centers, assign_log_tokens=prefix + steps, seed=seed, device=DEV)
+    oracles = make_oracles(S, cfg.d, delta, cfg.s, cfg.w, seed=seed, max_centers=max_centers, stream_ids=ids)
+    chunk = ingest_chunk or 2048
+    for t0 in range(0, prefix, chunk):
+        t1 = min(prefix, t0 + chunk)
+        K, V = wl.tokens(t0, t1)
+        sg.ingest_prefix(K, V)
+        Kc, Vc = to_f32_np(K[ids]), to_f32_np(V[ids])
+        for o, k, v in zip(oracles, Kc, Vc):
+            o.ingest(k, v)
+    K, V = wl.tokens(prefix, prefix + steps)
+    Q = wl.queries(0, steps)
+    outs = torch.empty(steps, S, cfg.g, cfg.d, dtype=torch.float32, device=DEV)
+    for t in range(steps):
+        kt, vt, qt = K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()
+        if fused:
+            sg.step(kt, vt, qt, outs[t])
+        else:
+            sg.update(kt, vt)
+            sg.attend(qt, outs[t])
+    sg.sync()
+    Kc, Vc, Qc = to_f32_np(K[ids]), to_f32_np(V[ids]), to_f32_np(Q[ids])
+    ref = np.stack([o.decode(k, v, q) for o, k, v, q in zip(oracles, Kc, Vc, Qc)], axis=1)  # [steps, ids, g, d]
+    got = outs.cpu().numpy()[:, ids]
+    return got, ref, sg, oracles, ids
+
+
+def check_outputs(got, ref, skip_streams=()):
+    err = rel_l2(got, ref)
+    if skip_streams:
+        keep = [i for i in range(err.shape[1]) if i not in skip_streams]
+        err = err[:, keep]
+    assert np.isfinite(got).all()
+    assert err.max() <= REL_L2_TOL, f"max rel-L2 {err.max():.3e}"
+    return float(err.max())
+
+
+@pytest.mark.parametrize("name,fused", [("cfg1", True), ("cfg1", False), ("cfg1b", True), ("cfg1b", False)])
+def test_cfg1_single_head_fp32(name, fused):
+    cfg = CONFIGS[name]
+    got, ref, sg, oracles, ids = run_config(cfg, None, cfg.delta, cfg.prefix, cfg.decode_steps, fused=fused)
+    ties = compare_state(sg, oracles, ids)
+    worst = check_outputs(got, ref)
+    m = sg.center_counts()
+    print(f"{name} fused={fused}: m={m.tolist()} near-ties={ties} max rel-L2={worst:.2e}")
+    assert ties == 0
+    if name == "cfg1":
+        assert m[0] == cfg.prefix + cfg.decode_steps - cfg.w      # delta = 1 never merges on this data
+    else:
+        assert 20 <= m[0] <= 300
+
+
+def test_cfg2_llama_layer_bf16_all_streams():
+    b = binding()
+    from paper_2402_06082_amd.tuning import tune_delta
+    cfg = CONFIGS["cfg2"]
+    delta, m_probe = tune_delta(cfg, DEV)
+    got, ref, sg, oracles, ids = run_config(cfg, None, delta, cfg.prefix, cfg.decode_steps)
+    ties = compare_state(sg, oracles, ids)
+    tied = [i for i, o in enumerate(oracles) if not np.array_equal(sg.export_state(ids[i], rows=False).assign,
+                                                                   o.assign)]
+    worst = check_outputs(got, ref, skip_streams=tied)
+    st = sg.stats()
+    print(f"cfg2: delta={delta:.4f} probe m={m_probe:.0f} mean m={st.total_centers / st.streams:.1f} "
+          f"near-tie streams={ties} max rel-L2={worst:.2e}")
+    assert st.flags_or == 0
+    assert 200 <= st.total_centers / st.streams <= 420
+    assert ties <= 2
+
+
+def test_cfg3_shape_16_streams_full_prefix():
+    from paper_2402_06082_amd.tuning import tune_delta
+    cfg = CONFIGS["cfg3"]
+    delta, _ = tune_delta(cfg, DEV, probe_streams=8)
+    got, ref, sg, oracles, ids = run_config(cfg, 16, delta, cfg.prefix, 32, oracle_ids=[0, 5, 15])
+    ties = compare_state(sg, oracles, ids)
+    assert ties == 0
+    worst = check_outputs(got, ref)
+    st = sg.stats()
+    print(f"cfg3x16: delta={delta:.4f} mean m={st.total_centers / st.streams:.1f} max rel-L2={worst:.2e}")
+    assert 400 <= st.total_centers / st.streams <= 800
+
+
+def test_cfg5_shape_gqa_four_queries():
+    cfg = CONFIGS["cfg5"]
+    got, ref, sg, oracles, ids = run_config(cfg, 8, 8.3, 2048, 64)
+    assert compare_state(sg, oracles, ids) == 0
+    worst = check_outputs(got, ref)
+    print(f"cfg5x8 g=4: max rel-L2={worst:.2e}")
+    got2, ref2, sg2, oracles2, ids2 = run_config(cfg, 8, 8.3, 2048, 16, fused=False)
+    assert compare_state(sg2, oracles2, ids2) == 0
+    check_outputs(got2, ref2)
+
+
+def test_cfg4_shape_drift_small():
+    cfg = CONFIGS["cfg4"]
+    got, ref, sg, oracles, ids = run_config(cfg, 4, 8.3, 4096, 16)
+    assert compare_state(sg, oracles, ids) == 0
+    check_outputs(got, ref)
+
+
+# ------------------------------------------------------------------ ABI contract
+def small_cfg(**kw):
+    base = CONFIGS["cfg2"].scaled(name="small", kv_heads=6, prefix=300, decode_steps=20, s=37, w=9, components=8)
+    return base.scaled(**kw)
+
+
+def state_tuple(sg, sid):
+    st = sg.export_state(sid)
+    return (st.m, st.mu, st.counts.tolist(), st.sample_idx.tolist(), st.sample_vn.tolist(),
+            st.centers.tobytes(), st.sample_k.tobytes(), st.sample_v.tobytes(), st.window_k.tobytes())
+
+
+def test_ingest_equals_updates_and_chunking_is_invariant():
+    b = binding()
+    cfg = small_cfg()
+    wl = Workload(cfg, device=DEV)
+    K, V = wl.tokens(0, 300)
+    mk = lambda: b.SubGen(wl.S, cfg.d, 8.0, cfg.s, cfg.w, dtype=cfg.torch_dtype, seed=3, device=DEV)
+    a, c, e = mk(), mk(), mk()
+    a.ingest_prefix(K, V)
+    for t in range(300):
+        c.update(K[:, t].contiguous(), V[:, t].contiguous())
+    for lo, hi in [(0, 1), (1, 8), (8, 9), (9, 10), (10, 211), (211, 300)]:
+        e.ingest_prefix(K[:, lo:hi], V[:, lo:hi])          # strided views, ragged chunks
+    e.ingest_prefix(K[:, 0:0], V[:, 0:0])                   # empty chunk is a no-op
+    for sid in range(wl.S):
+        assert state_tuple(a, sid) == state_tuple(c, sid) == state_tuple(e, sid)
+    # same seed twice -> same bytes; another seed -> other samples
+    f = mk()
+    f.ingest_prefix(K, V)
+    g = b.SubGen(wl.S, cfg.d, 8.0, cfg.s, cfg.w, dtype=cfg.torch_dtype, seed=4, device=DEV)
+    g.ingest_prefix(K, V)
+    assert state_tuple(a, 2) == state_tuple(f, 2)
+    assert a.export_state(2).sample_idx.tolist() != g.export_state(2).sample_idx.tolist()
+    assert a.export_state(2).counts.tolist() == g.export_state(2).counts.tolist()
+
+
+def test_step_equals_update_then_attend():
+    b = binding()
+    cfg = small_cfg(g=2)
+    wl = Workload(cfg, device=DEV)
+    K, V = wl.tokens(0, 120)
+    Q = wl.queries(0, 120)
+    mk = lambda: b.SubGen(wl.S, cfg.d, 8.0, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=2, device=DEV)
+    a, c = mk(), mk()
+    for t in range(120):
+        kt, vt, qt = K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()
+        o1 = a.step(kt, vt, qt)
+        c.update(kt, vt)
+        o2 = c.attend(qt)
+        err = rel_l2(o1.cpu().numpy(), o2.cpu().numpy().astype(np.float64))
+        assert err.max() < 1e-5, (t, err.max())
+    for sid in range(wl.S):
+        assert state_tuple(a, sid) == state_tuple(c, sid)
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.float32, 32), (torch.float32, 128), (torch.bfloat16, 64),
+                                     (torch.bfloat16, 256)])
+@pytest.mark.parametrize("s,w", [(1, 0), (5, 3), (130, 17)])
+def test_shapes_and_edge_parameters(dtype, d, s, w):
+    """Other row sizes, w = 0 (pure Algorithm 1), s = 1, s not a multiple of 4, n < w, n = w, n = w + 1."""
+    b = binding()
+    gen = torch.Generator(device="cpu").manual_seed(d * 1000 + s * 10 + w)
+    S, n = 3, 60
+    cent = torch.randn(S, 5, d, generator=gen) * 2.0
+    comp = torch.randint(0, 5, (S, n), generator=gen)
+    K = (torch.gather(cent, 1, comp[..., None].expand(S, n, d)) + 0.2 * torch.randn(S, n, d, generator=gen))
+    V = torch.randn(S, n, d, generator=gen)
+    Q = torch.randn(S, n, 1, d, generator=gen) / d ** 0.5
+    K, V, Q = (t.to(dtype).to(DEV) for t in (K, V, Q))
+    delta = 0.2 * (2 * d) ** 0.5 * 1.05
+    sg = b.SubGen(S, d, delta, s, w, dtype=dtype, assign_log_tokens=n, seed=11, device=DEV)
+    oracles = make_oracles(S, d, delta, s, w, seed=11)
+    for t in range(n):
+        out = sg.step(K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous())
+        ref = np.stack([o.decode(to_f32_np(K[i, t:t + 1]), to_f32_np(V[i, t:t + 1]), to_f32_np(Q[i, t:t + 1]))[0]
+                        for i, o in enumerate(oracles)])
+        assert rel_l2(out.cpu().numpy(), ref).max() <= REL_L2_TOL, t
+        if t in (0, w - 1, w, w + 1, n - 1):
+            assert compare_state(sg, oracles) == 0
+    assert 3 <= sg.center_counts().min() and sg.center_counts().max() <= 30
+
+
+def test_delta_zero_duplicates_and_center_overflow():
+    b = binding()
+    d, S, n = 64, 2, 90
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    pool = torch.randn(S, 12, d, generator=gen)
+    pick = torch.randint(0, 12, (S, n), generator=gen)
+    K = torch.gather(pool, 1, pick[..., None].expand(S, n, d)).contiguous().to(DEV)
+    V = torch.randn(S, n, d, generator=gen).to(DEV)
+    Q = (torch.randn(S, 1, d, generator=gen) / 8).to(DEV)
+    # delta = 0: only exact duplicates join, so the normaliser is the exact partition function
+    sg = b.SubGen(S, d, 0.0, 8, 0, assign_log_tokens=n, device=DEV)
+    oracles = make_oracles(S, d, 0.0, 8, 0)
+    sg.ingest_prefix(K, V)
+    for o, k, v in zip(oracles, to_f32_np(K), to_f32_np(V)):
+        o.ingest(k, v)
+    assert compare_state(sg, oracles) == 0 and sg.center_counts().max() <= 12
+    out = sg.attend(Q).cpu().numpy()
+    ref = np.stack([o.attend(to_f32_np(Q[i, 0]))[None] for i, o in enumerate(oracles)])
+    assert rel_l2(out, ref).max() <= REL_L2_TOL
+    # capacity 5 < 12 distinct keys: later tokens are force-joined and the sticky flag is raised
+    sg = b.SubGen(S, d, 0.0, 8, 0, max_centers=5, assign_log_tokens=n, device=DEV)
+    oracles = make_oracles(S, d, 0.0, 8, 0, max_centers=5)
+    sg.ingest_prefix(K, V)
+    for o, k, v in zip(oracles, to_f32_np(K), to_f32_np(V)):
+        o.ingest(k, v)
+    assert compare_state(sg, oracles) == 0
+    st = sg.stats()
+    assert st.max_centers == 5 and st.flags_or == b.FLAG_CENTER_OVERFLOW and st.flagged_streams == S
+    assert all(o.overflowed for o in oracles)
+
+
+def test_error_codes():
+    b = binding()
+    sg = b.SubGen(2, 128, 1.0, 4, 2, dtype=torch.bfloat16, device=DEV)
+    q = torch.zeros(2, 1, 128, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(b.SubgenError) as e:
+        sg.attend(q)
+    assert e.value.code == -4                      # attend before any token
+    for bad in [dict(d=100), dict(delta=-1.0), dict(delta=float("nan")), dict(s=0), dict(w=-1), dict(g=3),
+                dict(streams=0)]:
+        kw = dict(streams=2, d=128, delta=1.0, s=4, w=2, g=1)
+        kw.update(bad)
+        with pytest.raises(b.SubgenError) as e:
+            b.SubGen(kw["streams"], kw["d"], kw["delta"], kw["s"], kw["w"], dtype=torch.bfloat16,
+                     q_per_stream=kw["g"], device=DEV)
+        assert e.value.code == -1, bad
+    with pytest.raises(ValueError):
+        sg.update(torch.zeros(2, 64, dtype=torch.bfloat16, device=DEV), torch.zeros(2, 64, dtype=torch.bfloat16,
+                                                                                    device=DEV))
+    assert b.strerror(-4) == "attend before any token"
+
+
+@pytest.mark.parametrize("dtype,d,g,n", [(torch.bfloat16, 128, 1, 5000), (torch.bfloat16, 128, 4, 777),
+                                         (torch.float32, 64, 1, 1), (torch.float32, 64, 2, 300)])
+def test_exact_attend_against_textbook_attention(dtype, d, g, n):
+    b = binding()
+    gen = torch.Generator(device="cpu").manual_seed(n)
+    S = 5
+    K = (torch.randn(S, n, d, generator=gen)).to(dtype).to(DEV)
+    V = torch.randn(S, n, d, generator=gen).to(dtype).to(DEV)
+    Q = (torch.randn(S, g, d, generator=gen) / d ** 0.5 * 3).to(dtype).to(DEV)
+    out = b.exact_attend(K, V, Q).cpu().numpy()
+    Kc, Vc, Qc = to_f32_np(K), to_f32_np(V), to_f32_np(Q)
+    ref = np.stack([[exact_attention(Kc[i], Vc[i], Qc[i, h]) for h in range(g)] for i in range(S)])
+    assert rel_l2(out, ref).max() <= 1e-4
