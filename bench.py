@@ -1,0 +1,281 @@
+#!/usr/bin/env python3
+"""Benchmark of the SubGen decode step on one MI355X.
+
+One "step" = every stream of the workload takes one new (k, v) and answers its g queries
+(window push, cluster update, sampling update, attention estimate) through one call of
+``subgen_step``.  The default workload is the n=16k, 8192-stream config the metric is quoted on.
+Inputs are synthetic, generated on the device, and resident in HBM before the timed region.
+
+Prints ONE JSON line with the throughput, the roofline of the step kernel (algorithmic bytes /
+HIP-event kernel time against the 8 TB/s HBM peak) and the CPU oracle timed on the host cores
+on a bounded sample of the same workload (a baseline for context only).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import subprocess
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# Measured HBM traffic of one step-kernel launch (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this script, each scaled by what the counter reads for a plain 1 GiB device copy
+# (profiles/step_kernel_cfg3_pmc_hbm_traffic.txt).  Workloads without a measurement report null.
+MEASURED_TRAFFIC_BYTES = {"cfg3": 4.0105e9}
+
+
+def algorithmic_bytes(cfg, streams, total_centers):
+    """Bytes one decode step must move: every row of the state once, plus the new token, queries, output."""
+    e, d, s, w, g = cfg.elem_bytes, cfg.d, cfg.s, cfg.w, cfg.g
+    per_stream = e * d * (2 * s + 2 * w) + 4 * s          # sampled K,V rows + ||v||^2, window K,V rows
+    per_stream += e * d * (2 + g) + 4 * g * d             # read K_t, V_t, g queries; write g fp32 outputs
+    per_stream += 2 * e * d + 2 * e * d                   # write the new token into the ring, read the evicted one
+    return streams * per_stream + total_centers * (e * d + 4)   # center rows + counts, read once
+
+
+# --------------------------------------------------------------------------------------
+# CPU baseline leg: runs in a child process that never touches the GPU
+# --------------------------------------------------------------------------------------
+def _oracle_worker(args):
+    import numpy as np
+    from oracle.subgen_oracle import OracleStream
+    (d, delta, s, w, stream_id, K, V, Q, prefix) = args
+    o = OracleStream(d, delta, s, w, seed=0, stream=stream_id)
+    o.ingest(K[:prefix], V[:prefix])
+    t0 = time.perf_counter()
+    o.decode(K[prefix:], V[prefix:], Q)
+    return time.perf_counter() - t0, o.m
+
+
+def cpu_baseline_main(a):
+    """Oracle decode steps on `cores` streams in parallel (one process per core)."""
+    import multiprocessing as mp
+    import torch
+    from paper_2402_06082_amd.workloads import CONFIGS, Workload
+    torch.set_num_threads(1)
+    cfg = CONFIGS[a.config]
+    cores = len(os.sched_getaffinity(0))
+    if os.environ.get("OMP_NUM_THREADS", "").isdigit():
+        cores = min(cores, int(os.environ["OMP_NUM_THREADS"]))
+    nstreams = cores * a.cpu_streams_per_core
+    wl = Workload(cfg, device="cpu", streams=nstreams)
+    K, V = wl.tokens(0, a.prefix + a.cpu_steps)
+    Q = wl.queries(0, a.cpu_steps)
+    f32 = lambda t: t.to(torch.float32).numpy()
+    jobs = [(cfg.d, a.delta, cfg.s, cfg.w, i, f32(K[i]), f32(V[i]), f32(Q[i]), a.prefix) for i in range(nstreams)]
+    t0 = time.perf_counter()
+    with mp.get_context("fork").Pool(cores) as pool:
+        res = pool.map(_oracle_worker, jobs, chunksize=1)
+    wall_all = time.perf_counter() - t0
+    # decode phase: every core runs its streams back to back; take the slowest core's decode time
+    per_core = [sum(r[0] for r in res[c::cores]) for c in range(cores)]
+    decode_wall = max(per_core)
+    stream_steps = nstreams * a.cpu_steps
+    print(json.dumps({"stream_steps_per_s": stream_steps / decode_wall, "cores": cores, "streams": nstreams,
+                      "steps": a.cpu_steps, "decode_wall_s": decode_wall, "total_wall_s": wall_all,
+                      "mean_centers": sum(r[1] for r in res) / len(res)}))
+
+
+def run_cpu_baseline(a, cfg, delta, streams_total):
+    cmd = [sys.executable, os.path.abspath(__file__), "--cpu-baseline-worker", "--config", a.config,
+           "--delta", repr(delta), "--prefix", str(a.prefix), "--cpu-steps", str(a.cpu_steps),
+           "--cpu-streams-per-core", str(a.cpu_streams_per_core)]
+    out = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+    if out.returncode != 0:
+        raise RuntimeError("cpu baseline failed: " + out.stderr[-2000:])
+    r = json.loads(out.stdout.strip().splitlines()[-1])
+    return {
+        "value": r["stream_steps_per_s"] / streams_total, "unit": "decode steps/s", "cores": r["cores"],
+        "kind": "oracle",
+        "sample": (f"{r['streams']} streams of the same generator (prefix {a.prefix} ingested untimed, then "
+                   f"{r['steps']} timed decode steps each, {r['decode_wall_s']:.1f} s on the slowest core); "
+                   f"{r['stream_steps_per_s']:.0f} stream-steps/s scaled to {streams_total} streams"),
+    }
+
+
+# --------------------------------------------------------------------------------------
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--streams", type=int, default=0, help="override the stream count (debugging)")
+    ap.add_argument("--prefix", type=int, default=-1, help="override the prefix length (debugging)")
+    ap.add_argument("--delta", type=float, default=0.0, help="skip tuning and use this threshold")
+    ap.add_argument("--split", action="store_true", help="time subgen_update + subgen_attend instead of subgen_step")
+    ap.add_argument("--no-exact", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=2048)
+    ap.add_argument("--pmc-copy-mib", type=int, default=0,
+                    help="also launch one plain device copy of this many MiB (calibrates rocprofv3 byte counters)")
+    ap.add_argument("--cpu-streams-per-core", type=int, default=2)
+    ap.add_argument("--cpu-baseline-worker", action="store_true", help=argparse.SUPPRESS)
+    a = ap.parse_args()
+
+    from paper_2402_06082_amd.workloads import CONFIGS
+    cfg = CONFIGS[a.config]
+    if a.prefix < 0:
+        a.prefix = cfg.prefix
+    if a.cpu_baseline_worker:
+        return cpu_baseline_main(a)
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (streams are independent and would shard by stream "
+              "with no communication); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2402_06082_amd import binding
+    from paper_2402_06082_amd.tuning import tune_delta
+    from paper_2402_06082_amd.workloads import BLOCK, Workload
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    S = a.streams or cfg.streams
+    steps, warm = a.steps, a.warmup
+
+    t_setup = time.perf_counter()
+    if a.delta > 0:
+        delta, probe_m = a.delta, float("nan")
+    else:
+        delta, probe_m = tune_delta(cfg, dev, prefix=a.prefix)
+    wl = Workload(cfg, device=dev, streams=S)
+    max_centers = max(2048, 3 * (cfg.target_centers or 1024))
+    sg = binding.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=cfg.g,
+                        max_centers=max_centers, seed=0, device=dev)
+
+    # ---- prefix: generate on the device block by block, ingest; keep it resident for the exact kernel
+    keep = not a.no_exact
+    free_b, _ = torch.cuda.mem_get_info()
+    kv_bytes = 2 * S * a.prefix * cfg.d * cfg.elem_bytes
+    if keep and kv_bytes > 0.7 * free_b:
+        keep = False
+    Kall = Vall = None
+    if keep:
+        Kall = torch.empty(S, a.prefix, cfg.d, dtype=cfg.torch_dtype, device=dev)
+        Vall = torch.empty_like(Kall)
+    torch.cuda.synchronize()
+    ingest_s = 0.0
+    chunk = 4 * BLOCK
+    for t0 in range(0, a.prefix, chunk):
+        t1 = min(a.prefix, t0 + chunk)
+        K, V = wl.tokens(t0, t1)
+        if keep:
+            Kall[:, t0:t1] = K
+            Vall[:, t0:t1] = V
+        torch.cuda.synchronize()
+        ti = time.perf_counter()
+        sg.ingest_prefix(K, V)
+        sg.sync()
+        ingest_s += time.perf_counter() - ti
+        del K, V
+    st0 = sg.stats()
+
+    # ---- decode inputs, resident in HBM, one contiguous [S, d] slab per step
+    K, V = wl.tokens(a.prefix, a.prefix + warm + steps)
+    Q = wl.queries(0, warm + steps)
+    Kt = K.permute(1, 0, 2).contiguous()
+    Vt = V.permute(1, 0, 2).contiguous()
+    Qt = Q.permute(1, 0, 2, 3).contiguous()
+    out = torch.empty(S, cfg.g, cfg.d, dtype=torch.float32, device=dev)
+    del K, V, Q
+
+    def one(i):
+        if a.split:
+            sg.update(Kt[i], Vt[i])
+            sg.attend(Qt[i], out)
+        else:
+            sg.step(Kt[i], Vt[i], Qt[i], out)
+
+    for i in range(warm):
+        one(i)
+    torch.cuda.synchronize()
+    if a.pmc_copy_mib > 0:
+        src = torch.ones(a.pmc_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    m_before = sg.stats().total_centers
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ev0[i].record()          # the library enqueues on torch's current stream, which these events time
+        one(warm + i)
+        ev1[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    st1 = sg.stats()
+    kernel_ms = sum(x.elapsed_time(y) for x, y in zip(ev0, ev1)) / steps
+    total_centers = 0.5 * (m_before + st1.total_centers)
+    alg = algorithmic_bytes(cfg, S, total_centers)
+    if a.split:
+        alg += total_centers * cfg.elem_bytes * cfg.d      # the split path reads the center table twice
+    achieved = alg / (kernel_ms * 1e-3) / 1e9
+
+    # ---- exact full-KV decode attention from the same library, for context
+    exact = None
+    if keep:
+        ws = torch.empty(max(binding.load().subgen_exact_workspace_bytes(S, a.prefix, cfg.d, cfg.g), 16),
+                         dtype=torch.uint8, device=dev)
+        eo = torch.empty_like(out)
+        for _ in range(2):
+            binding.exact_attend(Kall, Vall, Qt[0], eo, ws)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 5
+        e0.record()
+        for i in range(reps):
+            binding.exact_attend(Kall, Vall, Qt[i % (warm + steps)], eo, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ems = e0.elapsed_time(e1) / reps
+        exact = {"ms_per_step": ems, "steps_per_s": 1e3 / ems, "GB_per_s": kv_bytes / (ems * 1e-3) / 1e9,
+                 "n": a.prefix}
+        del Kall, Vall, ws
+    setup_s = time.perf_counter() - t_setup
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = run_cpu_baseline(a, cfg, delta, S)
+
+    name = a.config + ("" if S == cfg.streams and a.prefix == cfg.prefix else f" (streams={S}, prefix={a.prefix})")
+    kernel = "subgen_update+subgen_attend" if a.split else "subgen_step"
+    result = {
+        "metric": "compressed decode steps/s (all heads, 1 GPU) at n=16k; % HBM roofline",
+        "value": steps / wall, "unit": "decode steps/s", "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": 1e3 * wall / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {
+            "workload": f"{name}: {S} streams (batch {cfg.batch} x {cfg.layers} layers x {cfg.kv_heads} KV heads), "
+                        f"g={cfg.g}, d={cfg.d}, {cfg.dtype}, prefix n={a.prefix}, s={cfg.s}, w={cfg.w}, "
+                        f"{cfg.components}-component clustered keys",
+            "entry_point": kernel, "streams": S, "delta": delta, "mean_centers": total_centers / S,
+            "min_centers": st1.min_centers, "max_centers": st1.max_centers, "flags": st1.flags_or,
+            "prefix_ingest_s": ingest_s, "prefix_ingest_tokens_per_s": S * a.prefix / max(ingest_s, 1e-9),
+            "setup_s": setup_s,
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (not a.split and S == cfg.streams
+                                                                    and a.prefix == cfg.prefix) else None,
+            "kernel": kernel, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": alg,
+        },
+        "cpu_baseline": cpu,
+        "exact_full_kv": exact,
+    }
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
