@@ -137,6 +137,15 @@ int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, 
                         int32_t d, int32_t g, int32_t dtype, void *workspace, size_t workspace_bytes,
                         void *hip_stream);
 
+/*
+ * subgen_hbm_read_probe — measurement aid, not part of the method: one plain streaming read of
+ * `bytes` bytes of device memory (16-byte loads, grid-stride over `workgroups` workgroups of 256
+ * lanes).  Timed by the caller, it gives the HBM read bandwidth a kernel reaches on this device,
+ * the practical ceiling quoted beside the step kernel's roofline fraction.
+ *   buf   device, 16-byte aligned, at least `bytes` bytes; sink  device, 4 bytes (never read back)
+ */
+int subgen_hbm_read_probe(const void *buf, size_t bytes, int32_t workgroups, void *sink, void *hip_stream);
+
 /* Aggregate counters; synchronises the context's stream. */
 typedef struct subgen_stats_t {
     uint32_t struct_size;

@@ -22,7 +22,7 @@ FLAG_CENTER_OVERFLOW = 1
 
 EXPORTS = [
     "subgen_create", "subgen_destroy", "subgen_update", "subgen_attend", "subgen_step", "subgen_ingest_prefix",
-    "subgen_exact_workspace_bytes", "subgen_exact_attend", "subgen_stats", "subgen_center_counts",
+    "subgen_exact_workspace_bytes", "subgen_exact_attend", "subgen_hbm_read_probe", "subgen_stats", "subgen_center_counts",
     "subgen_export_state", "subgen_sync", "subgen_strerror", "subgen_last_hip_error",
 ]
 
@@ -84,6 +84,8 @@ def load():
     L.subgen_exact_workspace_bytes.argtypes = [i64, i64, i32, i32]
     L.subgen_exact_attend.restype = C.c_int
     L.subgen_exact_attend.argtypes = [P, P, P, P, i64, i64, i32, i32, i32, P, C.c_size_t, P]
+    L.subgen_hbm_read_probe.restype = C.c_int
+    L.subgen_hbm_read_probe.argtypes = [P, C.c_size_t, i32, P, P]
     L.subgen_stats.restype = C.c_int
     L.subgen_stats.argtypes = [P, C.POINTER(subgen_stats_t)]
     L.subgen_center_counts.restype = C.c_int
@@ -289,3 +291,11 @@ def exact_attend(K: torch.Tensor, V: torch.Tensor, Q: torch.Tensor, out: Optiona
                                  C.c_void_p(workspace.data_ptr()), workspace.numel(),
                                  C.c_void_p(torch.cuda.current_stream(K.device).cuda_stream)), "subgen_exact_attend")
     return out
+
+
+def hbm_read_probe(buf: torch.Tensor, workgroups: int, sink: torch.Tensor) -> None:
+    """One plain streaming read of ``buf`` (measurement aid; time it with events around the call)."""
+    _check(load().subgen_hbm_read_probe(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), int(workgroups),
+                                        C.c_void_p(sink.data_ptr()),
+                                        C.c_void_p(torch.cuda.current_stream(buf.device).cuda_stream)),
+           "subgen_hbm_read_probe")

@@ -22,7 +22,8 @@ HIPCC_FLAGS = [
 def build(verbose: bool = False) -> Path:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB.with_suffix(".so.tmp%d" % os.getpid())
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", str(tmp), str(SRC)]
+    extra = os.environ.get("SUBGEN_EXTRA_FLAGS", "").split()     # e.g. -DSG_UNROLL=8 for tuning sweeps
+    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-o", str(tmp), str(SRC)]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

@@ -1,6 +1,6 @@
 // Device code of the SubGen decode step for gfx950 (wave64).
 //
-// One workgroup of 256 lanes (4 wavefronts) owns one stream for the whole
+// One workgroup of 64*kWaves lanes (4 wavefronts by default) owns one stream for the whole
 // kernel, so no two workgroups ever touch the same state.  Rows (centers,
 // sampled keys/values, window keys/values) are d contiguous elements; a row is
 // read by LPR consecutive lanes with one 16-byte load each, so one wavefront
@@ -19,9 +19,16 @@
 
 namespace sg {
 
-constexpr int kWG = 256;
-constexpr int kWaves = 4;
-constexpr int kQueue = 1024;  // sample slots handled per round of the sampling update
+#ifndef SG_WAVES
+#define SG_WAVES 4
+#endif
+constexpr int kWaves = SG_WAVES;  // wavefronts per workgroup
+constexpr int kWG = 64 * kWaves;
+constexpr int kQueue = 4 * kWG;  // sample slots handled per round of the sampling update (4 per lane)
+#ifndef SG_UNROLL
+#define SG_UNROLL 4
+#endif
+constexpr int kUnroll = SG_UNROLL;  // row loads in flight per lane in the scans
 
 // Pointers into the context's structure-of-arrays state (all device memory).
 struct State {
@@ -236,45 +243,56 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
     for (int g = 0; g < G; ++g) bsc[g] = 0.f;
 
     if ((UPD && evict) || ATT) {
-        for (int r0 = wave * RPW; r0 < m; r0 += RPB) {
-            const int r = r0 + sub;
-            const bool valid = r < m;
-            const int rr = valid ? r : m - 1;
-            float x[VEC];
-            unpack<BF16>(ld16(X + (size_t)rr * ROWB + col * 16), x);
-            double dist = 0.0;
-            if constexpr (UPD) {
-                if (evict) {
+        for (int r0 = wave * RPW; r0 < m; r0 += RPB * kUnroll) {
+            // issue all row loads of this iteration before any arithmetic (memory-level parallelism)
+            uint4 raw[kUnroll];
+            float cf[kUnroll];
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) {
-                        const double df = (double)x[v] - ekd[v];
-                        dist = fma(df, df, dist);
-                    }
-                    dist = group_sum<LPR>(dist);
-                }
+            for (int u = 0; u < kUnroll; ++u) {
+                const int r = r0 + u * RPB + sub;
+                const int rr = r < m ? r : m - 1;
+                raw[u] = ld16(X + (size_t)rr * ROWB + col * 16);
+                if constexpr (ATT) cf[u] = (float)cnt[rr];
             }
-            float b[G];
-            if constexpr (ATT) {
-                const float c = (float)cnt[rr];
 #pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    float a = 0.f;
+            for (int u = 0; u < kUnroll; ++u) {
+                const int r = r0 + u * RPB + sub;
+                const bool valid = r < m;
+                float x[VEC];
+                unpack<BF16>(raw[u], x);
+                double dist = 0.0;
+                if constexpr (UPD) {
+                    if (evict) {
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) a = fmaf(q[g][v], x[v], a);
-                    b[g] = group_sum<LPR>(a);
-                    if (valid) {
-                        part[g].raise(b[g]);
-                        part[g].den += c * __expf(b[g] - part[g].mx);
+                        for (int v = 0; v < VEC; ++v) {
+                            const double df = (double)x[v] - ekd[v];
+                            dist = fma(df, df, dist);
+                        }
+                        dist = group_sum<LPR>(dist);
                     }
                 }
-            }
-            if constexpr (UPD) {
-                if (evict && valid && dist < best) {
-                    best = dist;
-                    bidx = r;
-                    if constexpr (ATT) {
+                float b[G];
+                if constexpr (ATT) {
 #pragma unroll
-                        for (int g = 0; g < G; ++g) bsc[g] = b[g];
+                    for (int g = 0; g < G; ++g) {
+                        float a = 0.f;
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) a = fmaf(q[g][v], x[v], a);
+                        b[g] = group_sum<LPR>(a);
+                        if (valid) {
+                            part[g].raise(b[g]);
+                            part[g].den += cf[u] * __expf(b[g] - part[g].mx);
+                        }
+                    }
+                }
+                if constexpr (UPD) {
+                    if (evict && valid && dist < best) {
+                        best = dist;
+                        bidx = r;
+                        if constexpr (ATT) {
+#pragma unroll
+                            for (int g = 0; g < G; ++g) bsc[g] = b[g];
+                        }
                     }
                 }
             }
@@ -396,15 +414,57 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
         if (n_evicted_after > 0) {
             const float wmul = (float)(mu / (double)st.s);
             const float *svn = st.svn + sid * (size_t)st.s;
-            for (int r0 = wave * RPW; r0 < st.s; r0 += RPB) {
-                const int r = r0 + sub;
-                const bool valid = r < st.s;
-                const int rr = valid ? r : st.s - 1;
+            for (int r0 = wave * RPW; r0 < st.s; r0 += RPB * kUnroll) {
+                uint4 rk[kUnroll], rv[kUnroll];
+                float vnj[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const int r = r0 + u * RPB + sub;
+                    const int rr = r < st.s ? r : st.s - 1;
+                    rk[u] = ld16(Ks + (size_t)rr * ROWB + col * 16);
+                    rv[u] = ld16(Vs + (size_t)rr * ROWB + col * 16);
+                    vnj[u] = svn[rr];
+                }
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    const bool valid = r0 + u * RPB + sub < st.s;
+                    float kx[VEC], vx[VEC];
+                    unpack<BF16>(rk[u], kx);
+                    unpack<BF16>(rv[u], vx);
+                    const float wgt = vnj[u] > 0.f ? wmul / vnj[u] : 0.f;
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        float a = 0.f;
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) a = fmaf(q[g][v], kx[v], a);
+                        const float b = group_sum<LPR>(a);
+                        if (valid) {
+                            part[g].raise(b);
+                            const float e = wgt * __expf(b - part[g].mx);
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) part[g].acc[v] = fmaf(e, vx[v], part[g].acc[v]);
+                        }
+                    }
+                }
+            }
+        }
+        // ---- window: exact terms in numerator and normaliser
+        const int fill = (int)(n_after < st.w ? n_after : st.w);
+        for (int r0 = wave * RPW; r0 < fill; r0 += RPB * kUnroll) {
+            uint4 rk[kUnroll], rv[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int r = r0 + u * RPB + sub;
+                const int rr = r < fill ? r : fill - 1;
+                rk[u] = ld16(Kw + (size_t)rr * ROWB + col * 16);
+                rv[u] = ld16(Vw + (size_t)rr * ROWB + col * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const bool valid = r0 + u * RPB + sub < fill;
                 float kx[VEC], vx[VEC];
-                unpack<BF16>(ld16(Ks + (size_t)rr * ROWB + col * 16), kx);
-                unpack<BF16>(ld16(Vs + (size_t)rr * ROWB + col * 16), vx);
-                const float vnj = svn[rr];
-                const float wgt = vnj > 0.f ? wmul / vnj : 0.f;
+                unpack<BF16>(rk[u], kx);
+                unpack<BF16>(rv[u], vx);
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     float a = 0.f;
@@ -413,34 +473,11 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
                     const float b = group_sum<LPR>(a);
                     if (valid) {
                         part[g].raise(b);
-                        const float e = wgt * __expf(b - part[g].mx);
+                        const float e = __expf(b - part[g].mx);
+                        part[g].den += e;
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) part[g].acc[v] = fmaf(e, vx[v], part[g].acc[v]);
                     }
-                }
-            }
-        }
-        // ---- window: exact terms in numerator and normaliser
-        const int fill = (int)(n_after < st.w ? n_after : st.w);
-        for (int r0 = wave * RPW; r0 < fill; r0 += RPB) {
-            const int r = r0 + sub;
-            const bool valid = r < fill;
-            const int rr = valid ? r : fill - 1;
-            float kx[VEC], vx[VEC];
-            unpack<BF16>(ld16(Kw + (size_t)rr * ROWB + col * 16), kx);
-            unpack<BF16>(ld16(Vw + (size_t)rr * ROWB + col * 16), vx);
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                float a = 0.f;
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) a = fmaf(q[g][v], kx[v], a);
-                const float b = group_sum<LPR>(a);
-                if (valid) {
-                    part[g].raise(b);
-                    const float e = __expf(b - part[g].mx);
-                    part[g].den += e;
-#pragma unroll
-                    for (int v = 0; v < VEC; ++v) part[g].acc[v] = fmaf(e, vx[v], part[g].acc[v]);
                 }
             }
         }
@@ -487,7 +524,7 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
 }
 
 // ---------------------------------------------------------------------------
-// Kernels: grid = streams, block = 256
+// Kernels: grid = streams, block = kWG lanes
 // ---------------------------------------------------------------------------
 template <bool BF16, int LPR, int G, bool UPD, bool ATT>
 __global__ __launch_bounds__(kWG) void decode_kernel(const State st, const Call call)
