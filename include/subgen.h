@@ -72,6 +72,10 @@ typedef struct subgen_opts {
     void *hip_stream;       /* hipStream_t every call enqueues on; NULL = the default stream               */
     int32_t device;         /* HIP device ordinal; -1 (or struct zeroed with device_set = 0) = current     */
     int32_t device_set;     /* non-zero: use `device`                                                      */
+    int32_t kernel_path;    /* 0 = automatic (bf16 rows are scored on the matrix cores where the shape allows);
+                               1 = always the generic vector-ALU kernels (any dtype; same results up to fp32
+                               rounding of the outputs, identical decisions)                               */
+    int32_t reserved;       /* must be 0                                                                   */
 } subgen_opts;
 
 /*

@@ -36,7 +36,8 @@ class SubgenError(RuntimeError):
 class subgen_opts(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("dtype", C.c_int32), ("q_per_stream", C.c_int32),
                 ("max_centers", C.c_int32), ("assign_log_tokens", C.c_int64), ("seed", C.c_uint64),
-                ("hip_stream", C.c_void_p), ("device", C.c_int32), ("device_set", C.c_int32)]
+                ("hip_stream", C.c_void_p), ("device", C.c_int32), ("device_set", C.c_int32),
+                ("kernel_path", C.c_int32), ("reserved", C.c_int32)]
 
 
 class subgen_stats_t(C.Structure):
@@ -141,7 +142,8 @@ class SubGen:
 
     def __init__(self, streams: int, d: int, delta: float, sample_budget: int, window: int, *,
                  dtype: torch.dtype = torch.float32, q_per_stream: int = 1, max_centers: int = 0,
-                 assign_log_tokens: int = 0, seed: int = 0, device: Optional[torch.device] = None):
+                 assign_log_tokens: int = 0, seed: int = 0, device: Optional[torch.device] = None,
+                 kernel_path: int = 0):
         self._L = load()
         self._h = C.c_void_p()
         if not torch.cuda.is_available():
@@ -164,6 +166,7 @@ class SubGen:
         o.hip_stream = torch.cuda.current_stream(self.device).cuda_stream
         o.device = self.device.index or 0
         o.device_set = 1
+        o.kernel_path = int(kernel_path)
         _check(self._L.subgen_create(C.byref(self._h), self.streams, self.d, C.c_float(self.delta), self.s, self.w,
                                      C.byref(o)), "subgen_create")
 

@@ -12,6 +12,7 @@
 
 #include "exact_device.hpp"
 #include "subgen_device.hpp"
+#include "subgen_mfma_device.hpp"
 
 using sg::Call;
 using sg::State;
@@ -28,6 +29,7 @@ struct subgen_ctx {
     hipStream_t stream = nullptr;
     int device = 0;
     int last_hip = 0;
+    bool mfma = false;     // bf16 rows scored on the matrix cores
     std::vector<void *> allocs;
 };
 
@@ -102,9 +104,49 @@ void launch_lpr(int LPR, int G, Mode mode, dim3 grid, hipStream_t s, const State
     else launch_g<BF16, 32>(G, mode, grid, s, st, call);
 }
 
+template <int NK, int G>
+void launch_mfma_mode(Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    switch (mode) {
+        case MODE_UPDATE:
+            hipLaunchKernelGGL((sg::decode_mfma_kernel<NK, 1, true, false>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+        case MODE_ATTEND:
+            hipLaunchKernelGGL((sg::decode_mfma_kernel<NK, G, false, true>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+        case MODE_STEP:
+            hipLaunchKernelGGL((sg::decode_mfma_kernel<NK, G, true, true>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+    }
+}
+
+// matrix-core path: bf16 rows of 64, 128 or 256 elements, as long as the fp32 accumulators fit in registers
+bool mfma_supported(int dtype, int LPR, int G) { return dtype == SUBGEN_BF16 && (LPR / 4) * G <= 16; }
+
+void launch_mfma(int NK, int G, Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    if (NK == 2) {
+        if (G == 1) launch_mfma_mode<2, 1>(mode, grid, s, st, call);
+        else if (G == 2) launch_mfma_mode<2, 2>(mode, grid, s, st, call);
+        else launch_mfma_mode<2, 4>(mode, grid, s, st, call);
+    } else if (NK == 4) {
+        if (G == 1) launch_mfma_mode<4, 1>(mode, grid, s, st, call);
+        else if (G == 2) launch_mfma_mode<4, 2>(mode, grid, s, st, call);
+        else launch_mfma_mode<4, 4>(mode, grid, s, st, call);
+    } else {
+        if (G == 1) launch_mfma_mode<8, 1>(mode, grid, s, st, call);
+        else launch_mfma_mode<8, 2>(mode, grid, s, st, call);
+    }
+}
+
 int launch_decode(subgen_ctx *c, Mode mode, const Call &call)
 {
     const dim3 grid((unsigned)c->S);
+    if (c->mfma) {
+        launch_mfma(c->LPR / 4, c->G, mode, grid, c->stream, c->st, call);
+        const hipError_t e = hipGetLastError();
+        return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+    }
     if (c->dtype == SUBGEN_BF16) launch_lpr<true>(c->LPR, c->G, mode, grid, c->stream, c->st, call);
     else launch_lpr<false>(c->LPR, c->G, mode, grid, c->stream, c->st, call);
     const hipError_t e = hipGetLastError();
@@ -172,6 +214,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     if (sample_budget < 1 || sample_budget > (1 << 20) || window < 0 || window > (1 << 20)) return SUBGEN_EINVAL;
     if (G != 1 && G != 2 && G != 4) return SUBGEN_EINVAL;
     if (Mcap < 1 || Mcap > (1 << 24) || o.assign_log_tokens < 0) return SUBGEN_EINVAL;
+    if (o.kernel_path != 0 && o.kernel_path != 1) return SUBGEN_EINVAL;
 
     subgen_ctx *c = new (std::nothrow) subgen_ctx();
     if (!c) return SUBGEN_ENOMEM;
@@ -186,6 +229,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     c->S = streams; c->d = d; c->s = sample_budget; c->w = window; c->Mcap = Mcap; c->G = G;
     c->dtype = o.dtype; c->esz = esz; c->LPR = d * esz / 16; c->delta = delta;
     c->stream = reinterpret_cast<hipStream_t>(o.hip_stream);
+    c->mfma = o.kernel_path == 0 && mfma_supported(o.dtype, c->LPR, G);
 
     State &st = c->st;
     st.Mcap = Mcap; st.s = sample_budget; st.w = window; st.d = d;
@@ -196,6 +240,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     int rc = SUBGEN_OK;
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.X, S * Mcap * rowb, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.cnt, S * Mcap, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.xn, S * Mcap, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.m, S, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Ks, S * sample_budget * rowb, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Vs, S * sample_budget * rowb, 0);

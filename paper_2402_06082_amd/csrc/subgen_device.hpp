@@ -34,6 +34,7 @@ constexpr int kUnroll = SG_UNROLL;  // row loads in flight per lane in the scans
 struct State {
     char *X;            // [S][Mcap][d]   cluster representatives x_i
     int32_t *cnt;       // [S][Mcap]      cluster sizes n_i
+    float *xn;          // [S][Mcap]      ||x_i||^2 (fp32 rounding of the exact sum), used by the MFMA path
     int32_t *m;         // [S]            number of clusters
     char *Ks, *Vs;      // [S][s][d]      sampled pairs M
     int32_t *sidx;      // [S][s]         token index held by each slot (-1 = null)
@@ -341,9 +342,16 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
             const bool forced = !join && bidx >= 0 && m >= st.Mcap;
             const bool created = !join && !forced;
             const int target = created ? m : bidx;
+            double kk2 = 0.0;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) kk2 = fma(ekd[v], ekd[v], kk2);
+            kk2 = group_sum<LPR>(kk2);
             if (created) {
                 if (tid < LPR) st16(X + (size_t)m * ROWB + tid * 16, ek);
-                if (tid == 0) cnt[m] = 1;
+                if (tid == 0) {
+                    cnt[m] = 1;
+                    st.xn[sid * (size_t)st.Mcap + m] = (float)kk2;
+                }
             } else if (tid == 0) {
                 cnt[target] += 1;
                 if (forced) st.flags[sid] |= 1u;

@@ -22,14 +22,15 @@ def binding():
 
 
 def run_config(cfg, streams, delta, prefix, steps, *, fused=True, ingest_chunk=None, oracle_ids=None, seed=0,
-               max_centers=0):
+               max_centers=0, kernel_path=0):
     """Prefix ingest + decode steps on the GPU and in the oracle; returns (gpu outs, oracle outs, sg, oracles)."""
     b = binding()
     wl = Workload(cfg, device=DEV, streams=streams)
     S = wl.S
     ids = list(range(S)) if oracle_ids is None else list(oracle_ids)
     sg = b.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=cfg.g,
-                  max_centers=max_centers, assign_log_tokens=prefix + steps, seed=seed, device=DEV)
+                  max_centers=max_centers, assign_log_tokens=prefix + steps, seed=seed, device=DEV,
+                  kernel_path=kernel_path)
     oracles = make_oracles(S, cfg.d, delta, cfg.s, cfg.w, seed=seed, max_centers=max_centers, stream_ids=ids)
     chunk = ingest_chunk or 2048
     for t0 in range(0, prefix, chunk):
@@ -81,12 +82,13 @@ def test_cfg1_single_head_fp32(name, fused):
         assert 20 <= m[0] <= 300
 
 
-def test_cfg2_llama_layer_bf16_all_streams():
+@pytest.mark.parametrize("kernel_path", [0, 1])
+def test_cfg2_llama_layer_bf16_all_streams(kernel_path):
     b = binding()
     from paper_2402_06082_amd.tuning import tune_delta
     cfg = CONFIGS["cfg2"]
     delta, m_probe = tune_delta(cfg, DEV)
-    got, ref, sg, oracles, ids = run_config(cfg, None, delta, cfg.prefix, cfg.decode_steps)
+    got, ref, sg, oracles, ids = run_config(cfg, None, delta, cfg.prefix, cfg.decode_steps, kernel_path=kernel_path)
     ties = compare_state(sg, oracles, ids)
     tied = [i for i, o in enumerate(oracles) if not np.array_equal(sg.export_state(ids[i], rows=False).assign,
                                                                    o.assign)]
@@ -112,13 +114,14 @@ def test_cfg3_shape_16_streams_full_prefix():
     assert 400 <= st.total_centers / st.streams <= 800
 
 
-def test_cfg5_shape_gqa_four_queries():
+@pytest.mark.parametrize("kernel_path", [0, 1])
+def test_cfg5_shape_gqa_four_queries(kernel_path):
     cfg = CONFIGS["cfg5"]
-    got, ref, sg, oracles, ids = run_config(cfg, 8, 8.3, 2048, 64)
+    got, ref, sg, oracles, ids = run_config(cfg, 8, 8.3, 2048, 64, kernel_path=kernel_path)
     assert compare_state(sg, oracles, ids) == 0
     worst = check_outputs(got, ref)
-    print(f"cfg5x8 g=4: max rel-L2={worst:.2e}")
-    got2, ref2, sg2, oracles2, ids2 = run_config(cfg, 8, 8.3, 2048, 16, fused=False)
+    print(f"cfg5x8 g=4 path={kernel_path}: max rel-L2={worst:.2e}")
+    got2, ref2, sg2, oracles2, ids2 = run_config(cfg, 8, 8.3, 2048, 16, fused=False, kernel_path=kernel_path)
     assert compare_state(sg2, oracles2, ids2) == 0
     check_outputs(got2, ref2)
 
@@ -167,13 +170,15 @@ def test_ingest_equals_updates_and_chunking_is_invariant():
     assert a.export_state(2).counts.tolist() == g.export_state(2).counts.tolist()
 
 
-def test_step_equals_update_then_attend():
+@pytest.mark.parametrize("kernel_path", [0, 1])
+def test_step_equals_update_then_attend(kernel_path):
     b = binding()
     cfg = small_cfg(g=2)
     wl = Workload(cfg, device=DEV)
     K, V = wl.tokens(0, 120)
     Q = wl.queries(0, 120)
-    mk = lambda: b.SubGen(wl.S, cfg.d, 8.0, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=2, device=DEV)
+    mk = lambda: b.SubGen(wl.S, cfg.d, 8.0, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=2, device=DEV,
+                          kernel_path=kernel_path)
     a, c = mk(), mk()
     for t in range(120):
         kt, vt, qt = K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()
@@ -189,7 +194,8 @@ def test_step_equals_update_then_attend():
 @pytest.mark.parametrize("dtype,d", [(torch.float32, 32), (torch.float32, 128), (torch.bfloat16, 64),
                                      (torch.bfloat16, 256)])
 @pytest.mark.parametrize("s,w", [(1, 0), (5, 3), (130, 17)])
-def test_shapes_and_edge_parameters(dtype, d, s, w):
+@pytest.mark.parametrize("kernel_path", [0, 1])
+def test_shapes_and_edge_parameters(dtype, d, s, w, kernel_path):
     """Other row sizes, w = 0 (pure Algorithm 1), s = 1, s not a multiple of 4, n < w, n = w, n = w + 1."""
     b = binding()
     gen = torch.Generator(device="cpu").manual_seed(d * 1000 + s * 10 + w)
@@ -201,7 +207,9 @@ def test_shapes_and_edge_parameters(dtype, d, s, w):
     Q = torch.randn(S, n, 1, d, generator=gen) / d ** 0.5
     K, V, Q = (t.to(dtype).to(DEV) for t in (K, V, Q))
     delta = 0.2 * (2 * d) ** 0.5 * 1.05
-    sg = b.SubGen(S, d, delta, s, w, dtype=dtype, assign_log_tokens=n, seed=11, device=DEV)
+    if kernel_path == 1 and dtype == torch.float32:
+        pytest.skip("fp32 rows always take the generic kernels")
+    sg = b.SubGen(S, d, delta, s, w, dtype=dtype, assign_log_tokens=n, seed=11, device=DEV, kernel_path=kernel_path)
     oracles = make_oracles(S, d, delta, s, w, seed=11)
     for t in range(n):
         out = sg.step(K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous())
@@ -278,3 +286,31 @@ def test_exact_attend_against_textbook_attention(dtype, d, g, n):
     Kc, Vc, Qc = to_f32_np(K), to_f32_np(V), to_f32_np(Q)
     ref = np.stack([[exact_attention(Kc[i], Vc[i], Qc[i, h]) for h in range(g)] for i in range(S)])
     assert rel_l2(out, ref).max() <= 1e-4
+
+
+@pytest.mark.parametrize("g", [1, 2, 4])
+def test_matrix_core_path_exact_decisions_on_lattice_keys(g):
+    """Keys on a coarse lattice: many representatives at exactly equal distance and many distances exactly
+    at the threshold, so the approximate distances of the matrix-core path are ambiguous all the time and the
+    exact re-evaluation (lowest index on ties, inclusive threshold) decides."""
+    b = binding()
+    d, S, n, s, w = 128, 4, 400, 16, 5
+    gen = torch.Generator(device="cpu").manual_seed(77 + g)
+    K = torch.randint(-1, 2, (S, n, d), generator=gen).float() * 0.5       # coordinates in {-0.5, 0, 0.5}
+    K[:, :, 8:] = 0.0                                                      # only 8 active coordinates
+    V = torch.randn(S, n, d, generator=gen)
+    Q = torch.randn(S, n, g, d, generator=gen) / d ** 0.5
+    K, V, Q = (t.to(torch.bfloat16).to(DEV) for t in (K, V, Q))
+    delta = 1.0                                                            # distances are sqrt(j)/2: 1.0 is hit exactly
+    sg = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, q_per_stream=g, assign_log_tokens=n, seed=2, device=DEV)
+    oracles = make_oracles(S, d, delta, s, w, seed=2)
+    outs = torch.stack([sg.step(K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()) for t in range(n)])
+    ref = np.stack([o.decode(to_f32_np(K[i]), to_f32_np(V[i]), to_f32_np(Q[i])) for i, o in enumerate(oracles)], 1)
+    # margins are exactly zero very often here, yet decisions must agree: both sides are exact on this data
+    for o, sid in zip(oracles, range(S)):
+        st = sg.export_state(sid)
+        assert np.array_equal(st.assign, o.assign) and np.array_equal(st.counts, o.counts)
+        assert np.array_equal(st.sample_idx, o.sample_idx)
+        thr, gap = o.margins()
+        assert (thr == 0).sum() > 5 and (gap == 0).sum() > 5
+    assert rel_l2(outs.cpu().numpy(), ref).max() <= REL_L2_TOL
