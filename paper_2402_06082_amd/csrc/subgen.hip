@@ -233,19 +233,20 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
 
     State &st = c->st;
     st.Mcap = Mcap; st.s = sample_budget; st.w = window; st.d = d;
+    st.McapS = (Mcap + 15) / 16 * 16; st.sS = (sample_budget + 15) / 16 * 16;
     st.delta2 = (double)delta * (double)delta;
     st.seed_lo = (uint32_t)o.seed; st.seed_hi = (uint32_t)(o.seed >> 32);
     st.assign_cap = o.assign_log_tokens;
     const size_t S = (size_t)streams, rowb = (size_t)d * esz;
     int rc = SUBGEN_OK;
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.X, S * Mcap * rowb, 0);
-    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.cnt, S * Mcap, 0);
-    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.xn, S * Mcap, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.cnt, S * st.McapS, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.xn, S * st.McapS, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.m, S, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Ks, S * sample_budget * rowb, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Vs, S * sample_budget * rowb, 0);
-    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.sidx, S * sample_budget, 0xFF);
-    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.svn, S * sample_budget, 0);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.sidx, S * st.sS, 0xFF);
+    if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.svn, S * st.sS, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Kw, S * window * rowb, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Vw, S * window * rowb, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.mu, S, 0);
@@ -454,11 +455,11 @@ int subgen_export_state(subgen_ctx *c, int64_t stream, subgen_state_view *v)
     v->window_fill = (int32_t)(c->n_seen < c->w ? c->n_seen : c->w);
     if ((v->centers || v->counts) && v->centers_cap < m) return SUBGEN_EINVAL;
     SG_D2H(v->centers, st.X + sid * c->Mcap * rowb, (size_t)m * rowb);
-    SG_D2H(v->counts, st.cnt + sid * c->Mcap, (size_t)m * sizeof(int32_t));
+    SG_D2H(v->counts, st.cnt + sid * st.McapS, (size_t)m * sizeof(int32_t));
     SG_D2H(v->sample_K, st.Ks + sid * c->s * rowb, (size_t)c->s * rowb);
     SG_D2H(v->sample_V, st.Vs + sid * c->s * rowb, (size_t)c->s * rowb);
-    SG_D2H(v->sample_idx, st.sidx + sid * c->s, (size_t)c->s * sizeof(int32_t));
-    SG_D2H(v->sample_vn, st.svn + sid * c->s, (size_t)c->s * sizeof(float));
+    SG_D2H(v->sample_idx, st.sidx + sid * st.sS, (size_t)c->s * sizeof(int32_t));
+    SG_D2H(v->sample_vn, st.svn + sid * st.sS, (size_t)c->s * sizeof(float));
     SG_D2H(v->window_K, st.Kw + sid * c->w * rowb, (size_t)c->w * rowb);
     SG_D2H(v->window_V, st.Vw + sid * c->w * rowb, (size_t)c->w * rowb);
     v->assign_len = 0;

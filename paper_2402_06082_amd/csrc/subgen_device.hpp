@@ -33,18 +33,19 @@ constexpr int kUnroll = SG_UNROLL;  // row loads in flight per lane in the scans
 // Pointers into the context's structure-of-arrays state (all device memory).
 struct State {
     char *X;            // [S][Mcap][d]   cluster representatives x_i
-    int32_t *cnt;       // [S][Mcap]      cluster sizes n_i
-    float *xn;          // [S][Mcap]      ||x_i||^2 (fp32 rounding of the exact sum), used by the MFMA path
+    int32_t *cnt;       // [S][McapS]     cluster sizes n_i
+    float *xn;          // [S][McapS]     ||x_i||^2 (fp32 rounding of the exact sum), used by the MFMA path
     int32_t *m;         // [S]            number of clusters
     char *Ks, *Vs;      // [S][s][d]      sampled pairs M
-    int32_t *sidx;      // [S][s]         token index held by each slot (-1 = null)
-    float *svn;         // [S][s]         ||v||^2 of that token
+    int32_t *sidx;      // [S][sS]        token index held by each slot (-1 = null)
+    float *svn;         // [S][sS]        ||v||^2 of that token
     char *Kw, *Vw;      // [S][w][d]      window ring, slot = token index mod w
     double *mu;         // [S]            sum of ||v||^2 over evicted tokens
     uint32_t *flags;    // [S]            sticky flag word
     int32_t *assign;    // [S][assign_cap] or null
     int64_t assign_cap;
     int32_t Mcap, s, w, d;
+    int32_t McapS, sS;  // strides of the per-center / per-slot scalar arrays (Mcap, s rounded up to 16)
     double delta2;      // delta^2
     uint32_t seed_lo, seed_hi;
 };
@@ -173,7 +174,7 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
     const int grp = wave * RPW + sub;
 
     char *const X = st.X + sid * (size_t)st.Mcap * ROWB;
-    int32_t *const cnt = st.cnt + sid * (size_t)st.Mcap;
+    int32_t *const cnt = st.cnt + sid * (size_t)st.McapS;
     char *const Ks = st.Ks + sid * (size_t)st.s * ROWB;
     char *const Vs = st.Vs + sid * (size_t)st.s * ROWB;
     char *const Kw = st.Kw + sid * (size_t)st.w * ROWB;
@@ -350,7 +351,7 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
                 if (tid < LPR) st16(X + (size_t)m * ROWB + tid * 16, ek);
                 if (tid == 0) {
                     cnt[m] = 1;
-                    st.xn[sid * (size_t)st.Mcap + m] = (float)kk2;
+                    st.xn[sid * (size_t)st.McapS + m] = (float)kk2;
                 }
             } else if (tid == 0) {
                 cnt[target] += 1;
@@ -406,8 +407,8 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
                     st16(Ks + (size_t)j * ROWB + col * 16, ek);
                     st16(Vs + (size_t)j * ROWB + col * 16, ev);
                     if (col == 0) {
-                        st.sidx[sid * (size_t)st.s + j] = (int32_t)etoken;
-                        st.svn[sid * (size_t)st.s + j] = vn;
+                        st.sidx[sid * (size_t)st.sS + j] = (int32_t)etoken;
+                        st.svn[sid * (size_t)st.sS + j] = vn;
                     }
                 }
                 __syncthreads();
@@ -421,7 +422,7 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
         // ---- sampled pairs: numerator terms  mu/(s ||v_j||^2) e^{<q,k_j>} v_j
         if (n_evicted_after > 0) {
             const float wmul = (float)(mu / (double)st.s);
-            const float *svn = st.svn + sid * (size_t)st.s;
+            const float *svn = st.svn + sid * (size_t)st.sS;
             for (int r0 = wave * RPW; r0 < st.s; r0 += RPB * kUnroll) {
                 uint4 rk[kUnroll], rv[kUnroll];
                 float vnj[kUnroll];

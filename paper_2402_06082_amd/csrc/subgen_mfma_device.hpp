@@ -3,14 +3,17 @@
 // Every score of the step is a dot product of a stored row (representative,
 // sampled key, window key) with one of a few vectors (the queries and the
 // evicted key).  A wavefront takes 16 rows at a time and runs
-// v_mfma_f32_16x16x32_bf16 with the vectors as the A operand (the queries are
-// replicated in rows 4L+r, so every 16-lane row L of the result holds all G
-// scores of row n = lane % 16) and the 16 stored rows as the B operand: lane
-// (n, L) loads the 16-byte chunks L, L+4, L+8, ... of row n, which is exactly
-// the B layout (k = 8L..8L+7 of each 32-wide K slice), so rows go from HBM
-// into the MFMA operands with no shuffle, no LDS and no conversion.  Values
-// rows are loaded in the same layout and accumulated on the vector ALUs
-// (lane (n, L) owns columns of chunks L, L+4, ... of the output).
+// v_mfma_f32_16x16x32_bf16 with the 16 stored rows as the A operand and the
+// vectors as the B operand (column n carries the vector of role(n): a query or
+// the evicted key).  Lane (n, L) = lane 16L+n loads the 16-byte chunks L, L+4,
+// L+8, ... of row n, which is exactly the A layout (k = 8L..8L+7 of each
+// 32-wide K slice), so rows go from HBM into the MFMA operand with no shuffle,
+// no LDS and no conversion.  The result register r of lane (n, L) is the score
+// of row 4L+r against vector role(n): each lane row L owns four rows.
+//
+// Value rows are loaded one full row per 16 lanes (lane n takes chunk n of row
+// 4L+u), so the weight a lane needs sits in a lane of its own quad (DPP
+// quad broadcast) and a lane owns only 8 output columns per query.
 //
 // Nearest-center decisions stay exact: the matrix cores give
 // D~_i = ||x_i||^2 + ||k||^2 - 2<x_i,k> with a bounded error; the decision is
@@ -29,30 +32,6 @@ __device__ __forceinline__ floatx4_t mfma_bf16(const uint4 &a, const uint4 &b, f
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
                                                    0, 0, 0);
-}
-
-// all-reduce over the 16 lanes of a DPP row (row rotations 8, 4, 2, 1)
-template <int N>
-__device__ __forceinline__ float row_ror(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf,
-                                                                 false));
-}
-__device__ __forceinline__ float row_sum16(float v)
-{
-    v += row_ror<8>(v);
-    v += row_ror<4>(v);
-    v += row_ror<2>(v);
-    v += row_ror<1>(v);
-    return v;
-}
-__device__ __forceinline__ float row_max16(float v)
-{
-    v = fmaxf(v, row_ror<8>(v));
-    v = fmaxf(v, row_ror<4>(v));
-    v = fmaxf(v, row_ror<2>(v));
-    v = fmaxf(v, row_ror<1>(v));
-    return v;
 }
 
 // Relative bound used for |D~ - D| <= kDistEps * (||x||^2 + ||k||^2): 128..256 exact bf16 products
@@ -142,68 +121,78 @@ __device__ __forceinline__ void exact_nearest(const char *X, int m, const uint4 
     __syncthreads();
 }
 
-// per-lane online softmax state of one query: reference maximum (lazy), denominator, NK*8 output columns
-template <int NK>
-struct PartialM {
-    float mx, den;
-    float acc[NK * 8];
-    __device__ __forceinline__ void init()
-    {
-        mx = -INFINITY;
-        den = 0.f;
-#pragma unroll
-        for (int i = 0; i < NK * 8; ++i) acc[i] = 0.f;
+// broadcast lane g of every quad (DPP quad_perm [g,g,g,g])
+template <int Gq>
+__device__ __forceinline__ float quad_bcast(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v),
+                                                                 Gq | (Gq << 2) | (Gq << 4) | (Gq << 6), 0xf, 0xf, false));
+}
+template <int G>
+__device__ __forceinline__ void bcast_roles(float v, float (&out)[G])
+{
+    if constexpr (G == 1) {
+        out[0] = v;
+    } else if constexpr (G == 2) {
+        out[0] = quad_bcast<0>(v);
+        out[1] = quad_bcast<1>(v);
+    } else {
+        out[0] = quad_bcast<0>(v);
+        out[1] = quad_bcast<1>(v);
+        out[2] = quad_bcast<2>(v);
+        out[3] = quad_bcast<3>(v);
     }
-    __device__ __forceinline__ void raise(float b)
-    {
-        if (b > mx + kLazy || mx == -INFINITY) {
-            const float sc = __expf(mx - b);  // mx = -inf gives 0
-            den *= sc;
-#pragma unroll
-            for (int i = 0; i < NK * 8; ++i) acc[i] *= sc;
-            mx = b;
-        }
-    }
-};
+}
 
+// Lane layout of one 16-row step (lane = 16 L + n):
+//   A operand  : lane (n, L) loads row r0 + n, 16-byte chunks L, L+4, ...         (stored rows)
+//   B operand  : lane (n, L) holds the vector of column role(n), same chunks       (queries / evicted key)
+//   result c[r]: <row r0 + 4L + r, vector role(n)>, r = 0..3
+//   value rows : lane (n, L) loads chunk n of row r0 + 4L + u for u = 0..3 (one full row per 16 lanes),
+//                so the weight it needs is its own row-L register e[u] of the lane holding that query
+//                (same quad), and it owns 8 output columns per query.
 template <int NK, int G, bool UPD, bool ATT>
 __device__ __forceinline__ void token_step_mfma(const State &st, const size_t sid, const char *krow, const char *vrow,
                                                 const char *qrows, float *outrows, const int64_t n_seen, int &m,
                                                 double &mu, SmemMfma<NK, G> &sm)
 {
-    constexpr int LPR = 4 * NK;          // lanes per row in the plain row layout (copies, norms)
+    constexpr int CPR = 4 * NK;                    // 16-byte chunks per row
+    constexpr int LPR = CPR;                       // lanes per row in the plain row layout (copies, norms)
     constexpr int RPW = 64 / LPR, RPB = RPW * kWaves;
     constexpr size_t ROWB = (size_t)NK * 64;
     constexpr int D = NK * 32;
-    constexpr bool KSEP = UPD && ATT && G == 4;   // four queries fill the replicated rows: the key gets its own MFMA
-    constexpr int KROW = ATT ? G : 0;             // A row (mod 4) that carries the evicted key otherwise
-    constexpr int KIDX = KSEP ? 0 : (KROW & 3);   // result register of the key's dot product
+    constexpr int VL = CPR > 16 ? CPR / 16 : 1;    // value loads per row per lane (d = 256: 2)
+    constexpr int RPLD = CPR < 16 ? 16 / CPR : 1;  // value rows per 16-lane load (d = 64: 2)
+    constexpr int NVL = 4 / RPLD;                  // value row-steps per 16-row group
+    constexpr int ACC = 8 * VL;                    // output columns per query per lane
+    constexpr int NC = G == 1 ? 2 : (G == 2 ? 4 : 8);  // column roles in the center pass: G queries + the key
+    constexpr int KR = ATT ? G : 0;                // column role of the evicted key in the center pass
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int col = lane % LPR, sub = lane / LPR;   // plain row layout
+    const int col = lane % LPR, sub = lane / LPR;  // plain row layout
     const int grp = wave * RPW + sub;
-    const int n16 = lane & 15, L = lane >> 4;        // MFMA layout: row n16 of a 16-row group, K slice L
+    const int n16 = lane & 15, L = lane >> 4;
+    const int vchunk = RPLD == 2 ? (n16 & (CPR - 1)) : n16;   // value chunk (+16 per extra load)
+    const int vrsub = RPLD == 2 ? (n16 / CPR) : 0;             // which of the RPLD rows of a value load
 
     char *const X = st.X + sid * (size_t)st.Mcap * ROWB;
-    int32_t *const cnt = st.cnt + sid * (size_t)st.Mcap;
-    float *const xn = st.xn + sid * (size_t)st.Mcap;
+    int32_t *const cnt = st.cnt + sid * (size_t)st.McapS;
+    float *const xn = st.xn + sid * (size_t)st.McapS;
     char *const Ks = st.Ks + sid * (size_t)st.s * ROWB;
     char *const Vs = st.Vs + sid * (size_t)st.s * ROWB;
     char *const Kw = st.Kw + sid * (size_t)st.w * ROWB;
     char *const Vw = st.Vw + sid * (size_t)st.w * ROWB;
 
-    // ---- A operands: queries in rows 4L'+r (r < G), the evicted key in row KROW (or its own operand)
-    const int arow = n16 & 3;
-    uint4 Aq[NK], Ak[KSEP ? NK : 1];
+    // ---- B operand of the center pass: queries in column roles 0..G-1, evicted key in role KR
+    const int rc = n16 % NC;
+    const bool qrole_c = ATT && rc < G;
+    const bool krole_c = UPD && rc == KR;
+    uint4 Bc[NK];
 #pragma unroll
-    for (int kk = 0; kk < NK; ++kk) Aq[kk] = make_uint4(0, 0, 0, 0);
-    if constexpr (KSEP) {
-#pragma unroll
-        for (int kk = 0; kk < NK; ++kk) Ak[kk] = make_uint4(0, 0, 0, 0);
-    }
+    for (int kk = 0; kk < NK; ++kk) Bc[kk] = make_uint4(0, 0, 0, 0);
     if constexpr (ATT) {
-        if (arow < G) {
+        if (qrole_c) {
 #pragma unroll
-            for (int kk = 0; kk < NK; ++kk) Aq[kk] = ld16(qrows + (size_t)arow * ROWB + (L + 4 * kk) * 16);
+            for (int kk = 0; kk < NK; ++kk) Bc[kk] = ld16(qrows + (size_t)rc * ROWB + (L + 4 * kk) * 16);
         }
     }
 
@@ -231,13 +220,9 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
         if (evict) {
             ek = ld16(esk + col * 16);
             ev = ld16(esv + col * 16);
-            if (KSEP ? arow == 0 : arow == KROW) {
+            if (krole_c) {
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) {
-                    const uint4 t = ld16(esk + (L + 4 * kk) * 16);
-                    if constexpr (KSEP) Ak[kk] = t;
-                    else Aq[kk] = t;
-                }
+                for (int kk = 0; kk < NK; ++kk) Bc[kk] = ld16(esk + (L + 4 * kk) * 16);
             }
         }
         if (st.w > 0) {
@@ -267,9 +252,8 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
         vn = (float)group_sum<LPR>(b);
     }
 
-    PartialM<NK> part[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) part[g].init();
+    // online softmax state of this lane's query role: lazily raised reference, denominator
+    float mx = -INFINITY, den = 0.f;
 
     // ---- one pass over the representatives, 16 rows per wavefront step, two steps in flight
     float b1 = INFINITY, b2 = INFINITY, nxmax = 0.f;
@@ -277,48 +261,57 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
     if ((UPD && evict) || ATT) {
         constexpr int U = 2;
         for (int r0 = wave * 16; r0 < m; r0 += 16 * kWaves * U) {
-            uint4 b[U][NK];
-            float nx[U], cf[U];
+            uint4 a[U][NK];
+            float4 nx4[U];
+            int4 cn4[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int r = r0 + u * 16 * kWaves + n16;
-                const int rr = r < m ? r : m - 1;
+                int base = r0 + u * 16 * kWaves;
+                if (base >= m) base = r0;                       // past the end: repeat a valid group (masked below)
+                const int rr = base + n16 < m ? base + n16 : m - 1;
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) b[u][kk] = ld16(X + (size_t)rr * ROWB + (L + 4 * kk) * 16);
-                nx[u] = UPD ? xn[rr] : 0.f;
-                cf[u] = ATT ? (float)cnt[rr] : 0.f;
+                for (int kk = 0; kk < NK; ++kk) a[u][kk] = ld16(X + (size_t)rr * ROWB + (L + 4 * kk) * 16);
+                if constexpr (UPD) nx4[u] = *reinterpret_cast<const float4 *>(xn + base + 4 * L);
+                if constexpr (ATT) cn4[u] = *reinterpret_cast<const int4 *>(cnt + base + 4 * L);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int r = r0 + u * 16 * kWaves + n16;
-                const bool valid = r < m;
-                floatx4_t c = {0.f, 0.f, 0.f, 0.f}, ck = {0.f, 0.f, 0.f, 0.f};
+                const int base = r0 + u * 16 * kWaves;
+                floatx4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(Aq[kk], b[u][kk], c);
-                if constexpr (KSEP) {
+                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(a[u][kk], Bc[kk], c);
+                const int row0 = base + 4 * L;   // rows of this lane's four results
+                if constexpr (ATT) {
+                    if (qrole_c && row0 < m) {
+                        const float cf[4] = {(float)cn4[u].x, (float)cn4[u].y, (float)cn4[u].z, (float)cn4[u].w};
+                        float mc = c[0];
 #pragma unroll
-                    for (int kk = 0; kk < NK; ++kk) ck = mfma_bf16(Ak[kk], b[u][kk], ck);
-                }
-                if constexpr (UPD) {
-                    if (evict && valid) {
-                        const float dotk = KSEP ? ck[KIDX] : c[KIDX];
-                        const float dt = fmaf(-2.f, dotk, nx[u] + nk);
-                        if (dt < b1) {
-                            b2 = b1;
-                            b1 = dt;
-                            i1 = r;
-                        } else if (dt < b2) {
-                            b2 = dt;
+                        for (int r = 1; r < 4; ++r) mc = (row0 + r < m) ? fmaxf(mc, c[r]) : mc;
+                        if (mc > mx + kLazy || mx == -INFINITY) {
+                            den *= __expf(mx - mc);
+                            mx = mc;
                         }
-                        nxmax = fmaxf(nxmax, nx[u]);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (row0 + r < m) den = fmaf(cf[r], __expf(c[r] - mx), den);
                     }
                 }
-                if constexpr (ATT) {
-                    if (valid) {
+                if constexpr (UPD) {
+                    if (krole_c && evict) {
+                        const float nxr[4] = {nx4[u].x, nx4[u].y, nx4[u].z, nx4[u].w};
 #pragma unroll
-                        for (int g = 0; g < G; ++g) {
-                            part[g].raise(c[g]);
-                            part[g].den = fmaf(cf[u], __expf(c[g] - part[g].mx), part[g].den);
+                        for (int r = 0; r < 4; ++r) {
+                            if (row0 + r < m) {
+                                const float dt = fmaf(-2.f, c[r], nxr[r] + nk);
+                                if (dt < b1) {
+                                    b2 = b1;
+                                    b1 = dt;
+                                    i1 = row0 + r;
+                                } else if (dt < b2) {
+                                    b2 = dt;
+                                }
+                                nxmax = fmaxf(nxmax, nxr[r]);
+                            }
                         }
                     }
                 }
@@ -328,9 +321,9 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
 
     if constexpr (UPD) {
         if (evict) {
-            // ---- best / runner-up of the approximate distances over the workgroup
+            // ---- best / runner-up of the approximate distances: over the four lane rows, then the wavefronts
 #pragma unroll
-            for (int o = 1; o < 16; o <<= 1) {
+            for (int o = 16; o < 64; o <<= 1) {
                 const float ob1 = __shfl_xor(b1, o), ob2 = __shfl_xor(b2, o);
                 const int oi1 = __shfl_xor(i1, o);
                 if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
@@ -342,7 +335,7 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
                 }
                 nxmax = fmaxf(nxmax, __shfl_xor(nxmax, o));
             }
-            if (lane == 0) {
+            if (lane == KR) {   // a key-role lane of lane row 0
                 sm.wb1[wave] = b1;
                 sm.wb2[wave] = b2;
                 sm.wi1[wave] = i1;
@@ -438,8 +431,8 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
                     st16(Ks + (size_t)j * ROWB + col * 16, ek);
                     st16(Vs + (size_t)j * ROWB + col * 16, ev);
                     if (col == 0) {
-                        st.sidx[sid * (size_t)st.s + j] = (int32_t)etoken;
-                        st.svn[sid * (size_t)st.s + j] = vn;
+                        st.sidx[sid * (size_t)st.sS + j] = (int32_t)etoken;
+                        st.svn[sid * (size_t)st.sS + j] = vn;
                     }
                 }
                 __syncthreads();
@@ -451,101 +444,137 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
 
     if constexpr (ATT) {
         const bool extra = UPD && evict;
-        // ---- sampled pairs: numerator terms  mu/(s ||v_j||^2) e^{<q,k_j>} v_j
-        if (n_evicted_after > 0) {
-            const float wmul = (float)(mu / (double)st.s);
-            const float *svn = st.svn + sid * (size_t)st.s;
-            for (int r0 = wave * 16; r0 < st.s; r0 += 16 * kWaves) {
-                const int r = r0 + n16;
-                const bool valid = r < st.s;
-                const int rr = valid ? r : st.s - 1;
-                uint4 bk[NK], bv[NK];
+        // ---- hand the normaliser state from the center-pass column roles to the query roles n % G
+        {
+            const int src = (lane & 48) | (n16 % G);
+            mx = __shfl(mx, src);
+            den = __shfl(den, src);
+        }
+        uint4 Bq[NK];
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) bk[kk] = ld16(Ks + (size_t)rr * ROWB + (L + 4 * kk) * 16);
+        for (int kk = 0; kk < NK; ++kk) Bq[kk] = ld16(qrows + (size_t)(n16 % G) * ROWB + (L + 4 * kk) * 16);
+        float acc[G][ACC];
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) bv[kk] = ld16(Vs + (size_t)rr * ROWB + (L + 4 * kk) * 16);
-                const float vnj = svn[rr];
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int i = 0; i < ACC; ++i) acc[g][i] = 0.f;
+
+        // one 16-row group of (key rows, value rows): scores on the matrix cores, weights per lane row,
+        // value rows accumulated into the lane's output columns
+        auto scan = [&](const char *Kb, const char *Vb, const float *vnorm, const float wmul, const int nrows,
+                        const bool to_den) {
+            for (int r0 = wave * 16; r0 < nrows; r0 += 16 * kWaves) {
+                const int rr = r0 + n16 < nrows ? r0 + n16 : nrows - 1;
+                uint4 a[NK], bv[NVL][VL];
+#pragma unroll
+                for (int kk = 0; kk < NK; ++kk) a[kk] = ld16(Kb + (size_t)rr * ROWB + (L + 4 * kk) * 16);
+#pragma unroll
+                for (int u = 0; u < NVL; ++u) {
+                    const int vr = r0 + 4 * L + u * RPLD + vrsub;
+                    const int vrr = vr < nrows ? vr : nrows - 1;
+#pragma unroll
+                    for (int vl = 0; vl < VL; ++vl) bv[u][vl] = ld16(Vb + (size_t)vrr * ROWB + (vchunk + 16 * vl) * 16);
+                }
+                float wg[4] = {1.f, 1.f, 1.f, 1.f};
+                if (vnorm != nullptr) {
+                    const float4 v4 = *reinterpret_cast<const float4 *>(vnorm + r0 + 4 * L);
+                    const float vv[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) wg[r] = vv[r] > 0.f ? wmul * __builtin_amdgcn_rcpf(vv[r]) : 0.f;
+                }
                 floatx4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(Aq[kk], bk[kk], c);
-                const float wgt = (valid && vnj > 0.f) ? wmul / vnj : 0.f;
+                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(a[kk], Bq[kk], c);
+                const int row0 = r0 + 4 * L;
+                float scale = 1.f;
+                float e[4] = {0.f, 0.f, 0.f, 0.f};
+                if (row0 < nrows) {
+                    float mc = c[0];
 #pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    if (valid) part[g].raise(c[g]);
-                    const float e = valid ? wgt * __expf(c[g] - part[g].mx) : 0.f;
+                    for (int r = 1; r < 4; ++r) mc = (row0 + r < nrows) ? fmaxf(mc, c[r]) : mc;
+                    if (mc > mx + kLazy || mx == -INFINITY) {
+                        scale = __expf(mx - mc);   // mx = -inf gives 0
+                        den *= scale;
+                        mx = mc;
+                    }
 #pragma unroll
-                    for (int kk = 0; kk < NK; ++kk) {
+                    for (int r = 0; r < 4; ++r)
+                        if (row0 + r < nrows) e[r] = wg[r] * __expf(c[r] - mx);
+                    if (to_den) den += (e[0] + e[1]) + (e[2] + e[3]);
+                }
+                if (__any(scale != 1.f)) {
+                    float sg[G];
+                    bcast_roles<G>(scale, sg);
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+#pragma unroll
+                        for (int i = 0; i < ACC; ++i) acc[g][i] *= sg[g];
+                }
+#pragma unroll
+                for (int u = 0; u < NVL; ++u) {
+                    float esel = e[u * RPLD];
+                    if constexpr (RPLD == 2) esel = vrsub ? e[u * RPLD + 1] : esel;
+                    float eg[G];
+                    bcast_roles<G>(esel, eg);
+#pragma unroll
+                    for (int vl = 0; vl < VL; ++vl) {
                         float vf[8];
-                        unpack<true>(bv[kk], vf);
+                        unpack<true>(bv[u][vl], vf);
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) part[g].acc[kk * 8 + i] = fmaf(e, vf[i], part[g].acc[kk * 8 + i]);
+                        for (int g = 0; g < G; ++g)
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) acc[g][vl * 8 + i] = fmaf(eg[g], vf[i], acc[g][vl * 8 + i]);
                     }
                 }
             }
-        }
-        // ---- window: exact terms in numerator and normaliser
+        };
+        // sampled pairs: numerator terms  mu/(s ||v_j||^2) e^{<q,k_j>} v_j
+        if (n_evicted_after > 0)
+            scan(Ks, Vs, st.svn + sid * (size_t)st.sS, (float)(mu / (double)st.s), st.s, false);
+        // window: exact terms in numerator and normaliser
         const int fill = (int)(n_after < st.w ? n_after : st.w);
-        for (int r0 = wave * 16; r0 < fill; r0 += 16 * kWaves) {
-            const int r = r0 + n16;
-            const bool valid = r < fill;
-            const int rr = valid ? r : fill - 1;
-            uint4 bk[NK], bv[NK];
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk) bk[kk] = ld16(Kw + (size_t)rr * ROWB + (L + 4 * kk) * 16);
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk) bv[kk] = ld16(Vw + (size_t)rr * ROWB + (L + 4 * kk) * 16);
-            floatx4_t c = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(Aq[kk], bk[kk], c);
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                if (valid) part[g].raise(c[g]);
-                const float e = valid ? __expf(c[g] - part[g].mx) : 0.f;
-                part[g].den += e;
-#pragma unroll
-                for (int kk = 0; kk < NK; ++kk) {
-                    float vf[8];
-                    unpack<true>(bv[kk], vf);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) part[g].acc[kk * 8 + i] = fmaf(e, vf[i], part[g].acc[kk * 8 + i]);
-                }
-            }
+        scan(Kw, Vw, nullptr, 1.f, fill, true);
+
+        // ---- merge the four lane rows of the wavefront, then the wavefronts through LDS
+        float M = fmaxf(mx, __shfl_xor(mx, 16));
+        M = fmaxf(M, __shfl_xor(M, 32));
+        const float f = (mx == -INFINITY) ? 0.f : __expf(mx - M);
+        float dsum = den * f;
+        dsum += __shfl_xor(dsum, 16);
+        dsum += __shfl_xor(dsum, 32);
+        if (lane < G) {   // lane g of lane row 0 has query role g
+            sm.wmx[wave][lane] = M;
+            sm.wden[wave][lane] = dsum;
         }
-        // ---- merge the 16 lanes of each DPP row, then the wavefronts through LDS
+        float fg[G];
+        bcast_roles<G>(f, fg);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const float M = row_max16(part[g].mx);
-            const float sc = (part[g].mx == -INFINITY) ? 0.f : __expf(part[g].mx - M);
-            const float den = row_sum16(part[g].den * sc);
-            if (lane == 0) {
-                sm.wmx[wave][g] = M;
-                sm.wden[wave][g] = den;
-            }
 #pragma unroll
-            for (int kk = 0; kk < NK; ++kk) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float a = row_sum16(part[g].acc[kk * 8 + i] * sc);
-                    if (n16 == 0) sm.wacc[wave][g][(L + 4 * kk) * 8 + i] = a;
-                }
+            for (int i = 0; i < ACC; ++i) {
+                float t = acc[g][i] * fg[g];
+                t += __shfl_xor(t, 16);
+                t += __shfl_xor(t, 32);
+                if constexpr (RPLD == 2) t += __shfl_xor(t, 8);
+                if (L == 0 && n16 < CPR) sm.wacc[wave][g][(vchunk + 16 * (i / 8)) * 8 + (i % 8)] = t;
             }
         }
         __syncthreads();
         for (int i = tid; i < G * D; i += kWG) {
             const int g = i / D, c = i % D;
             const float bx = extra ? sm.bx[g] : -INFINITY;
-            float M = bx;
+            float Mx = bx;
 #pragma unroll
-            for (int wv = 0; wv < kWaves; ++wv) M = fmaxf(M, sm.wmx[wv][g]);
-            float den = extra ? __expf(bx - M) : 0.f, num = 0.f;
+            for (int wv = 0; wv < kWaves; ++wv) Mx = fmaxf(Mx, sm.wmx[wv][g]);
+            float dn = extra ? __expf(bx - Mx) : 0.f, num = 0.f;
 #pragma unroll
             for (int wv = 0; wv < kWaves; ++wv) {
                 const float wm = sm.wmx[wv][g];
-                const float sc = (wm == -INFINITY) ? 0.f : __expf(wm - M);
-                den = fmaf(sm.wden[wv][g], sc, den);
+                const float sc = (wm == -INFINITY) ? 0.f : __expf(wm - Mx);
+                dn = fmaf(sm.wden[wv][g], sc, dn);
                 num = fmaf(sm.wacc[wv][g][c], sc, num);
             }
-            outrows[(size_t)g * D + c] = num / den;
+            outrows[(size_t)g * D + c] = num / dn;
         }
     }
     __syncthreads();  // LDS and state are reusable by the next token
