@@ -1,0 +1,405 @@
+// Chunked prefix ingest for bf16 rows on gfx950.
+//
+// A stream's tokens must be clustered in order (the greedy rule is order
+// dependent), but the arithmetic of 64 consecutive tokens can be batched:
+//   1. distances of the 64 tokens to all representatives that exist at the
+//      start of the chunk are one dense (m x 64 x d) contraction on the matrix
+//      cores (representatives as the A operand, the 64 token keys as four B
+//      operands); every lane tracks best / runner-up for its token;
+//   2. distances between the 64 tokens themselves (one more 64 x 64 x d
+//      contraction) cover the representatives created inside the chunk;
+//   3. a resolve loop, one lane per token, replays the order: a token only
+//      sees the chunk's creators that precede it; the loop advances from one
+//      creation (or one ambiguous token) to the next, so it runs a few
+//      iterations per chunk once the table has filled;
+//   4. ambiguous decisions (gap or threshold distance within the error bound
+//      of the matrix-core distances) are re-evaluated exactly in double;
+//   5. the sampling coins of the 64 tokens are drawn per 4-slot block, the
+//      last accepting token of a slot wins (sequential overwrite semantics).
+// The window is handled by index arithmetic: the tokens that leave the window
+// during the call come first from the ring, then from the call's own input;
+// the ring is rewritten once at the end.
+#pragma once
+#include "subgen_mfma_device.hpp"
+
+namespace sg {
+
+constexpr int kChunkT = 64;  // tokens per chunk = one lane per token in the resolve loop
+
+template <int NK>
+struct SmemIngest {
+    alignas(16) float nk[kChunkT];
+    float vn[kChunkT], p[kChunkT];
+    float wb1[kWaves][kChunkT], wb2[kWaves][kChunkT];
+    int wi1[kWaves][kChunkT];
+    float wnx[kWaves];
+    float tt[kChunkT][kChunkT + 1];
+    double wbest[kWaves];
+    int widx[kWaves];
+};
+
+// merge candidate (d, idx) into best / runner-up; lower index wins exact ties of the approximate value
+__device__ __forceinline__ void cand_merge(float d, int idx, float &b1, int &i1, float &b2)
+{
+    if (d < b1 || (d == b1 && (uint32_t)idx < (uint32_t)i1)) {
+        b2 = b1;
+        b1 = d;
+        i1 = idx;
+    } else {
+        b2 = fminf(b2, d);
+    }
+}
+
+template <int NK>
+__global__ __launch_bounds__(kWG, 2) void ingest_mfma_kernel(const State st, const Call call)
+{
+    static_assert(kWaves == 4, "the chunk layout assumes four wavefronts per workgroup");
+    constexpr int T = kChunkT;
+    constexpr int CPR = 4 * NK, LPR = CPR;
+    constexpr int RPW = 64 / LPR, RPB = RPW * kWaves;
+    constexpr size_t ROWB = (size_t)NK * 64;
+    __shared__ SmemIngest<NK> sm;
+
+    const size_t sid = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane % LPR, sub = lane / LPR, grp = wave * RPW + sub;
+    const int n16 = lane & 15, L = lane >> 4;
+
+    char *const X = st.X + sid * (size_t)st.Mcap * ROWB;
+    int32_t *const cnt = st.cnt + sid * (size_t)st.McapS;
+    float *const xn = st.xn + sid * (size_t)st.McapS;
+    char *const Ks = st.Ks + sid * (size_t)st.s * ROWB;
+    char *const Vs = st.Vs + sid * (size_t)st.s * ROWB;
+    char *const Kw = st.Kw + sid * (size_t)st.w * ROWB;
+    char *const Vw = st.Vw + sid * (size_t)st.w * ROWB;
+    const char *const kin = call.K + sid * call.stream_stride;
+    const char *const vin = call.V + sid * call.stream_stride;
+
+    const int64_t n0 = call.n_seen, n = call.n_tokens, w = st.w;
+    // global indices [ge0, ge1) of the tokens that leave the window during this call
+    const int64_t ge0 = w == 0 ? n0 : (n0 > w ? n0 - w : 0);
+    int64_t ge1 = w == 0 ? n0 + n : n0 + n - w;
+    if (ge1 < ge0) ge1 = ge0;
+    auto krow_of = [&](int64_t ge) -> const char * {
+        return ge < n0 ? Kw + (size_t)(ge % w) * ROWB : kin + (ge - n0) * call.token_stride;
+    };
+    auto vrow_of = [&](int64_t ge) -> const char * {
+        return ge < n0 ? Vw + (size_t)(ge % w) * ROWB : vin + (ge - n0) * call.token_stride;
+    };
+
+    int m = st.m[sid];
+    double mu = st.mu[sid];
+    const float thr = (float)st.delta2;
+
+    for (int64_t c0 = ge0; c0 < ge1; c0 += T) {
+        const int nt = (int)(ge1 - c0 < T ? ge1 - c0 : T);
+        const int m0 = m;
+
+        // ---- squared norms of the chunk's keys and values (double, exact products), one token per lane group
+        for (int j = grp; j < T; j += RPB) {
+            const int jj = j < nt ? j : nt - 1;
+            float kf[8], vf[8];
+            unpack<true>(ld16(krow_of(c0 + jj) + col * 16), kf);
+            unpack<true>(ld16(vrow_of(c0 + jj) + col * 16), vf);
+            double a = 0.0, b = 0.0;
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                a = fma((double)kf[v], (double)kf[v], a);
+                b = fma((double)vf[v], (double)vf[v], b);
+            }
+            a = group_sum<LPR>(a);
+            b = group_sum<LPR>(b);
+            if (col == 0) {
+                sm.nk[j] = (float)a;
+                sm.vn[j] = (float)b;
+            }
+        }
+        // ---- the 64 keys as four B operands (token 16 ts + n in column n)
+        uint4 Bt[4][NK];
+#pragma unroll
+        for (int ts = 0; ts < 4; ++ts) {
+            const int j = 16 * ts + n16;
+            const char *kp = krow_of(c0 + (j < nt ? j : nt - 1));
+#pragma unroll
+            for (int kk = 0; kk < NK; ++kk) Bt[ts][kk] = ld16(kp + (L + 4 * kk) * 16);
+        }
+        __syncthreads();
+        float nkt[4];
+#pragma unroll
+        for (int ts = 0; ts < 4; ++ts) nkt[ts] = sm.nk[16 * ts + n16];
+
+        // ---- token-token distances: wavefront `wave` takes rows 16 wave .. 16 wave + 15
+        {
+            const float4 nkr = *reinterpret_cast<const float4 *>(&sm.nk[16 * wave + 4 * L]);
+            const float nkrow[4] = {nkr.x, nkr.y, nkr.z, nkr.w};
+#pragma unroll
+            for (int ts = 0; ts < 4; ++ts) {
+                floatx4_t c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < NK; ++kk) {
+                    // rows of the A operand = tokens 16 wave + n: the same registers as B set `wave`
+                    const uint4 arow = wave == 0 ? Bt[0][kk] : wave == 1 ? Bt[1][kk] : wave == 2 ? Bt[2][kk] : Bt[3][kk];
+                    c = mfma_bf16(arow, Bt[ts][kk], c);
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    sm.tt[16 * wave + 4 * L + r][16 * ts + n16] = fmaf(-2.f, c[r], nkrow[r] + nkt[ts]);
+            }
+        }
+
+        // ---- distances to the representatives that exist at the start of the chunk
+        float b1[4], b2[4], nxmax = 0.f;
+        int i1[4];
+#pragma unroll
+        for (int ts = 0; ts < 4; ++ts) {
+            b1[ts] = INFINITY;
+            b2[ts] = INFINITY;
+            i1[ts] = -1;
+        }
+        {
+            uint4 a[NK];
+            float4 nx4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            int r0 = wave * 16;
+            if (r0 < m0) {
+                const int rr = r0 + n16 < m0 ? r0 + n16 : m0 - 1;
+#pragma unroll
+                for (int kk = 0; kk < NK; ++kk) a[kk] = ld16(X + (size_t)rr * ROWB + (L + 4 * kk) * 16);
+                nx4 = *reinterpret_cast<const float4 *>(xn + r0 + 4 * L);
+            }
+            for (; r0 < m0; r0 += 16 * kWaves) {
+                // prefetch the next group while this one is on the matrix cores
+                uint4 an[NK];
+                float4 nxn = make_float4(0.f, 0.f, 0.f, 0.f);
+                const int rn = r0 + 16 * kWaves;
+                if (rn < m0) {
+                    const int rr = rn + n16 < m0 ? rn + n16 : m0 - 1;
+#pragma unroll
+                    for (int kk = 0; kk < NK; ++kk) an[kk] = ld16(X + (size_t)rr * ROWB + (L + 4 * kk) * 16);
+                    nxn = *reinterpret_cast<const float4 *>(xn + rn + 4 * L);
+                }
+                const float nxr[4] = {nx4.x, nx4.y, nx4.z, nx4.w};
+                const int row0 = r0 + 4 * L;
+#pragma unroll
+                for (int ts = 0; ts < 4; ++ts) {
+                    floatx4_t c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(a[kk], Bt[ts][kk], c);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if (row0 + r < m0) {
+                            const float dt = fmaf(-2.f, c[r], nxr[r] + nkt[ts]);
+                            if (dt < b1[ts]) {
+                                b2[ts] = b1[ts];
+                                b1[ts] = dt;
+                                i1[ts] = row0 + r;
+                            } else if (dt < b2[ts]) {
+                                b2[ts] = dt;
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (row0 + r < m0) nxmax = fmaxf(nxmax, nxr[r]);
+                if (rn < m0) {
+#pragma unroll
+                    for (int kk = 0; kk < NK; ++kk) a[kk] = an[kk];
+                    nx4 = nxn;
+                }
+            }
+        }
+#pragma unroll
+        for (int ts = 0; ts < 4; ++ts) {
+#pragma unroll
+            for (int o = 16; o < 64; o <<= 1) {
+                const float ob1 = __shfl_xor(b1[ts], o), ob2 = __shfl_xor(b2[ts], o);
+                const int oi1 = __shfl_xor(i1[ts], o);
+                if (ob1 < b1[ts] || (ob1 == b1[ts] && (uint32_t)oi1 < (uint32_t)i1[ts])) {
+                    b2[ts] = fminf(b1[ts], ob2);
+                    b1[ts] = ob1;
+                    i1[ts] = oi1;
+                } else {
+                    b2[ts] = fminf(b2[ts], ob1);
+                }
+            }
+            if (L == 0) {
+                sm.wb1[wave][16 * ts + n16] = b1[ts];
+                sm.wb2[wave][16 * ts + n16] = b2[ts];
+                sm.wi1[wave][16 * ts + n16] = i1[ts];
+            }
+        }
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) nxmax = fmaxf(nxmax, __shfl_xor(nxmax, o));
+        if (lane == 0) sm.wnx[wave] = nxmax;
+        __syncthreads();
+
+        // ---- resolve in token order: lane j = token j of the chunk; every wavefront runs the same loop
+        //      (same LDS inputs, same results), wavefront 0 applies the side effects
+        const int j = lane;
+        const bool valid = j < nt;
+        float ob1 = sm.wb1[0][j], ob2 = sm.wb2[0][j];
+        int oi1 = sm.wi1[0][j];
+        float nxold = sm.wnx[0];
+#pragma unroll
+        for (int wv = 1; wv < kWaves; ++wv) {
+            const float x1 = sm.wb1[wv][j], x2 = sm.wb2[wv][j];
+            const int xi = sm.wi1[wv][j];
+            if (x1 < ob1 || (x1 == ob1 && (uint32_t)xi < (uint32_t)oi1)) {
+                ob2 = fminf(ob1, x2);
+                ob1 = x1;
+                oi1 = xi;
+            } else {
+                ob2 = fminf(ob2, x1);
+            }
+            nxold = fmaxf(nxold, sm.wnx[wv]);
+        }
+        const float nkj = sm.nk[j];
+        uint64_t cmask = 0;   // tokens of this chunk that opened a cluster (uniform)
+        int done = 0;         // tokens below `done` are final (uniform)
+        const uint64_t below = j == 0 ? 0ull : (~0ull >> (64 - j));
+        while (done < nt) {
+            float c1 = ob1, c2 = ob2, nxl = nxold;
+            int ci = oi1;
+            uint64_t rest = cmask;
+            while (rest) {   // uniform loop over the creators; a lane only sees those before it
+                const int l = __builtin_ctzll(rest);
+                rest &= rest - 1;
+                if (l < j) {
+                    cand_merge(sm.tt[l][j], m0 + __builtin_popcountll(cmask & (l == 0 ? 0ull : (~0ull >> (64 - l)))), c1,
+                               ci, c2);
+                    nxl = fmaxf(nxl, sm.nk[l]);
+                }
+            }
+            const int mcur = m0 + __builtin_popcountll(cmask & below);   // clusters that exist when token j arrives
+            const float emax = kDistEps * (nxl + nkj);
+            const bool live = valid && j >= done;
+            const bool amb = mcur > 0 && (!(c2 - c1 > 2.f * emax) || !(fabsf(c1 - thr) > emax + 1e-6f * thr));
+            const bool join = mcur > 0 && c1 <= thr;
+            const bool forced = !join && mcur > 0 && mcur >= st.Mcap;
+            const bool event = live && (amb || (!join && !forced));
+            const uint64_t evmask = __ballot(event);
+            const int e = evmask ? __builtin_ctzll(evmask) : nt;   // first creation / ambiguous token
+            // tokens before the event are final: they join (or are force-joined to) their nearest cluster
+            if (wave == 0 && live && j < e) {
+                atomicAdd(&cnt[ci], 1);
+                if (forced) atomicOr(&st.flags[sid], 1u);
+                if (st.assign != nullptr && c0 + j < st.assign_cap) st.assign[sid * (size_t)st.assign_cap + c0 + j] = ci;
+            }
+            if (e >= nt) break;
+            const bool e_amb = (__ballot(amb && live) >> e) & 1ull;
+            const int me = m0 + __builtin_popcountll(cmask);   // clusters that exist when token e arrives
+            bool create = true;
+            int target = me;
+            if (e_amb) {
+                __syncthreads();   // rows of this chunk's creators are visible to every wavefront
+                double best;
+                int bidx;
+                exact_nearest<LPR>(X, me, ld16(krow_of(c0 + e) + col * 16), sm.wbest, sm.widx, best, bidx);
+                const bool ejoin = bidx >= 0 && best <= st.delta2;
+                const bool eforced = !ejoin && me > 0 && me >= st.Mcap;
+                create = !ejoin && !eforced;
+                if (!create) {
+                    target = bidx;
+                    if (tid == 0) {
+                        atomicAdd(&cnt[bidx], 1);
+                        if (eforced) atomicOr(&st.flags[sid], 1u);
+                    }
+                }
+            }
+            if (create) {
+                if (tid < LPR) st16(X + (size_t)me * ROWB + tid * 16, ld16(krow_of(c0 + e) + tid * 16));
+                if (tid == 0) {
+                    atomicAdd(&cnt[me], 1);
+                    xn[me] = sm.nk[e];
+                }
+                cmask |= 1ull << e;
+            }
+            if (tid == 0 && st.assign != nullptr && c0 + e < st.assign_cap)
+                st.assign[sid * (size_t)st.assign_cap + c0 + e] = target;
+            done = e + 1;
+        }
+        m = m0 + __builtin_popcountll(cmask);
+
+        // ---- sampling: p_j from the running mu (sequential double adds, token order), then the coins
+        {
+            double muj = mu;
+            for (int l = 0; l < nt; ++l) {
+                const double v = (double)sm.vn[l];
+                if (l < j) muj += v;
+            }
+            const float vnj = sm.vn[j];
+            float pj;
+            if (muj == 0.0) pj = 1.f;
+            else if (vnj == 0.f) pj = 0.f;
+            else pj = (float)((double)vnj / (muj + (double)vnj));
+            if (wave == 0) sm.p[j] = valid ? pj : 0.f;
+            const double mend = muj + (double)vnj;
+            mu = __shfl(mend, nt - 1);
+        }
+        __syncthreads();
+        {
+            const int nblk = (st.s + 3) >> 2;
+            int nsplit = 1;   // token sub-ranges per 4-slot block, so that every lane has coins to draw
+            while (nsplit < 16 && nblk * nsplit * 2 <= kWG) nsplit *= 2;
+            const int per = T / nsplit;
+            for (int item = tid; item < ((nblk * nsplit + kWG - 1) / kWG) * kWG; item += kWG) {
+                const int blk = item / nsplit, part = item % nsplit;
+                int last[4] = {-1, -1, -1, -1};
+                if (blk < nblk) {
+                    for (int jj = part * per; jj < (part + 1) * per && jj < nt; ++jj) {
+                        const float pj = sm.p[jj];
+                        if (pj > 0.f) {
+                            const uint64_t ge = (uint64_t)(c0 + jj);
+                            uint32_t r[4];
+                            philox4x32_10((uint32_t)blk, (uint32_t)ge, (uint32_t)(ge >> 32), (uint32_t)sid, st.seed_lo,
+                                          st.seed_hi, r);
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if ((float)(r[i] >> 8) * (1.0f / 16777216.0f) < pj) last[i] = jj;
+                        }
+                    }
+                }
+                // later tokens overwrite earlier ones: the largest token index over the sub-ranges wins
+                for (int o = 1; o < nsplit; o <<= 1) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) last[i] = max(last[i], __shfl_xor(last[i], o));
+                }
+                if (blk < nblk) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int slot = blk * 4 + i;
+                        const int owner = nsplit >= 4 ? i : (i % nsplit);   // spread the row copies over the lanes
+                        if (part == owner && last[i] >= 0 && slot < st.s) {
+                            const char *ks = krow_of(c0 + last[i]), *vs = vrow_of(c0 + last[i]);
+#pragma unroll
+                            for (int ch = 0; ch < CPR; ++ch) {
+                                st16(Ks + (size_t)slot * ROWB + ch * 16, ld16(ks + ch * 16));
+                                st16(Vs + (size_t)slot * ROWB + ch * 16, ld16(vs + ch * 16));
+                            }
+                            st.sidx[sid * (size_t)st.sS + slot] = (int32_t)(c0 + last[i]);
+                            st.svn[sid * (size_t)st.sS + slot] = sm.vn[last[i]];
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();   // LDS is reused by the next chunk; new rows are visible
+    }
+
+    // ---- the ring ends up holding the last min(n, w) tokens of the call
+    if (w > 0) {
+        __syncthreads();
+        const int64_t tfirst = n > w ? n - w : 0;
+        for (int64_t t = tfirst + grp; t < n; t += RPB) {
+            const size_t slot = (size_t)((n0 + t) % w);
+            st16(Kw + slot * ROWB + col * 16, ld16(kin + t * call.token_stride + col * 16));
+            st16(Vw + slot * ROWB + col * 16, ld16(vin + t * call.token_stride + col * 16));
+        }
+    }
+    if (tid == 0) {
+        st.m[sid] = m;
+        st.mu[sid] = mu;
+    }
+}
+
+}  // namespace sg

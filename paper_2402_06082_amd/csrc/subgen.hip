@@ -13,6 +13,7 @@
 #include "exact_device.hpp"
 #include "subgen_device.hpp"
 #include "subgen_mfma_device.hpp"
+#include "ingest_mfma_device.hpp"
 
 using sg::Call;
 using sg::State;
@@ -325,7 +326,11 @@ int subgen_ingest_prefix(subgen_ctx *c, const void *K, const void *V, int64_t n,
         call.n_tokens = (n - t0 < kChunk) ? n - t0 : kChunk;
         call.n_seen = c->n_seen;
         const dim3 grid((unsigned)c->S);
-        if (c->dtype == SUBGEN_BF16) launch_ingest_lpr<true>(c->LPR, grid, c->stream, c->st, call);
+        if (c->mfma && c->LPR == 8)
+            hipLaunchKernelGGL((sg::ingest_mfma_kernel<2>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+        else if (c->mfma && c->LPR == 16)
+            hipLaunchKernelGGL((sg::ingest_mfma_kernel<4>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+        else if (c->dtype == SUBGEN_BF16) launch_ingest_lpr<true>(c->LPR, grid, c->stream, c->st, call);
         else launch_ingest_lpr<false>(c->LPR, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail_hip(c, e);

@@ -314,3 +314,10 @@ def test_matrix_core_path_exact_decisions_on_lattice_keys(g):
         thr, gap = o.margins()
         assert (thr == 0).sum() > 5 and (gap == 0).sum() > 5
     assert rel_l2(outs.cpu().numpy(), ref).max() <= REL_L2_TOL
+    # the chunked prefix ingest takes the same decisions on the same data (ragged chunks)
+    ing = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, q_per_stream=g, assign_log_tokens=n, seed=2, device=DEV)
+    for lo, hi in [(0, 3), (3, 70), (70, 71), (71, 333), (333, n)]:
+        ing.ingest_prefix(K[:, lo:hi], V[:, lo:hi])
+    for sid in range(S):
+        assert state_tuple(ing, sid) == state_tuple(sg, sid)
+        assert np.array_equal(ing.export_state(sid).assign, sg.export_state(sid).assign)
