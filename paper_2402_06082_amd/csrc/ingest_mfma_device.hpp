@@ -51,7 +51,7 @@ __device__ __forceinline__ void cand_merge(float d, int idx, float &b1, int &i1,
 }
 
 template <int NK>
-__global__ __launch_bounds__(kWG, 2) void ingest_mfma_kernel(const State st, const Call call)
+__global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, const Call call)
 {
     static_assert(kWaves == 4, "the chunk layout assumes four wavefronts per workgroup");
     constexpr int T = kChunkT;
@@ -96,22 +96,33 @@ __global__ __launch_bounds__(kWG, 2) void ingest_mfma_kernel(const State st, con
         const int m0 = m;
 
         // ---- squared norms of the chunk's keys and values (double, exact products), one token per lane group
-        for (int j = grp; j < T; j += RPB) {
-            const int jj = j < nt ? j : nt - 1;
-            float kf[8], vf[8];
-            unpack<true>(ld16(krow_of(c0 + jj) + col * 16), kf);
-            unpack<true>(ld16(vrow_of(c0 + jj) + col * 16), vf);
-            double a = 0.0, b = 0.0;
+        {
+            constexpr int NP = T / RPB;   // passes of the lane groups over the 64 tokens
+            uint4 rk[NP], rv[NP];
 #pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                a = fma((double)kf[v], (double)kf[v], a);
-                b = fma((double)vf[v], (double)vf[v], b);
+            for (int it = 0; it < NP; ++it) {   // all row loads first
+                const int j = grp + it * RPB;
+                const int jj = j < nt ? j : nt - 1;
+                rk[it] = ld16(krow_of(c0 + jj) + col * 16);
+                rv[it] = ld16(vrow_of(c0 + jj) + col * 16);
             }
-            a = group_sum<LPR>(a);
-            b = group_sum<LPR>(b);
-            if (col == 0) {
-                sm.nk[j] = (float)a;
-                sm.vn[j] = (float)b;
+#pragma unroll
+            for (int it = 0; it < NP; ++it) {
+                float kf[8], vf[8];
+                unpack<true>(rk[it], kf);
+                unpack<true>(rv[it], vf);
+                double a = 0.0, b = 0.0;
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    a = fma((double)kf[v], (double)kf[v], a);
+                    b = fma((double)vf[v], (double)vf[v], b);
+                }
+                a = group_sum<LPR>(a);
+                b = group_sum<LPR>(b);
+                if (col == 0) {
+                    sm.nk[grp + it * RPB] = (float)a;
+                    sm.vn[grp + it * RPB] = (float)b;
+                }
             }
         }
         // ---- the 64 keys as four B operands (token 16 ts + n in column n)
@@ -128,23 +139,26 @@ __global__ __launch_bounds__(kWG, 2) void ingest_mfma_kernel(const State st, con
 #pragma unroll
         for (int ts = 0; ts < 4; ++ts) nkt[ts] = sm.nk[16 * ts + n16];
 
-        // ---- token-token distances: wavefront `wave` takes rows 16 wave .. 16 wave + 15
+        // ---- token-token distances: wavefront `wave` takes rows 16 wave .. 16 wave + 15 (its A operand is
+        //      B set `wave`; the branch keeps the register indices static)
         {
             const float4 nkr = *reinterpret_cast<const float4 *>(&sm.nk[16 * wave + 4 * L]);
             const float nkrow[4] = {nkr.x, nkr.y, nkr.z, nkr.w};
+            auto tt_rows = [&](const uint4(&arow)[NK]) {
 #pragma unroll
-            for (int ts = 0; ts < 4; ++ts) {
-                floatx4_t c = {0.f, 0.f, 0.f, 0.f};
+                for (int ts = 0; ts < 4; ++ts) {
+                    floatx4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) {
-                    // rows of the A operand = tokens 16 wave + n: the same registers as B set `wave`
-                    const uint4 arow = wave == 0 ? Bt[0][kk] : wave == 1 ? Bt[1][kk] : wave == 2 ? Bt[2][kk] : Bt[3][kk];
-                    c = mfma_bf16(arow, Bt[ts][kk], c);
+                    for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(arow[kk], Bt[ts][kk], c);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        sm.tt[16 * wave + 4 * L + r][16 * ts + n16] = fmaf(-2.f, c[r], nkrow[r] + nkt[ts]);
                 }
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    sm.tt[16 * wave + 4 * L + r][16 * ts + n16] = fmaf(-2.f, c[r], nkrow[r] + nkt[ts]);
-            }
+            };
+            if (wave == 0) tt_rows(Bt[0]);
+            else if (wave == 1) tt_rows(Bt[1]);
+            else if (wave == 2) tt_rows(Bt[2]);
+            else tt_rows(Bt[3]);
         }
 
         // ---- distances to the representatives that exist at the start of the chunk
