@@ -147,8 +147,12 @@ int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, 
  * lanes).  Timed by the caller, it gives the HBM read bandwidth a kernel reaches on this device,
  * the practical ceiling quoted beside the step kernel's roofline fraction.
  *   buf   device, 16-byte aligned, at least `bytes` bytes; sink  device, 4 bytes (never read back)
+ *   region_bytes 0: grid-stride over the buffer; else workgroup b reads its own contiguous region
+ *                [b*region_bytes, (b+1)*region_bytes), the pattern of one-stream-per-workgroup kernels
+ *   nontemporal  non-zero: use the non-temporal (streaming) loads the decode kernels use for state rows
  */
-int subgen_hbm_read_probe(const void *buf, size_t bytes, int32_t workgroups, void *sink, void *hip_stream);
+int subgen_hbm_read_probe(const void *buf, size_t bytes, int32_t workgroups, int32_t nontemporal,
+                          size_t region_bytes, void *sink, void *hip_stream);
 
 /* Aggregate counters; synchronises the context's stream. */
 typedef struct subgen_stats_t {

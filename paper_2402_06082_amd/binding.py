@@ -86,7 +86,7 @@ def load():
     L.subgen_exact_attend.restype = C.c_int
     L.subgen_exact_attend.argtypes = [P, P, P, P, i64, i64, i32, i32, i32, P, C.c_size_t, P]
     L.subgen_hbm_read_probe.restype = C.c_int
-    L.subgen_hbm_read_probe.argtypes = [P, C.c_size_t, i32, P, P]
+    L.subgen_hbm_read_probe.argtypes = [P, C.c_size_t, i32, i32, C.c_size_t, P, P]
     L.subgen_stats.restype = C.c_int
     L.subgen_stats.argtypes = [P, C.POINTER(subgen_stats_t)]
     L.subgen_center_counts.restype = C.c_int
@@ -296,9 +296,10 @@ def exact_attend(K: torch.Tensor, V: torch.Tensor, Q: torch.Tensor, out: Optiona
     return out
 
 
-def hbm_read_probe(buf: torch.Tensor, workgroups: int, sink: torch.Tensor) -> None:
+def hbm_read_probe(buf: torch.Tensor, workgroups: int, sink: torch.Tensor, nontemporal: bool = True,
+                   region_bytes: int = 0) -> None:
     """One plain streaming read of ``buf`` (measurement aid; time it with events around the call)."""
     _check(load().subgen_hbm_read_probe(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), int(workgroups),
-                                        C.c_void_p(sink.data_ptr()),
+                                        int(bool(nontemporal)), int(region_bytes), C.c_void_p(sink.data_ptr()),
                                         C.c_void_p(torch.cuda.current_stream(buf.device).cuda_stream)),
            "subgen_hbm_read_probe")

@@ -45,8 +45,8 @@ __global__ __launch_bounds__(kWG) void exact_partial_kernel(const ExactCall c)
         const bool valid = r < t1;
         const int64_t rr = valid ? r : t1 - 1;
         float kx[VEC], vx[VEC];
-        unpack<BF16>(ld16(K + (size_t)rr * ROWB + col * 16), kx);
-        unpack<BF16>(ld16(V + (size_t)rr * ROWB + col * 16), vx);
+        unpack<BF16>(ldnt16(K + (size_t)rr * ROWB + col * 16), kx);
+        unpack<BF16>(ldnt16(V + (size_t)rr * ROWB + col * 16), vx);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             float a = 0.f;
@@ -125,21 +125,31 @@ __global__ __launch_bounds__(kWG) void exact_combine_kernel(const ExactCall c)
 }
 
 
-// Plain streaming read of a buffer (16-byte loads, 8 in flight per lane, grid-stride): measures the
+// Plain streaming read of a buffer (16-byte loads, 8 in flight per lane, grid-stride; ordinary or
+// non-temporal loads): measures the
 // HBM read bandwidth a kernel can reach on this device, as the practical ceiling beside the 8 TB/s peak.
-__global__ __launch_bounds__(kWG) void hbm_read_probe_kernel(const uint4 *buf, size_t n16, uint32_t *sink)
+__global__ __launch_bounds__(kWG) void hbm_read_probe_kernel(const uint4 *buf, size_t n16, uint32_t *sink,
+                                                             const bool nontemporal, const size_t region16)
 {
-    const size_t stride = (size_t)gridDim.x * kWG;
-    size_t i = (size_t)blockIdx.x * kWG + threadIdx.x;
+    // region16 == 0: grid-stride over the whole buffer; else workgroup b streams its own contiguous region
+    // [b * region16, (b+1) * region16) of 16-byte words (the access pattern of one-stream-per-workgroup kernels)
+    size_t stride = (size_t)gridDim.x * kWG, i = (size_t)blockIdx.x * kWG + threadIdx.x, end = n16;
+    if (region16 != 0) {
+        stride = kWG;
+        i = (size_t)blockIdx.x * region16 + threadIdx.x;
+        end = (size_t)(blockIdx.x + 1) * region16;
+        if (end > n16) end = n16;
+    }
     uint32_t acc = 0;
-    for (; i + 7 * stride < n16; i += 8 * stride) {
+    for (; i + 7 * stride < end; i += 8 * stride) {
         uint4 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = buf[i + u * stride];
+        for (int u = 0; u < 8; ++u)
+            v[u] = nontemporal ? ldnt16(reinterpret_cast<const char *>(buf + i + u * stride)) : buf[i + u * stride];
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
-    for (; i < n16; i += stride) {
+    for (; i < end; i += stride) {
         const uint4 v = buf[i];
         acc ^= v.x ^ v.y ^ v.z ^ v.w;
     }

@@ -377,11 +377,13 @@ int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, 
     return hipGetLastError() == hipSuccess ? SUBGEN_OK : SUBGEN_EHIP;
 }
 
-int subgen_hbm_read_probe(const void *buf, size_t bytes, int32_t workgroups, void *sink, void *hip_stream)
+int subgen_hbm_read_probe(const void *buf, size_t bytes, int32_t workgroups, int32_t nontemporal,
+                          size_t region_bytes, void *sink, void *hip_stream)
 {
     if (!buf || !sink || !aligned16(buf) || bytes < 16 || workgroups < 1 || workgroups > (1 << 20)) return SUBGEN_EINVAL;
     hipLaunchKernelGGL(sg::hbm_read_probe_kernel, dim3((unsigned)workgroups), dim3(sg::kWG), 0,
-                       reinterpret_cast<hipStream_t>(hip_stream), (const uint4 *)buf, bytes / 16, (uint32_t *)sink);
+                       reinterpret_cast<hipStream_t>(hip_stream), (const uint4 *)buf, bytes / 16, (uint32_t *)sink,
+                       nontemporal != 0, region_bytes / 16);
     return hipGetLastError() == hipSuccess ? SUBGEN_OK : SUBGEN_EHIP;
 }
 

@@ -85,6 +85,13 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 // 16-byte row chunks
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ uint4 ld16(const char *p) { return *reinterpret_cast<const uint4 *>(p); }
+// streaming load: the row is read once per kernel, so it should not displace anything in the caches
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ldnt16(const char *p)
+{
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ void st16(char *p, uint4 v) { *reinterpret_cast<uint4 *>(p) = v; }
 
 template <bool BF16>
@@ -254,7 +261,7 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
             for (int u = 0; u < kUnroll; ++u) {
                 const int r = r0 + u * RPB + sub;
                 const int rr = r < m ? r : m - 1;
-                raw[u] = ld16(X + (size_t)rr * ROWB + col * 16);
+                raw[u] = ldnt16(X + (size_t)rr * ROWB + col * 16);
                 if constexpr (ATT) cf[u] = (float)cnt[rr];
             }
 #pragma unroll
@@ -431,8 +438,8 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
                 for (int u = 0; u < kUnroll; ++u) {
                     const int r = r0 + u * RPB + sub;
                     const int rr = r < st.s ? r : st.s - 1;
-                    rk[u] = ld16(Ks + (size_t)rr * ROWB + col * 16);
-                    rv[u] = ld16(Vs + (size_t)rr * ROWB + col * 16);
+                    rk[u] = ldnt16(Ks + (size_t)rr * ROWB + col * 16);
+                    rv[u] = ldnt16(Vs + (size_t)rr * ROWB + col * 16);
                     vnj[u] = svn[rr];
                 }
 #pragma unroll
@@ -466,8 +473,8 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
             for (int u = 0; u < kUnroll; ++u) {
                 const int r = r0 + u * RPB + sub;
                 const int rr = r < fill ? r : fill - 1;
-                rk[u] = ld16(Kw + (size_t)rr * ROWB + col * 16);
-                rv[u] = ld16(Vw + (size_t)rr * ROWB + col * 16);
+                rk[u] = ldnt16(Kw + (size_t)rr * ROWB + col * 16);
+                rv[u] = ldnt16(Vw + (size_t)rr * ROWB + col * 16);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {

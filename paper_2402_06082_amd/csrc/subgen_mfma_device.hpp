@@ -255,67 +255,75 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
     // online softmax state of this lane's query role: lazily raised reference, denominator
     float mx = -INFINITY, den = 0.f;
 
-    // ---- one pass over the representatives, 16 rows per wavefront step, two steps in flight
+    // ---- one pass over the representatives, 16 rows per wavefront step; the loads of the next step are
+    //      issued before the arithmetic of the current one (two register sets, ping-pong)
     float b1 = INFINITY, b2 = INFINITY, nxmax = 0.f;
     int i1 = -1;
     if ((UPD && evict) || ATT) {
-        constexpr int U = 2;
-        for (int r0 = wave * 16; r0 < m; r0 += 16 * kWaves * U) {
-            uint4 a[U][NK];
-            float4 nx4[U];
-            int4 cn4[U];
+        struct Group {
+            uint4 a[NK];
+            float4 nx;
+            int4 cn;
+        };
+        auto load = [&](Group &gq, const int base) {
+            const int rr = base + n16 < m ? base + n16 : m - 1;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                int base = r0 + u * 16 * kWaves;
-                if (base >= m) base = r0;                       // past the end: repeat a valid group (masked below)
-                const int rr = base + n16 < m ? base + n16 : m - 1;
+            for (int kk = 0; kk < NK; ++kk) gq.a[kk] = ldnt16(X + (size_t)rr * ROWB + (L + 4 * kk) * 16);
+            if constexpr (UPD) gq.nx = *reinterpret_cast<const float4 *>(xn + base + 4 * L);
+            if constexpr (ATT) gq.cn = *reinterpret_cast<const int4 *>(cnt + base + 4 * L);
+        };
+        auto compute = [&](const Group &gq, const int base) {
+            floatx4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) a[u][kk] = ld16(X + (size_t)rr * ROWB + (L + 4 * kk) * 16);
-                if constexpr (UPD) nx4[u] = *reinterpret_cast<const float4 *>(xn + base + 4 * L);
-                if constexpr (ATT) cn4[u] = *reinterpret_cast<const int4 *>(cnt + base + 4 * L);
-            }
+            for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(gq.a[kk], Bc[kk], c);
+            const int row0 = base + 4 * L;   // rows of this lane's four results
+            if constexpr (ATT) {
+                if (qrole_c && row0 < m) {
+                    const float cf[4] = {(float)gq.cn.x, (float)gq.cn.y, (float)gq.cn.z, (float)gq.cn.w};
+                    float mc = c[0];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int base = r0 + u * 16 * kWaves;
-                floatx4_t c = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(a[u][kk], Bc[kk], c);
-                const int row0 = base + 4 * L;   // rows of this lane's four results
-                if constexpr (ATT) {
-                    if (qrole_c && row0 < m) {
-                        const float cf[4] = {(float)cn4[u].x, (float)cn4[u].y, (float)cn4[u].z, (float)cn4[u].w};
-                        float mc = c[0];
-#pragma unroll
-                        for (int r = 1; r < 4; ++r) mc = (row0 + r < m) ? fmaxf(mc, c[r]) : mc;
-                        if (mc > mx + kLazy || mx == -INFINITY) {
-                            den *= __expf(mx - mc);
-                            mx = mc;
-                        }
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (row0 + r < m) den = fmaf(cf[r], __expf(c[r] - mx), den);
+                    for (int r = 1; r < 4; ++r) mc = (row0 + r < m) ? fmaxf(mc, c[r]) : mc;
+                    if (mc > mx + kLazy || mx == -INFINITY) {
+                        den *= __expf(mx - mc);
+                        mx = mc;
                     }
-                }
-                if constexpr (UPD) {
-                    if (krole_c && evict) {
-                        const float nxr[4] = {nx4[u].x, nx4[u].y, nx4[u].z, nx4[u].w};
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            if (row0 + r < m) {
-                                const float dt = fmaf(-2.f, c[r], nxr[r] + nk);
-                                if (dt < b1) {
-                                    b2 = b1;
-                                    b1 = dt;
-                                    i1 = row0 + r;
-                                } else if (dt < b2) {
-                                    b2 = dt;
-                                }
-                                nxmax = fmaxf(nxmax, nxr[r]);
+                    for (int r = 0; r < 4; ++r)
+                        if (row0 + r < m) den = fmaf(cf[r], __expf(c[r] - mx), den);
+                }
+            }
+            if constexpr (UPD) {
+                if (krole_c && evict) {
+                    const float nxr[4] = {gq.nx.x, gq.nx.y, gq.nx.z, gq.nx.w};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if (row0 + r < m) {
+                            const float dt = fmaf(-2.f, c[r], nxr[r] + nk);
+                            if (dt < b1) {
+                                b2 = b1;
+                                b1 = dt;
+                                i1 = row0 + r;
+                            } else if (dt < b2) {
+                                b2 = dt;
                             }
+                            nxmax = fmaxf(nxmax, nxr[r]);
                         }
                     }
                 }
             }
+        };
+        constexpr int STEP = 16 * kWaves;
+        Group ga, gb;
+        int r0 = wave * 16;
+        if (r0 < m) load(ga, r0);
+        while (r0 < m) {
+            if (r0 + STEP < m) load(gb, r0 + STEP);
+            compute(ga, r0);
+            r0 += STEP;
+            if (r0 >= m) break;
+            if (r0 + STEP < m) load(ga, r0 + STEP);
+            compute(gb, r0);
+            r0 += STEP;
         }
     }
 
@@ -461,30 +469,36 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
 
         // one 16-row group of (key rows, value rows): scores on the matrix cores, weights per lane row,
         // value rows accumulated into the lane's output columns
+        struct RowGroup {
+            uint4 a[NK], bv[NVL][VL];
+            float4 vn4;
+        };
         auto scan = [&](const char *Kb, const char *Vb, const float *vnorm, const float wmul, const int nrows,
                         const bool to_den) {
-            for (int r0 = wave * 16; r0 < nrows; r0 += 16 * kWaves) {
+            auto load = [&](RowGroup &gq, const int r0) {
                 const int rr = r0 + n16 < nrows ? r0 + n16 : nrows - 1;
-                uint4 a[NK], bv[NVL][VL];
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) a[kk] = ld16(Kb + (size_t)rr * ROWB + (L + 4 * kk) * 16);
+                for (int kk = 0; kk < NK; ++kk) gq.a[kk] = ldnt16(Kb + (size_t)rr * ROWB + (L + 4 * kk) * 16);
 #pragma unroll
                 for (int u = 0; u < NVL; ++u) {
                     const int vr = r0 + 4 * L + u * RPLD + vrsub;
                     const int vrr = vr < nrows ? vr : nrows - 1;
 #pragma unroll
-                    for (int vl = 0; vl < VL; ++vl) bv[u][vl] = ld16(Vb + (size_t)vrr * ROWB + (vchunk + 16 * vl) * 16);
+                    for (int vl = 0; vl < VL; ++vl)
+                        gq.bv[u][vl] = ldnt16(Vb + (size_t)vrr * ROWB + (vchunk + 16 * vl) * 16);
                 }
+                if (vnorm != nullptr) gq.vn4 = *reinterpret_cast<const float4 *>(vnorm + r0 + 4 * L);
+            };
+            auto compute = [&](const RowGroup &gq, const int r0) {
                 float wg[4] = {1.f, 1.f, 1.f, 1.f};
                 if (vnorm != nullptr) {
-                    const float4 v4 = *reinterpret_cast<const float4 *>(vnorm + r0 + 4 * L);
-                    const float vv[4] = {v4.x, v4.y, v4.z, v4.w};
+                    const float vv[4] = {gq.vn4.x, gq.vn4.y, gq.vn4.z, gq.vn4.w};
 #pragma unroll
                     for (int r = 0; r < 4; ++r) wg[r] = vv[r] > 0.f ? wmul * __builtin_amdgcn_rcpf(vv[r]) : 0.f;
                 }
                 floatx4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(a[kk], Bq[kk], c);
+                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(gq.a[kk], Bq[kk], c);
                 const int row0 = r0 + 4 * L;
                 float scale = 1.f;
                 float e[4] = {0.f, 0.f, 0.f, 0.f};
@@ -519,13 +533,26 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
 #pragma unroll
                     for (int vl = 0; vl < VL; ++vl) {
                         float vf[8];
-                        unpack<true>(bv[u][vl], vf);
+                        unpack<true>(gq.bv[u][vl], vf);
 #pragma unroll
                         for (int g = 0; g < G; ++g)
 #pragma unroll
                             for (int i = 0; i < 8; ++i) acc[g][vl * 8 + i] = fmaf(eg[g], vf[i], acc[g][vl * 8 + i]);
                     }
                 }
+            };
+            constexpr int STEP = 16 * kWaves;
+            RowGroup ga, gb;
+            int r0 = wave * 16;
+            if (r0 < nrows) load(ga, r0);
+            while (r0 < nrows) {
+                if (r0 + STEP < nrows) load(gb, r0 + STEP);
+                compute(ga, r0);
+                r0 += STEP;
+                if (r0 >= nrows) break;
+                if (r0 + STEP < nrows) load(ga, r0 + STEP);
+                compute(gb, r0);
+                r0 += STEP;
             }
         };
         // sampled pairs: numerator terms  mu/(s ||v_j||^2) e^{<q,k_j>} v_j
@@ -582,7 +609,7 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
 
 // at least two workgroups per CU (two wavefronts per SIMD) even for the widest accumulator sets
 template <int NK, int G, bool UPD, bool ATT>
-__global__ __launch_bounds__(kWG, 2) void decode_mfma_kernel(const State st, const Call call)
+__global__ __launch_bounds__(kWG, 3) void decode_mfma_kernel(const State st, const Call call)
 {
     __shared__ SmemMfma<NK, G> sm;
     const size_t sid = blockIdx.x;
