@@ -111,6 +111,7 @@ def main():
     ap.add_argument("--prefix", type=int, default=-1, help="override the prefix length (debugging)")
     ap.add_argument("--delta", type=float, default=0.0, help="skip tuning and use this threshold")
     ap.add_argument("--split", action="store_true", help="time subgen_update + subgen_attend instead of subgen_step")
+    ap.add_argument("--generic", action="store_true", help="force the generic vector-ALU kernels (kernel_path = 1)")
     ap.add_argument("--no-exact", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=2048)
@@ -148,7 +149,7 @@ def main():
     wl = Workload(cfg, device=dev, streams=S)
     max_centers = max(2048, 3 * (cfg.target_centers or 1024))
     sg = binding.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=cfg.g,
-                        max_centers=max_centers, seed=0, device=dev)
+                        max_centers=max_centers, seed=0, device=dev, kernel_path=1 if a.generic else 0)
 
     # ---- prefix: generate on the device block by block, ingest; keep it resident for the exact kernel
     keep = not a.no_exact

@@ -143,7 +143,11 @@ void launch_mfma(int NK, int G, Mode mode, dim3 grid, hipStream_t s, const State
 int launch_decode(subgen_ctx *c, Mode mode, const Call &call)
 {
     const dim3 grid((unsigned)c->S);
-    if (c->mfma) {
+    // One query per stream: the generic kernels read whole rows with one contiguous 1 KB access per wavefront
+    // load, which the memory system serves faster than the 64-byte pieces of the matrix-core operand layout,
+    // and a single dot product per row does not saturate the vector ALUs.  With several queries per stream the
+    // vector ALUs would be the bound, so those go to the matrix cores.  (Prefix ingest always does.)
+    if (c->mfma && (c->G > 1 || mode == MODE_UPDATE)) {
         launch_mfma(c->LPR / 4, c->G, mode, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);

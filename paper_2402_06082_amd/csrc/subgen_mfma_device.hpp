@@ -42,6 +42,7 @@ constexpr float kLazy = 8.0f;  // the running softmax reference is raised only w
 
 template <int NK, int G>
 struct SmemMfma {
+    alignas(16) uint4 ekrow[NK * 4], evrow[NK * 4];   // the evicted (key, value) rows, for the sampling copies
     // approximate nearest-center candidates per wavefront
     float wb1[kWaves], wb2[kWaves], wnx[kWaves];
     int wi1[kWaves];
@@ -51,8 +52,6 @@ struct SmemMfma {
     float bx[G];
     float wmx[kWaves][G], wden[kWaves][G];
     float wacc[kWaves][G][NK * 32];
-    int qn;
-    int queue[kQueue];
 };
 
 // Exact nearest representative in double precision (lowest index on ties); block-uniform result.
@@ -220,13 +219,17 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
         if (evict) {
             ek = ld16(esk + col * 16);
             ev = ld16(esv + col * 16);
+            if (tid < LPR) {
+                sm.ekrow[tid] = ek;
+                sm.evrow[tid] = ev;
+            }
             if (krole_c) {
 #pragma unroll
                 for (int kk = 0; kk < NK; ++kk) Bc[kk] = ld16(esk + (L + 4 * kk) * 16);
             }
         }
+        __syncthreads();  // every lane holds the evicted row (registers, LDS) before the slot is overwritten
         if (st.w > 0) {
-            __syncthreads();  // every lane holds the evicted row before the slot is overwritten
             if (tid < LPR) {
                 st16(kw + tid * 16, ld16(krow + tid * 16));
                 st16(vw + tid * 16, ld16(vrow + tid * 16));
@@ -418,32 +421,26 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
             if (mu == 0.0) p = 1.f;
             else if (vn == 0.f) p = 0.f;
             else p = (float)((double)vn / (mu + (double)vn));
-            for (int base = 0; base < st.s; base += kQueue) {
-                if (tid == 0) sm.qn = 0;
-                __syncthreads();
-                const int j0 = base + tid * 4;
-                if (j0 < st.s && p > 0.f) {
+            // accepts are rare (about s/n per token), so the lane that draws one copies the two rows itself
+            if (p > 0.f) {
+                for (int j0 = tid * 4; j0 < st.s; j0 += kWG * 4) {
                     uint32_t r[4];
                     philox4x32_10((uint32_t)(j0 >> 2), (uint32_t)etoken, (uint32_t)((uint64_t)etoken >> 32),
                                   (uint32_t)sid, st.seed_lo, st.seed_hi, r);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const float u = (float)(r[i] >> 8) * (1.0f / 16777216.0f);
-                        if (j0 + i < st.s && u < p) sm.queue[atomicAdd(&sm.qn, 1)] = j0 + i;
+                        const int j = j0 + i;
+                        if (j < st.s && u < p) {
+                            for (int ch = 0; ch < CPR; ++ch) {
+                                st16(Ks + (size_t)j * ROWB + ch * 16, sm.ekrow[ch]);
+                                st16(Vs + (size_t)j * ROWB + ch * 16, sm.evrow[ch]);
+                            }
+                            st.sidx[sid * (size_t)st.sS + j] = (int32_t)etoken;
+                            st.svn[sid * (size_t)st.sS + j] = vn;
+                        }
                     }
                 }
-                __syncthreads();
-                const int nq = sm.qn;
-                for (int e = grp; e < nq; e += RPB) {
-                    const int j = sm.queue[e];
-                    st16(Ks + (size_t)j * ROWB + col * 16, ek);
-                    st16(Vs + (size_t)j * ROWB + col * 16, ev);
-                    if (col == 0) {
-                        st.sidx[sid * (size_t)st.sS + j] = (int32_t)etoken;
-                        st.svn[sid * (size_t)st.sS + j] = vn;
-                    }
-                }
-                __syncthreads();
             }
             mu += (double)vn;
         }
