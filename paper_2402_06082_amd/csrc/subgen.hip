@@ -14,6 +14,7 @@
 #include "subgen_device.hpp"
 #include "subgen_mfma_device.hpp"
 #include "ingest_mfma_device.hpp"
+#include "subgen_dot2_device.hpp"
 
 using sg::Call;
 using sg::State;
@@ -143,11 +144,26 @@ void launch_mfma(int NK, int G, Mode mode, dim3 grid, hipStream_t s, const State
 int launch_decode(subgen_ctx *c, Mode mode, const Call &call)
 {
     const dim3 grid((unsigned)c->S);
-    // One query per stream: the generic kernels read whole rows with one contiguous 1 KB access per wavefront
-    // load, which the memory system serves faster than the 64-byte pieces of the matrix-core operand layout,
-    // and a single dot product per row does not saturate the vector ALUs.  With several queries per stream the
-    // vector ALUs would be the bound, so those go to the matrix cores.  (Prefix ingest always does.)
-    if (c->mfma && (c->G > 1 || mode == MODE_UPDATE)) {
+    // bf16 rows of 128 elements, one query per stream: whole-row loads (one contiguous 1 KB access per wavefront
+    // load, which the memory system serves faster than the 64-byte pieces of the matrix-core operand layout)
+    // with packed-bf16 dot products.  With several queries per stream the vector ALUs would be the bound, so
+    // those go to the matrix cores.
+    if (c->mfma && c->G == 1 && c->LPR == 16) {
+        switch (mode) {
+            case MODE_UPDATE:
+                hipLaunchKernelGGL((sg::decode_dot2_kernel<true, false>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+                break;
+            case MODE_ATTEND:
+                hipLaunchKernelGGL((sg::decode_dot2_kernel<false, true>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+                break;
+            case MODE_STEP:
+                hipLaunchKernelGGL((sg::decode_dot2_kernel<true, true>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+                break;
+        }
+        const hipError_t e = hipGetLastError();
+        return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+    }
+    if (c->mfma) {
         launch_mfma(c->LPR / 4, c->G, mode, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);

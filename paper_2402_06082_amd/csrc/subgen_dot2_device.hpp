@@ -1,0 +1,398 @@
+// Single-query decode step for bf16 rows of 128 elements (gfx950).
+//
+// With one query per stream the step is a pure stream over the state, so what matters is the shape of the
+// loads and the number of vector-ALU instructions per byte:
+//   - a row is read by 16 consecutive lanes with one 16-byte non-temporal load each, so every wavefront load
+//     is one contiguous 1 KB piece of memory (four whole rows), four loads in flight per lane;
+//   - dot products run on packed bf16 pairs (v_dot2c_f32_bf16: two multiply-adds per instruction, no
+//     unpacking of key rows) and are reduced over the 16 lanes of a row with DPP row rotations (no LDS);
+//   - the softmax reference is raised lazily, so accumulators are almost never rescaled.
+// Nearest-center decisions stay exact the same way as on the matrix-core path: approximate squared distances
+// D~ = ||x||^2 + ||k||^2 - 2<x,k> decide only when the best/runner-up gap and |D~ - delta^2| exceed their error
+// bound; otherwise the workgroup re-evaluates all distances in double precision.
+#pragma once
+#include "subgen_mfma_device.hpp"
+
+namespace sg {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+__device__ __forceinline__ float dot8_bf16(const uint4 &x, const uint4 &y)
+{
+    float s = dot2_bf16(x.x, y.x, 0.f);
+    s = dot2_bf16(x.y, y.y, s);
+    s = dot2_bf16(x.z, y.z, s);
+    return dot2_bf16(x.w, y.w, s);
+}
+
+// all-reduce over the 16 lanes of a DPP row (row rotations by 8, 4, 2, 1)
+template <int N>
+__device__ __forceinline__ float row_ror(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf,
+                                                                 false));
+}
+__device__ __forceinline__ float row_sum16(float v)
+{
+    v += row_ror<8>(v);
+    v += row_ror<4>(v);
+    v += row_ror<2>(v);
+    v += row_ror<1>(v);
+    return v;
+}
+
+struct SmemDot2 {
+    alignas(16) uint4 ekrow[16], evrow[16];   // the evicted (key, value) rows, for the sampling copies
+    float wb1[kWaves], wb2[kWaves], wnx[kWaves];
+    int wi1[kWaves];
+    double wbest[kWaves];
+    int widx[kWaves];
+    float bx;
+    float wmx[kWaves], wden[kWaves];
+    float wacc[kWaves][128];
+};
+
+template <bool UPD, bool ATT>
+__device__ __forceinline__ void token_step_dot2(const State &st, const size_t sid, const char *krow, const char *vrow,
+                                                const char *qrow, float *outrow, const int64_t n_seen, int &m,
+                                                double &mu, SmemDot2 &sm)
+{
+    constexpr int LPR = 16, RPW = 4, RPB = RPW * kWaves;
+    constexpr size_t ROWB = 256;
+    constexpr int U = 4;   // row loads in flight per lane
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 15, sub = lane >> 4;
+
+    char *const X = st.X + sid * (size_t)st.Mcap * ROWB;
+    int32_t *const cnt = st.cnt + sid * (size_t)st.McapS;
+    float *const xn = st.xn + sid * (size_t)st.McapS;
+    char *const Ks = st.Ks + sid * (size_t)st.s * ROWB;
+    char *const Vs = st.Vs + sid * (size_t)st.s * ROWB;
+    char *const Kw = st.Kw + sid * (size_t)st.w * ROWB;
+    char *const Vw = st.Vw + sid * (size_t)st.w * ROWB;
+
+    uint4 qp = make_uint4(0, 0, 0, 0);   // this lane's 8 packed query elements
+    if constexpr (ATT) qp = ld16(qrow + col * 16);
+
+    // ---- window push; the token that leaves the window is the one that is compressed
+    bool evict = false;
+    int64_t etoken = 0;
+    uint4 ek = make_uint4(0, 0, 0, 0), ev = make_uint4(0, 0, 0, 0);
+    float nk = 0.f, vn = 0.f;
+    if constexpr (UPD) {
+        const char *esk = krow, *esv = vrow;
+        char *kw = nullptr, *vw = nullptr;
+        if (st.w == 0) {
+            evict = true;
+            etoken = n_seen;
+        } else {
+            const int slot = (int)(n_seen % st.w);
+            kw = Kw + (size_t)slot * ROWB;
+            vw = Vw + (size_t)slot * ROWB;
+            esk = kw;
+            esv = vw;
+            if (n_seen >= st.w) {
+                evict = true;
+                etoken = n_seen - st.w;
+            }
+        }
+        if (evict) {
+            ek = ld16(esk + col * 16);
+            ev = ld16(esv + col * 16);
+            if (tid < LPR) {
+                sm.ekrow[tid] = ek;
+                sm.evrow[tid] = ev;
+            }
+            // ||k'||^2 and ||v'||^2 in double from the exactly converted elements
+            float ekf[8], evf[8];
+            unpack<true>(ek, ekf);
+            unpack<true>(ev, evf);
+            double a = 0.0, b = 0.0;
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                a = fma((double)ekf[v], (double)ekf[v], a);
+                b = fma((double)evf[v], (double)evf[v], b);
+            }
+            nk = (float)group_sum<LPR>(a);
+            vn = (float)group_sum<LPR>(b);
+        }
+        __syncthreads();  // every lane holds the evicted row (registers, LDS) before the slot is overwritten
+        if (st.w > 0 && tid < LPR) {
+            st16(kw + tid * 16, ld16(krow + tid * 16));
+            st16(vw + tid * 16, ld16(vrow + tid * 16));
+        }
+    }
+    const int64_t n_after = UPD ? n_seen + 1 : n_seen;
+    const int64_t n_evicted_after = st.w == 0 ? n_after : (n_after > st.w ? n_after - st.w : 0);
+
+    // online softmax of this lane's row group: lazily raised reference, denominator, 8 output columns
+    float mx = -INFINITY, den = 0.f, acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+
+    // ---- one pass over the representatives: approximate squared distance to the evicted key and
+    //      count-weighted exp(<q, x_i>) for the softmax normaliser
+    float b1 = INFINITY, b2 = INFINITY, nxmax = 0.f;
+    int i1 = -1;
+    if ((UPD && evict) || ATT) {
+        for (int r0 = wave * RPW; r0 < m; r0 += RPB * U) {
+            uint4 raw[U];
+            float nx[U], cf[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int r = r0 + u * RPB + sub;
+                const int rr = r < m ? r : m - 1;
+                raw[u] = ldnt16(X + (size_t)rr * ROWB + col * 16);
+                if constexpr (UPD) nx[u] = xn[rr];
+                if constexpr (ATT) cf[u] = (float)cnt[rr];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int r = r0 + u * RPB + sub;
+                const bool valid = r < m;
+                if constexpr (ATT) {
+                    const float b = row_sum16(dot8_bf16(raw[u], qp));
+                    if (valid) {
+                        if (b > mx + kLazy || mx == -INFINITY) {
+                            den *= __expf(mx - b);   // no value rows yet: acc is still zero
+                            mx = b;
+                        }
+                        den = fmaf(cf[u], __expf(b - mx), den);
+                    }
+                }
+                if constexpr (UPD) {
+                    if (evict) {
+                        const float dk = row_sum16(dot8_bf16(raw[u], ek));
+                        if (valid) {
+                            const float dt = fmaf(-2.f, dk, nx[u] + nk);
+                            if (dt < b1) {
+                                b2 = b1;
+                                b1 = dt;
+                                i1 = r;
+                            } else if (dt < b2) {
+                                b2 = dt;
+                            }
+                            nxmax = fmaxf(nxmax, nx[u]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    bool extra = false;
+    if constexpr (UPD) {
+        if (evict) {
+            // ---- best / runner-up of the approximate distances over the workgroup
+#pragma unroll
+            for (int o = 16; o < 64; o <<= 1) {
+                const float ob1 = __shfl_xor(b1, o), ob2 = __shfl_xor(b2, o);
+                const int oi1 = __shfl_xor(i1, o);
+                if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
+                    b2 = fminf(b1, ob2);
+                    b1 = ob1;
+                    i1 = oi1;
+                } else {
+                    b2 = fminf(b2, ob1);
+                }
+                nxmax = fmaxf(nxmax, __shfl_xor(nxmax, o));
+            }
+            if (lane == 0) {
+                sm.wb1[wave] = b1;
+                sm.wb2[wave] = b2;
+                sm.wi1[wave] = i1;
+                sm.wnx[wave] = nxmax;
+            }
+            __syncthreads();
+            b1 = sm.wb1[0]; b2 = sm.wb2[0]; i1 = sm.wi1[0]; nxmax = sm.wnx[0];
+#pragma unroll
+            for (int wv = 1; wv < kWaves; ++wv) {
+                const float ob1 = sm.wb1[wv], ob2 = sm.wb2[wv];
+                const int oi1 = sm.wi1[wv];
+                if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
+                    b2 = fminf(b1, ob2);
+                    b1 = ob1;
+                    i1 = oi1;
+                } else {
+                    b2 = fminf(b2, ob1);
+                }
+                nxmax = fmaxf(nxmax, sm.wnx[wv]);
+            }
+            // ---- decide from D~ when the error bound allows it, else re-evaluate exactly
+            const float thr = (float)st.delta2;
+            const float emax = kDistEps * (nxmax + nk);
+            bool join;
+            int bidx = i1;
+            const bool ambiguous = m > 0 && (!(b2 - b1 > 2.f * emax) || !(fabsf(b1 - thr) > emax + 1e-6f * thr));
+            if (ambiguous) {
+                double best;
+                exact_nearest<LPR>(X, m, ek, sm.wbest, sm.widx, best, bidx);
+                join = bidx >= 0 && best <= st.delta2;
+            } else {
+                join = m > 0 && b1 <= thr;
+            }
+            const bool forced = !join && m > 0 && m >= st.Mcap;
+            const bool created = !join && !forced;
+            const int target = created ? m : bidx;
+            if constexpr (ATT) {
+                // score of the cluster that gained this token: one more term of the normaliser
+                if (wave == 0 && sub == 0) {
+                    uint4 xr = ek;
+                    if (!created) xr = ld16(X + (size_t)target * ROWB + col * 16);
+                    const float a = row_sum16(dot8_bf16(xr, qp));
+                    if (col == 0) sm.bx = a;
+                }
+                extra = true;
+            }
+            if (created) {
+                if (tid < LPR) st16(X + (size_t)m * ROWB + tid * 16, ek);
+                if (tid == 0) {
+                    cnt[m] = 1;
+                    xn[m] = nk;
+                }
+            } else if (tid == 0) {
+                cnt[target] += 1;
+                if (forced) st.flags[sid] |= 1u;
+            }
+            if (tid == 0 && st.assign != nullptr && etoken < st.assign_cap)
+                st.assign[sid * (size_t)st.assign_cap + etoken] = target;
+            if (created) m += 1;
+
+            // ---- sampling update: p from the old mu, one coin per slot, then mu += ||v||^2.  Accepts are rare
+            //      (about s/n per token), so the lane that draws one copies the two rows itself.
+            float p;
+            if (mu == 0.0) p = 1.f;
+            else if (vn == 0.f) p = 0.f;
+            else p = (float)((double)vn / (mu + (double)vn));
+            if (p > 0.f) {
+                for (int j0 = tid * 4; j0 < st.s; j0 += kWG * 4) {
+                    uint32_t r[4];
+                    philox4x32_10((uint32_t)(j0 >> 2), (uint32_t)etoken, (uint32_t)((uint64_t)etoken >> 32),
+                                  (uint32_t)sid, st.seed_lo, st.seed_hi, r);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float u = (float)(r[i] >> 8) * (1.0f / 16777216.0f);
+                        const int j = j0 + i;
+                        if (j < st.s && u < p) {
+                            for (int ch = 0; ch < 16; ++ch) {
+                                st16(Ks + (size_t)j * ROWB + ch * 16, sm.ekrow[ch]);
+                                st16(Vs + (size_t)j * ROWB + ch * 16, sm.evrow[ch]);
+                            }
+                            st.sidx[sid * (size_t)st.sS + j] = (int32_t)etoken;
+                            st.svn[sid * (size_t)st.sS + j] = vn;
+                        }
+                    }
+                }
+            }
+            mu += (double)vn;
+        }
+        __syncthreads();  // window slot, center row and sample rows are visible to the whole workgroup
+    }
+
+    if constexpr (ATT) {
+        // rows with values: sampled pairs (importance weights, numerator only), then the window (weight 1, both)
+        auto scan = [&](const char *Kb, const char *Vb, const float *vnorm, const float wmul, const int nrows,
+                        const bool to_den) __attribute__((always_inline)) {
+            for (int r0 = wave * RPW; r0 < nrows; r0 += RPB * U) {
+                uint4 rk[U], rv[U];
+                float vnj[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * RPB + sub;
+                    const int rr = r < nrows ? r : nrows - 1;
+                    rk[u] = ldnt16(Kb + (size_t)rr * ROWB + col * 16);
+                    rv[u] = ldnt16(Vb + (size_t)rr * ROWB + col * 16);
+                    vnj[u] = vnorm != nullptr ? vnorm[rr] : 1.f;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const bool valid = r0 + u * RPB + sub < nrows;
+                    const float b = row_sum16(dot8_bf16(rk[u], qp));
+                    float e = 0.f;
+                    if (valid) {
+                        if (b > mx + kLazy || mx == -INFINITY) {
+                            const float sc = __expf(mx - b);   // mx = -inf gives 0
+                            den *= sc;
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) acc[i] *= sc;
+                            mx = b;
+                        }
+                        const float wgt = vnorm != nullptr ? (vnj[u] > 0.f ? wmul * __builtin_amdgcn_rcpf(vnj[u]) : 0.f)
+                                                           : 1.f;
+                        e = wgt * __expf(b - mx);
+                        if (to_den) den += e;
+                    }
+                    float vf[8];
+                    unpack<true>(rv[u], vf);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[i] = fmaf(e, vf[i], acc[i]);
+                }
+            }
+        };
+        if (n_evicted_after > 0)
+            scan(Ks, Vs, st.svn + sid * (size_t)st.sS, (float)(mu / (double)st.s), st.s, false);
+        const int fill = (int)(n_after < st.w ? n_after : st.w);
+        scan(Kw, Vw, nullptr, 1.f, fill, true);
+
+        // ---- merge the four row groups of the wavefront, then the wavefronts through LDS
+        float M = fmaxf(mx, __shfl_xor(mx, 16));
+        M = fmaxf(M, __shfl_xor(M, 32));
+        const float f = (mx == -INFINITY) ? 0.f : __expf(mx - M);
+        float dsum = den * f;
+        dsum += __shfl_xor(dsum, 16);
+        dsum += __shfl_xor(dsum, 32);
+        if (lane == 0) {
+            sm.wmx[wave] = M;
+            sm.wden[wave] = dsum;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float t = acc[i] * f;
+            t += __shfl_xor(t, 16);
+            t += __shfl_xor(t, 32);
+            if (sub == 0) sm.wacc[wave][col * 8 + i] = t;
+        }
+        __syncthreads();
+        if (tid < 128) {
+            const float bx = extra ? sm.bx : -INFINITY;
+            float Mx = bx;
+#pragma unroll
+            for (int wv = 0; wv < kWaves; ++wv) Mx = fmaxf(Mx, sm.wmx[wv]);
+            float dn = extra ? __expf(bx - Mx) : 0.f, num = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < kWaves; ++wv) {
+                const float wm = sm.wmx[wv];
+                const float sc = (wm == -INFINITY) ? 0.f : __expf(wm - Mx);
+                dn = fmaf(sm.wden[wv], sc, dn);
+                num = fmaf(sm.wacc[wv][tid], sc, num);
+            }
+            outrow[tid] = num / dn;
+        }
+    }
+}
+
+template <bool UPD, bool ATT>
+__global__ __launch_bounds__(kWG) void decode_dot2_kernel(const State st, const Call call)
+{
+    __shared__ SmemDot2 sm;
+    const size_t sid = blockIdx.x;
+    int m = st.m[sid];
+    double mu = st.mu[sid];
+    const char *krow = UPD ? call.K + sid * call.stream_stride : nullptr;
+    const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
+    const char *qrow = ATT ? call.Q + sid * 256 : nullptr;
+    float *outrow = ATT ? call.out + sid * 128 : nullptr;
+    token_step_dot2<UPD, ATT>(st, sid, krow, vrow, qrow, outrow, call.n_seen, m, mu, sm);
+    if constexpr (UPD) {
+        if (threadIdx.x == 0) {
+            st.m[sid] = m;
+            st.mu[sid] = mu;
+        }
+    }
+}
+
+}  // namespace sg
