@@ -198,6 +198,17 @@ typedef struct subgen_state_view {
 
 int subgen_export_state(subgen_ctx *ctx, int64_t stream, subgen_state_view *host_view);
 
+/*
+ * subgen_import_state — the inverse of subgen_export_state: load one stream's state from host buffers
+ * (checkpoint / resume).  The view must carry m, n_seen, mu, flags and every buffer (centers and counts
+ * with at least m rows; sample_K, sample_V, sample_idx, sample_vn; window_K, window_V when w > 0), in the
+ * layout export writes.  All streams of a context share one token counter: the first import into a fresh
+ * context sets it, every further import must carry the same n_seen (else SUBGEN_EINVAL).  Because the coin
+ * flips are counter-based (seed, stream, token, slot), a context restored this way and created with the same
+ * seed continues bit-identically.  Synchronises.
+ */
+int subgen_import_state(subgen_ctx *ctx, int64_t stream, const subgen_state_view *host_view);
+
 /* Block until everything enqueued on the context's stream has run. */
 int subgen_sync(subgen_ctx *ctx);
 

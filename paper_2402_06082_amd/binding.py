@@ -23,7 +23,7 @@ FLAG_CENTER_OVERFLOW = 1
 EXPORTS = [
     "subgen_create", "subgen_destroy", "subgen_update", "subgen_attend", "subgen_step", "subgen_ingest_prefix",
     "subgen_exact_workspace_bytes", "subgen_exact_attend", "subgen_hbm_read_probe", "subgen_stats", "subgen_center_counts",
-    "subgen_export_state", "subgen_sync", "subgen_strerror", "subgen_last_hip_error",
+    "subgen_export_state", "subgen_import_state", "subgen_sync", "subgen_strerror", "subgen_last_hip_error",
 ]
 
 
@@ -93,6 +93,8 @@ def load():
     L.subgen_center_counts.argtypes = [P, P]
     L.subgen_export_state.restype = C.c_int
     L.subgen_export_state.argtypes = [P, i64, C.POINTER(subgen_state_view)]
+    L.subgen_import_state.restype = C.c_int
+    L.subgen_import_state.argtypes = [P, i64, C.POINTER(subgen_state_view)]
     L.subgen_sync.restype = C.c_int
     L.subgen_sync.argtypes = [P]
     L.subgen_strerror.restype = C.c_char_p
@@ -235,6 +237,35 @@ class SubGen:
         m = np.zeros(self.streams, dtype=np.int32)
         _check(self._L.subgen_center_counts(self._h, m.ctypes.data_as(C.c_void_p)), "subgen_center_counts")
         return m
+
+    def export_raw(self, stream: int) -> dict:
+        """One stream's state as host arrays in the library's own element format (for import_raw)."""
+        v = subgen_state_view()
+        v.struct_size = C.sizeof(subgen_state_view)
+        cap = self.max_centers
+        bufs = {
+            "centers": _np_rows(self.dtype_code, cap, self.d), "counts": np.zeros(cap, dtype=np.int32),
+            "sample_K": _np_rows(self.dtype_code, self.s, self.d), "sample_V": _np_rows(self.dtype_code, self.s, self.d),
+            "sample_idx": np.zeros(self.s, dtype=np.int32), "sample_vn": np.zeros(self.s, dtype=np.float32),
+            "window_K": _np_rows(self.dtype_code, max(self.w, 1), self.d),
+            "window_V": _np_rows(self.dtype_code, max(self.w, 1), self.d),
+        }
+        v.centers_cap = cap
+        for k, a in bufs.items():
+            setattr(v, k, a.ctypes.data)
+        _check(self._L.subgen_export_state(self._h, int(stream), C.byref(v)), "subgen_export_state")
+        bufs.update(m=v.m, n_seen=v.n_seen, mu=v.mu, flags=v.flags)
+        return bufs
+
+    def import_raw(self, stream: int, state: dict) -> None:
+        """Load a stream's state produced by export_raw (possibly of another context with the same shape)."""
+        v = subgen_state_view()
+        v.struct_size = C.sizeof(subgen_state_view)
+        v.m, v.n_seen, v.mu, v.flags = state["m"], state["n_seen"], state["mu"], state["flags"]
+        v.centers_cap = state["centers"].shape[0]
+        for k in ("centers", "counts", "sample_K", "sample_V", "sample_idx", "sample_vn", "window_K", "window_V"):
+            setattr(v, k, np.ascontiguousarray(state[k]).ctypes.data)
+        _check(self._L.subgen_import_state(self._h, int(stream), C.byref(v)), "subgen_import_state")
 
     def export_state(self, stream: int, rows: bool = True) -> StreamState:
         v = subgen_state_view()

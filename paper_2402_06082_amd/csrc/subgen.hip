@@ -32,6 +32,7 @@ struct subgen_ctx {
     int device = 0;
     int last_hip = 0;
     bool mfma = false;     // bf16 rows scored on the matrix cores
+    bool imported = false; // a stream state has been imported (pins n_seen)
     std::vector<void *> allocs;
 };
 
@@ -498,6 +499,59 @@ int subgen_export_state(subgen_ctx *c, int64_t stream, subgen_state_view *v)
         v->assign_len = len;
     }
 #undef SG_D2H
+    return SUBGEN_OK;
+}
+
+int subgen_import_state(subgen_ctx *c, int64_t stream, const subgen_state_view *v)
+{
+    if (!c || !v || stream < 0 || stream >= c->S) return SUBGEN_EINVAL;
+    if (v->struct_size != sizeof(subgen_state_view)) return SUBGEN_EINVAL;
+    if (v->m < 0 || v->m > c->Mcap || v->n_seen < 0 || !std::isfinite(v->mu) || v->mu < 0.0) return SUBGEN_EINVAL;
+    if (v->m > 0 && (!v->centers || !v->counts)) return SUBGEN_EINVAL;
+    if (!v->sample_K || !v->sample_V || !v->sample_idx || !v->sample_vn) return SUBGEN_EINVAL;
+    if (c->w > 0 && (!v->window_K || !v->window_V)) return SUBGEN_EINVAL;
+    // all streams of a context share one token counter: the first import into an untouched context sets it
+    if (c->n_seen != v->n_seen && (c->n_seen != 0 || c->imported)) return SUBGEN_EINVAL;
+    DeviceGuard guard(c->device);
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return fail_hip(c, e);
+    const State &st = c->st;
+    const size_t sid = (size_t)stream, rowb = (size_t)c->d * c->esz;
+#define SG_H2D(dst, src, bytes)                                                       \
+    do {                                                                              \
+        if ((bytes) > 0) {                                                            \
+            e = hipMemcpy((dst), (src), (bytes), hipMemcpyHostToDevice);              \
+            if (e != hipSuccess) return fail_hip(c, e);                               \
+        }                                                                             \
+    } while (0)
+    const int32_t m = v->m;
+    SG_H2D(st.m + sid, &m, sizeof(int32_t));
+    SG_H2D(st.mu + sid, &v->mu, sizeof(double));
+    SG_H2D(st.flags + sid, &v->flags, sizeof(uint32_t));
+    SG_H2D(st.X + sid * c->Mcap * rowb, v->centers, (size_t)m * rowb);
+    SG_H2D(st.cnt + sid * st.McapS, v->counts, (size_t)m * sizeof(int32_t));
+    SG_H2D(st.Ks + sid * c->s * rowb, v->sample_K, (size_t)c->s * rowb);
+    SG_H2D(st.Vs + sid * c->s * rowb, v->sample_V, (size_t)c->s * rowb);
+    SG_H2D(st.sidx + sid * st.sS, v->sample_idx, (size_t)c->s * sizeof(int32_t));
+    SG_H2D(st.svn + sid * st.sS, v->sample_vn, (size_t)c->s * sizeof(float));
+    SG_H2D(st.Kw + sid * c->w * rowb, v->window_K, (size_t)c->w * rowb);
+    SG_H2D(st.Vw + sid * c->w * rowb, v->window_V, (size_t)c->w * rowb);
+#undef SG_H2D
+    // derived per-center norms
+    const dim3 grid(1), block(sg::kWG);
+    if (c->dtype == SUBGEN_BF16) {
+        if (c->LPR == 8) hipLaunchKernelGGL((sg::center_norms_kernel<true, 8>), grid, block, 0, c->stream, st, stream);
+        else if (c->LPR == 16) hipLaunchKernelGGL((sg::center_norms_kernel<true, 16>), grid, block, 0, c->stream, st, stream);
+        else hipLaunchKernelGGL((sg::center_norms_kernel<true, 32>), grid, block, 0, c->stream, st, stream);
+    } else {
+        if (c->LPR == 8) hipLaunchKernelGGL((sg::center_norms_kernel<false, 8>), grid, block, 0, c->stream, st, stream);
+        else if (c->LPR == 16) hipLaunchKernelGGL((sg::center_norms_kernel<false, 16>), grid, block, 0, c->stream, st, stream);
+        else hipLaunchKernelGGL((sg::center_norms_kernel<false, 32>), grid, block, 0, c->stream, st, stream);
+    }
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(c, e);
+    c->n_seen = v->n_seen;
+    c->imported = true;
     return SUBGEN_OK;
 }
 

@@ -585,4 +585,30 @@ __global__ __launch_bounds__(kWG) void ingest_kernel(const State st, const Call 
     }
 }
 
+
+// ||x_i||^2 of one stream's representatives (double sum of the exactly converted elements, rounded to fp32):
+// the derived array the bf16 fast paths read.  Used after a state import.
+template <bool BF16, int LPR>
+__global__ __launch_bounds__(kWG) void center_norms_kernel(const State st, const int64_t stream)
+{
+    constexpr int VEC = BF16 ? 8 : 4;
+    constexpr int RPW = 64 / LPR, RPB = RPW * kWaves;
+    constexpr size_t ROWB = (size_t)LPR * 16;
+    const size_t sid = (size_t)stream;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane % LPR, sub = lane / LPR;
+    const int m = st.m[sid];
+    const char *X = st.X + sid * (size_t)st.Mcap * ROWB;
+    for (int r0 = wave * RPW; r0 < m; r0 += RPB) {
+        const int r = r0 + sub;
+        float x[VEC];
+        unpack<BF16>(ld16(X + (size_t)(r < m ? r : m - 1) * ROWB + col * 16), x);
+        double a = 0.0;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) a = fma((double)x[v], (double)x[v], a);
+        a = group_sum<LPR>(a);
+        if (r < m && col == 0) st.xn[sid * (size_t)st.McapS + r] = (float)a;
+    }
+}
+
 }  // namespace sg

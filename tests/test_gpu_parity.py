@@ -321,3 +321,30 @@ def test_matrix_core_path_exact_decisions_on_lattice_keys(g):
     for sid in range(S):
         assert state_tuple(ing, sid) == state_tuple(sg, sid)
         assert np.array_equal(ing.export_state(sid).assign, sg.export_state(sid).assign)
+
+
+@pytest.mark.parametrize("cfgname,g", [("cfg2", 1), ("cfg5", 4), ("cfg1b", 1)])
+def test_export_import_resumes_bit_identically(cfgname, g):
+    """Checkpoint / resume: a context restored from exported state continues exactly like the original
+    (the coins are counter-based, so there is no generator state to carry)."""
+    b = binding()
+    cfg = CONFIGS[cfgname].scaled(g=g)
+    S = 5
+    wl = Workload(cfg, device=DEV, streams=S)
+    delta = cfg.delta or 8.3
+    K, V = wl.tokens(0, 700)
+    Q = wl.queries(0, 700)
+    mk = lambda: b.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=g, seed=9, device=DEV)
+    a, c = mk(), mk()
+    a.ingest_prefix(K[:, :600], V[:, :600])
+    for sid in range(S):
+        c.import_raw(sid, a.export_raw(sid))
+    assert c.stats().n_seen == 600
+    for t in range(600, 700):
+        kt, vt, qt = K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()
+        assert torch.equal(a.step(kt, vt, qt), c.step(kt, vt, qt)), t
+    for sid in range(S):
+        assert state_tuple(a, sid) == state_tuple(c, sid)
+    # a second import must agree on the shared token counter
+    with pytest.raises(b.SubgenError):
+        c.import_raw(0, a.export_raw(0) | {"n_seen": 5})
