@@ -7,9 +7,12 @@
  *
  *   - UpdateSoftmaxNormalizer (Algorithm 1, procedure 1; Lemma 2): online
  *     threshold clustering of keys, one representative and one count per
- *     cluster.  The per-cluster reservoir S_i is collapsed to the
- *     representative x_i ("representative mode", t = 0), so the softmax
- *     normaliser is tau = sum_i n_i * exp(<q, x_i>).
+ *     cluster.  With t = 0 ("representative mode") the per-cluster reservoir
+ *     S_i is collapsed to the representative x_i, so the softmax normaliser
+ *     is tau = sum_i n_i * exp(<q, x_i>).  With t >= 1 the procedure is the
+ *     paper's: S_i holds t uniform samples of the cluster (each slot replaced
+ *     with probability 1/n_i on a join, t copies on creation; Lemma 2 (5)) and
+ *     tau = sum_i (n_i / t) sum_{k in S_i} exp(<q, k>).
  *   - UpdateMatrixProduct (Algorithm 1, procedure 2; Lemma 1): s independent
  *     slots, each overwritten with probability ||v||^2 / (mu + ||v||^2),
  *     followed by mu += ||v||^2 (main loop of Algorithm 1).
@@ -77,11 +80,23 @@ float sgo_uniform24(uint64_t seed, uint32_t stream, uint64_t token, uint32_t slo
     return (float)(r[slot % 4u] >> 8) * (1.0f / 16777216.0f);
 }
 
+/* Coins of the per-cluster reservoirs (UpdateSoftmaxNormalizer): same generator, a disjoint counter
+ * domain (top bit of the third counter word set), slot j of the reservoir of the cluster the token joins. */
+float sgo_uniform24_res(uint64_t seed, uint32_t stream, uint64_t token, uint32_t slot)
+{
+    uint32_t ctr[4] = { slot / 4u, (uint32_t)token, (uint32_t)(token >> 32) | 0x80000000u, stream };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t r[4];
+    philox4x32_10(ctr, key, r);
+    return (float)(r[slot % 4u] >> 8) * (1.0f / 16777216.0f);
+}
+
 /* ------------------------------------------------------------------------
  * State of one stream
  * ---------------------------------------------------------------------- */
 typedef struct sgo_stream {
     int d, s, w;
+    int t;                    /* reservoir slots per cluster; 0 = representative mode */
     int max_centers;          /* 0 = unbounded */
     double delta;
     uint64_t seed;
@@ -97,6 +112,7 @@ typedef struct sgo_stream {
     /* D = {(x_i, n_i)}: representatives and counts */
     float *X;
     int64_t *cnt;
+    float *R;                 /* [cap][t][d]: per-cluster reservoirs S_i (t >= 1) */
     int m, cap;
 
     /* M: s sampled (k, v) pairs, the token each came from, its ||v||^2 */
@@ -115,12 +131,12 @@ typedef struct sgo_stream {
     int overflowed;           /* a token was force-joined because max_centers was hit */
 } sgo_stream;
 
-sgo_stream *sgo_create(int d, double delta, int s, int w, uint64_t seed, uint32_t stream, int max_centers)
+sgo_stream *sgo_create(int d, double delta, int s, int w, uint64_t seed, uint32_t stream, int max_centers, int t)
 {
-    if (d < 1 || s < 1 || w < 0 || !(delta >= 0.0)) return NULL;
+    if (d < 1 || s < 1 || w < 0 || t < 0 || !(delta >= 0.0)) return NULL;
     sgo_stream *o = (sgo_stream *)calloc(1, sizeof(sgo_stream));
     if (!o) return NULL;
-    o->d = d; o->s = s; o->w = w; o->max_centers = max_centers;
+    o->d = d; o->s = s; o->w = w; o->t = t; o->max_centers = max_centers;
     o->delta = delta; o->seed = seed; o->stream = stream;
     o->win_k = (float *)calloc((size_t)(w > 0 ? w : 1) * d, sizeof(float));
     o->win_v = (float *)calloc((size_t)(w > 0 ? w : 1) * d, sizeof(float));
@@ -137,7 +153,7 @@ void sgo_destroy(sgo_stream *o)
 {
     if (!o) return;
     free(o->win_k); free(o->win_v); free(o->win_idx);
-    free(o->X); free(o->cnt);
+    free(o->X); free(o->cnt); free(o->R);
     free(o->Mk); free(o->Mv); free(o->Midx); free(o->Mvn);
     free(o->assign); free(o->created); free(o->dist1); free(o->dist2);
     free(o);
@@ -149,9 +165,12 @@ static void append_center(sgo_stream *o, const float *k)
         int ncap = o->cap ? 2 * o->cap : 64;
         o->X = (float *)realloc(o->X, (size_t)ncap * o->d * sizeof(float));
         o->cnt = (int64_t *)realloc(o->cnt, (size_t)ncap * sizeof(int64_t));
+        if (o->t > 0) o->R = (float *)realloc(o->R, (size_t)ncap * o->t * o->d * sizeof(float));
         o->cap = ncap;
     }
     memcpy(o->X + (size_t)o->m * o->d, k, (size_t)o->d * sizeof(float));
+    for (int j = 0; j < o->t; ++j)   /* a new cluster's reservoir is t copies of its first key */
+        memcpy(o->R + ((size_t)o->m * o->t + j) * o->d, k, (size_t)o->d * sizeof(float));
     o->cnt[o->m] = 1;
     o->m += 1;
 }
@@ -177,7 +196,18 @@ static void log_decision(sgo_stream *o, int32_t a, int is_new, double d1, double
  * (tested on squared values), else open a new cluster whose representative
  * is k.  When a capacity is set and reached the token joins its nearest
  * cluster regardless of delta. */
-static void cluster_update(sgo_stream *o, const float *k)
+/* On a join with t >= 1 every reservoir slot of that cluster is replaced by k with probability 1/n_i,
+ * n_i being the count after the increment (reservoir sampling, Lemma 2 (5)). */
+static void reservoir_update(sgo_stream *o, int i, int64_t token, const float *k)
+{
+    const float p = 1.0f / (float)o->cnt[i];
+    for (int j = 0; j < o->t; ++j) {
+        float u = sgo_uniform24_res(o->seed, o->stream, (uint64_t)token, (uint32_t)j);
+        if (u < p) memcpy(o->R + ((size_t)i * o->t + j) * o->d, k, (size_t)o->d * sizeof(float));
+    }
+}
+
+static void cluster_update(sgo_stream *o, int64_t token, const float *k)
 {
     const int d = o->d;
     double best = INFINITY, second = INFINITY;
@@ -195,9 +225,11 @@ static void cluster_update(sgo_stream *o, const float *k)
     const double thr = o->delta * o->delta;
     if (arg >= 0 && best <= thr) {
         o->cnt[arg] += 1;
+        reservoir_update(o, arg, token, k);
         log_decision(o, arg, 0, best, second);
     } else if (arg >= 0 && o->max_centers > 0 && o->m >= o->max_centers) {
         o->cnt[arg] += 1;
+        reservoir_update(o, arg, token, k);
         o->overflowed = 1;
         log_decision(o, arg, 0, best, second);
     } else {
@@ -238,7 +270,7 @@ void sgo_update(sgo_stream *o, const float *k, const float *v)
     const int64_t i = o->n_seen;
     o->n_seen += 1;
     if (o->w == 0) {
-        cluster_update(o, k);
+        cluster_update(o, i, k);
         sample_update(o, i, k, v);
         o->n_evicted += 1;
         return;
@@ -248,7 +280,7 @@ void sgo_update(sgo_stream *o, const float *k, const float *v)
         const float *ek = o->win_k + (size_t)slot * d;
         const float *ev = o->win_v + (size_t)slot * d;
         const int64_t ei = o->win_idx[slot];
-        cluster_update(o, ek);
+        cluster_update(o, ei, ek);
         sample_update(o, ei, ek, ev);
         o->n_evicted += 1;
     }
@@ -265,7 +297,8 @@ static double dotd(const float *a, const float *b, int d)
 }
 
 /* QueryStreamAttn with the window:
- *   den = sum_{j in W} e^{<q,k_j>} + sum_i n_i e^{<q,x_i>}
+ *   den = sum_{j in W} e^{<q,k_j>} + sum_i n_i e^{<q,x_i>}        (t = 0)
+ *       = sum_{j in W} e^{<q,k_j>} + sum_i (n_i/t) sum_{k in S_i} e^{<q,k>}   (t >= 1)
  *   num = sum_{j in W} e^{<q,k_j>} v_j + sum_{j in [s]} mu/(s ||v_j||^2) e^{<q,k_j>} v_j
  * every exponent shifted by the largest score.  Returns 0, or -1 if no token
  * has been seen.  Optionally reports den*e^{mx} pieces for tests. */
@@ -281,9 +314,16 @@ int sgo_attend(const sgo_stream *o, const float *q, double *out, double *den_out
         double a = dotd(q, o->win_k + (size_t)j * d, d);
         if (a > mx) mx = a;
     }
-    for (int i = 0; i < o->m; ++i) {
-        double b = dotd(q, o->X + (size_t)i * d, d);
-        if (b > mx) mx = b;
+    if (o->t == 0) {
+        for (int i = 0; i < o->m; ++i) {
+            double b = dotd(q, o->X + (size_t)i * d, d);
+            if (b > mx) mx = b;
+        }
+    } else {
+        for (int r = 0; r < o->m * o->t; ++r) {
+            double b = dotd(q, o->R + (size_t)r * d, d);
+            if (b > mx) mx = b;
+        }
     }
     if (have_samples)
         for (int j = 0; j < o->s; ++j) {
@@ -298,8 +338,16 @@ int sgo_attend(const sgo_stream *o, const float *q, double *out, double *den_out
         den += e;
         for (int c = 0; c < d; ++c) out[c] += e * (double)o->win_v[(size_t)j * d + c];
     }
-    for (int i = 0; i < o->m; ++i)
-        den += (double)o->cnt[i] * exp(dotd(q, o->X + (size_t)i * d, d) - mx);
+    if (o->t == 0) {
+        for (int i = 0; i < o->m; ++i)
+            den += (double)o->cnt[i] * exp(dotd(q, o->X + (size_t)i * d, d) - mx);
+    } else {   /* tau = sum_i (n_i / t) sum_{k in S_i} e^{<q,k>} */
+        for (int i = 0; i < o->m; ++i) {
+            double si = 0.0;
+            for (int j = 0; j < o->t; ++j) si += exp(dotd(q, o->R + ((size_t)i * o->t + j) * d, d) - mx);
+            den += (double)o->cnt[i] / (double)o->t * si;
+        }
+    }
     if (have_samples)
         for (int j = 0; j < o->s; ++j) {
             double vn = (double)o->Mvn[j];
@@ -342,6 +390,7 @@ int64_t sgo_n_evicted(const sgo_stream *o) { return o->n_evicted; }
 double sgo_mu(const sgo_stream *o) { return o->mu; }
 int sgo_overflowed(const sgo_stream *o) { return o->overflowed; }
 const float *sgo_centers(const sgo_stream *o) { return o->X; }
+const float *sgo_reservoirs(const sgo_stream *o) { return o->R; }
 const int64_t *sgo_counts(const sgo_stream *o) { return o->cnt; }
 const float *sgo_sample_k(const sgo_stream *o) { return o->Mk; }
 const float *sgo_sample_v(const sgo_stream *o) { return o->Mv; }

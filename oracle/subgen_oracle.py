@@ -45,7 +45,7 @@ def _load():
     fp = C.POINTER(C.c_float)
     dp = C.POINTER(C.c_double)
     L.sgo_create.restype = P
-    L.sgo_create.argtypes = [C.c_int, C.c_double, C.c_int, C.c_int, C.c_uint64, C.c_uint32, C.c_int]
+    L.sgo_create.argtypes = [C.c_int, C.c_double, C.c_int, C.c_int, C.c_uint64, C.c_uint32, C.c_int, C.c_int]
     L.sgo_destroy.argtypes = [P]
     L.sgo_update.argtypes = [P, fp, fp]
     L.sgo_attend.restype = C.c_int
@@ -55,12 +55,14 @@ def _load():
     L.sgo_decode.argtypes = [P, fp, fp, fp, C.c_int64, C.c_int, dp]
     L.sgo_uniform24.restype = C.c_float
     L.sgo_uniform24.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32]
+    L.sgo_uniform24_res.restype = C.c_float
+    L.sgo_uniform24_res.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32]
     L.sgo_philox4x32_10.argtypes = [C.POINTER(C.c_uint32)] * 3
     for name, rt in [("sgo_m", C.c_int), ("sgo_n_seen", C.c_int64), ("sgo_n_evicted", C.c_int64),
                      ("sgo_mu", C.c_double), ("sgo_overflowed", C.c_int)]:
         getattr(L, name).restype = rt
         getattr(L, name).argtypes = [P]
-    for name in ["sgo_centers", "sgo_counts", "sgo_sample_k", "sgo_sample_v", "sgo_sample_idx", "sgo_sample_vn",
+    for name in ["sgo_centers", "sgo_reservoirs", "sgo_counts", "sgo_sample_k", "sgo_sample_v", "sgo_sample_idx", "sgo_sample_vn",
                  "sgo_window_k", "sgo_window_v", "sgo_window_idx", "sgo_assign", "sgo_created", "sgo_dist1",
                  "sgo_dist2"]:
         getattr(L, name).restype = P
@@ -90,16 +92,22 @@ def uniform24(seed: int, stream: int, token: int, slot: int) -> float:
     return float(_load().sgo_uniform24(seed, stream, token, slot))
 
 
+def uniform24_res(seed: int, stream: int, token: int, slot: int) -> float:
+    """Coin of reservoir slot `slot` of the cluster that `token` joins (t >= 1)."""
+    return float(_load().sgo_uniform24_res(seed, stream, token, slot))
+
+
 class OracleStream:
     """One (sequence, layer, head) stream of the oracle."""
 
     def __init__(self, d: int, delta: float, s: int, w: int, seed: int = 0, stream: int = 0,
-                 max_centers: int = 0):
+                 max_centers: int = 0, t: int = 0):
         self._L = _load()
         # delta is a float32 at the library boundary; the oracle squares its double value
         self.delta = float(np.float32(delta))
-        self.d, self.s, self.w = int(d), int(s), int(w)
-        self._h = self._L.sgo_create(self.d, self.delta, self.s, self.w, int(seed), int(stream), int(max_centers))
+        self.d, self.s, self.w, self.t = int(d), int(s), int(w), int(t)
+        self._h = self._L.sgo_create(self.d, self.delta, self.s, self.w, int(seed), int(stream), int(max_centers),
+                                     self.t)
         if not self._h:
             raise ValueError("invalid oracle parameters")
 
@@ -178,6 +186,11 @@ class OracleStream:
     @property
     def centers(self):
         return self._arr("sgo_centers", np.float32, (self.m, self.d))
+
+    @property
+    def reservoirs(self):
+        """Per-cluster reservoirs S_i as [m, t, d] (t >= 1)."""
+        return self._arr("sgo_reservoirs", np.float32, (self.m, self.t, self.d))
 
     @property
     def counts(self):

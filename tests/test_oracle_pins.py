@@ -421,3 +421,135 @@ def test_exact_attention_against_library_softmax_and_uniform_case():
     ref = torch.softmax(torch.from_numpy(K) @ torch.from_numpy(q), 0) @ torch.from_numpy(V)
     assert np.allclose(exact_attention(K, V, q), ref.numpy(), rtol=1e-12)
     assert np.allclose(exact_attention(np.zeros((7, 3)), V[:7, :3], q[:3]), V[:7, :3].mean(0), rtol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# per-cluster reservoirs S_i (t >= 1): Algorithm 1 as printed (UpdateSoftmaxNormalizer, Lemma 2 (5),
+# the tau line of QueryStreamAttn, Theorem 1's bound on tau)
+# --------------------------------------------------------------------------
+from oracle.subgen_oracle import uniform24_res  # noqa: E402
+
+
+def test_reservoir_coin_counter_layout():
+    seed, stream, token = 0x0123456789ABCDEF, 5, (3 << 32) + 77
+    for slot in [0, 1, 5, 63]:
+        words = philox4x32_10([slot // 4, token & 0xFFFFFFFF, (token >> 32) | 0x80000000, stream],
+                              [seed & 0xFFFFFFFF, seed >> 32])
+        assert uniform24_res(seed, stream, token, slot) == (words[slot % 4] >> 8) / 2.0 ** 24
+        assert uniform24_res(seed, stream, token, slot) != uniform24(seed, stream, token, slot)
+
+
+def test_reservoir_does_not_change_clustering_or_sampling():
+    r = rng(20)
+    n, d = 300, 6
+    K = (r.normal(size=(8, d))[r.integers(0, 8, size=n)] * 3 + 0.3 * r.normal(size=(n, d))).astype(np.float32)
+    V = r.normal(size=(n, d)).astype(np.float32)
+    a = OracleStream(d, 1.2, s=8, w=4, seed=3)
+    b = OracleStream(d, 1.2, s=8, w=4, seed=3, t=3)
+    a.ingest(K, V)
+    b.ingest(K, V)
+    assert np.array_equal(a.assign, b.assign) and np.array_equal(a.counts, b.counts)
+    assert np.array_equal(a.sample_idx, b.sample_idx) and a.mu == b.mu
+    # every reservoir entry is a member of its own cluster (Lemma 2 (5): samples from C_i)
+    ev = K[: n - 4]
+    R = b.reservoirs
+    for i in range(b.m):
+        members = ev[b.assign == i]
+        for j in range(3):
+            assert (members == R[i, j]).all(axis=1).any()
+
+
+def test_new_cluster_reservoir_is_t_copies_and_second_member_probability_half():
+    o = OracleStream(1, 1.0, s=1, w=0, t=5)
+    o.update([7.0], [1.0])
+    assert np.array_equal(o.reservoirs, np.full((1, 5, 1), 7.0, dtype=np.float32))
+    # second member of the cluster: each slot is replaced with probability 1/2
+    t = 20000
+    o = OracleStream(1, 1.0, s=1, w=0, t=t, seed=4)
+    o.update([0.0], [1.0])
+    o.update([0.5], [1.0])
+    frac = (o.reservoirs[0, :, 0] == 0.5).mean()
+    assert abs(frac - 0.5) < 5 * math.sqrt(0.25 / t)
+
+
+def test_lemma2_reservoir_is_uniform_over_the_cluster_and_slots_independent():
+    # one cluster of 9 distinguishable members (all within delta of the first)
+    keys = np.array([[0.01 * i] for i in range(9)], dtype=np.float32)
+    seeds = 5000
+    hist = np.zeros((3, 9))
+    joint = np.zeros((9, 9))
+    for seed in range(seeds):
+        o = OracleStream(1, 1.0, s=1, w=0, t=3, seed=seed)
+        o.ingest(keys, np.ones((9, 1)))
+        assert o.m == 1
+        idx = np.rint(o.reservoirs[0, :, 0] / 0.01).astype(int)
+        hist[np.arange(3), idx] += 1
+        joint[idx[0], idx[1]] += 1
+    for j in range(3):   # chi-square, 8 dof: 99.99% quantile ~ 31
+        chi = ((hist[j] - seeds / 9.0) ** 2 / (seeds / 9.0)).sum()
+        assert chi < 36.0, (j, chi)
+    exp = seeds / 81.0
+    chi = ((joint - exp) ** 2 / exp).sum()   # 80 dof
+    assert chi < 80 + 6 * math.sqrt(160)
+
+
+def test_tau_is_unbiased_and_tightens_with_t():
+    # E[(n_i/t) sum_{k in S_i} e^{<q,k>}] = sum_{k in C_i} e^{<q,k>}: the mean of tau over seeds is the exact
+    # partition function, and its spread shrinks like 1/sqrt(t) (the proof of Theorem 1 uses exactly this)
+    r = rng(21)
+    n, d, delta = 240, 6, 2.0
+    K = (r.normal(size=(6, d))[r.integers(0, 6, size=n)] * 2.5 + 0.45 * r.normal(size=(n, d))).astype(np.float32)
+    V = r.normal(size=(n, d)).astype(np.float32)
+    q = (r.normal(size=d) * 0.8).astype(np.float32)
+    Z = np.exp(K.astype(np.float64) @ q.astype(np.float64)).sum()
+    spread = {}
+    for t in (1, 16):
+        taus = []
+        for seed in range(1500 if t == 1 else 300):
+            o = OracleStream(d, delta, s=2, w=5, seed=seed, t=t)
+            o.ingest(K, V)
+            assert o.m < n // 3
+            _, den, mx = o.attend(q, return_den=True)
+            taus.append(den * math.exp(mx))
+        taus = np.array(taus)
+        sem = taus.std() / math.sqrt(len(taus))
+        assert abs(taus.mean() - Z) < 4.5 * sem, (t, taus.mean(), Z, sem)
+        spread[t] = taus.std() / Z
+    assert spread[1] > 0.01                       # a single sample per cluster is visibly noisy ...
+    assert 2.5 < spread[1] / spread[16] < 6.5     # ... and 16 samples cut the noise about 4-fold
+    # representative mode on the same data is deterministic but biased: it is not the exact Z
+    o = OracleStream(d, delta, s=2, w=5)
+    o.ingest(K, V)
+    _, den, mx = o.attend(q, return_den=True)
+    assert abs(den * math.exp(mx) / Z - 1.0) > 1e-3
+
+
+def test_tau_within_one_plus_minus_eps_for_large_t():
+    # Theorem 1 (tau bound): with t of the order eps^-2 e^{2 delta r} log n, tau is within (1 +- eps/3) Z
+    r = rng(22)
+    n, d, delta = 400, 8, 1.0
+    K = (r.normal(size=(10, d))[r.integers(0, 10, size=n)] * 3 + 0.2 * r.normal(size=(n, d))).astype(np.float32)
+    V = r.normal(size=(n, d)).astype(np.float32)
+    q = (r.normal(size=d) / math.sqrt(d)).astype(np.float32)
+    rq = float(np.linalg.norm(q))
+    eps = 0.3
+    t = int(math.ceil(eps ** -2 * math.exp(2 * delta * rq) * math.log(n)))
+    Z = np.exp(K.astype(np.float64) @ q.astype(np.float64)).sum()
+    bad = 0
+    for seed in range(120):
+        o = OracleStream(d, delta, s=2, w=0, seed=seed, t=t)
+        o.ingest(K, V)
+        _, den, mx = o.attend(q, return_den=True)
+        bad += abs(den * math.exp(mx) / Z - 1.0) > eps / 3
+    assert bad <= 1, (bad, t)
+
+
+def test_delta_zero_reservoirs_give_exact_partition_function():
+    r = rng(23)
+    n, d = 150, 5
+    K = r.normal(size=(25, d)).astype(np.float32)[r.integers(0, 25, size=n)]
+    o = OracleStream(d, 0.0, s=4, w=3, t=2, seed=1)
+    o.ingest(K, r.normal(size=(n, d)))
+    q = r.normal(size=d).astype(np.float32)
+    _, den, mx = o.attend(q, return_den=True)
+    assert den * math.exp(mx) == pytest.approx(np.exp(K.astype(np.float64) @ q.astype(np.float64)).sum(), rel=1e-12)
