@@ -31,13 +31,14 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {"cfg3": 4.0381e9}
 
 
-def algorithmic_bytes(cfg, streams, total_centers):
+def algorithmic_bytes(cfg, streams, total_centers, t=0):
     """Bytes one decode step must move: every row of the state once, plus the new token, queries, output."""
     e, d, s, w, g = cfg.elem_bytes, cfg.d, cfg.s, cfg.w, cfg.g
     per_stream = e * d * (2 * s + 2 * w) + 4 * s          # sampled K,V rows + ||v||^2, window K,V rows
     per_stream += e * d * (2 + g) + 4 * g * d             # read K_t, V_t, g queries; write g fp32 outputs
     per_stream += 2 * e * d + 2 * e * d                   # write the new token into the ring, read the evicted one
-    return streams * per_stream + total_centers * (e * d + 4)   # center rows + counts, read once
+    # center rows + counts, read once; with per-cluster reservoirs also the t sampled keys of every cluster
+    return streams * per_stream + total_centers * (e * d * (1 + t) + 4)
 
 
 # --------------------------------------------------------------------------------------
@@ -111,6 +112,7 @@ def main():
     ap.add_argument("--prefix", type=int, default=-1, help="override the prefix length (debugging)")
     ap.add_argument("--delta", type=float, default=0.0, help="skip tuning and use this threshold")
     ap.add_argument("--split", action="store_true", help="time subgen_update + subgen_attend instead of subgen_step")
+    ap.add_argument("--t", type=int, default=0, help="per-cluster reservoir slots (0 = representative mode)")
     ap.add_argument("--generic", action="store_true", help="force the generic vector-ALU kernels (kernel_path = 1)")
     ap.add_argument("--no-exact", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -149,7 +151,8 @@ def main():
     wl = Workload(cfg, device=dev, streams=S)
     max_centers = max(2048, 3 * (cfg.target_centers or 1024))
     sg = binding.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=cfg.g,
-                        max_centers=max_centers, seed=0, device=dev, kernel_path=1 if a.generic else 0)
+                        max_centers=max_centers, seed=0, device=dev, kernel_path=1 if a.generic else 0,
+                        t_per_cluster=a.t)
 
     # ---- prefix: generate on the device block by block, ingest; keep it resident for the exact kernel
     keep = not a.no_exact
@@ -218,7 +221,7 @@ def main():
     st1 = sg.stats()
     kernel_ms = sum(x.elapsed_time(y) for x, y in zip(ev0, ev1)) / steps
     total_centers = 0.5 * (m_before + st1.total_centers)
-    alg = algorithmic_bytes(cfg, S, total_centers)
+    alg = algorithmic_bytes(cfg, S, total_centers, a.t)
     if a.split:
         alg += total_centers * cfg.elem_bytes * cfg.d      # the split path reads the center table twice
     achieved = alg / (kernel_ms * 1e-3) / 1e9
@@ -260,7 +263,7 @@ def main():
             "workload": f"{name}: {S} streams (batch {cfg.batch} x {cfg.layers} layers x {cfg.kv_heads} KV heads), "
                         f"g={cfg.g}, d={cfg.d}, {cfg.dtype}, prefix n={a.prefix}, s={cfg.s}, w={cfg.w}, "
                         f"{cfg.components}-component clustered keys",
-            "entry_point": kernel, "streams": S, "delta": delta, "mean_centers": total_centers / S,
+            "entry_point": kernel, "streams": S, "delta": delta, "t_per_cluster": a.t, "mean_centers": total_centers / S,
             "min_centers": st1.min_centers, "max_centers": st1.max_centers, "flags": st1.flags_or,
             "prefix_ingest_s": ingest_s, "prefix_ingest_tokens_per_s": S * a.prefix / max(ingest_s, 1e-9),
             "setup_s": setup_s,
@@ -268,7 +271,8 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(a.config) if (not a.split and S == cfg.streams
-                                                                    and a.prefix == cfg.prefix) else None,
+                                                                    and a.prefix == cfg.prefix and a.t == 0
+                                                                    and not a.generic) else None,
             "kernel": kernel, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": alg,
         },
         "cpu_baseline": cpu,

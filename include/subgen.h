@@ -75,7 +75,10 @@ typedef struct subgen_opts {
     int32_t kernel_path;    /* 0 = automatic (bf16 rows are scored on the matrix cores where the shape allows);
                                1 = always the generic vector-ALU kernels (any dtype; same results up to fp32
                                rounding of the outputs, identical decisions)                               */
-    int32_t reserved;       /* must be 0                                                                   */
+    int32_t t_per_cluster;  /* t: reservoir slots per cluster.  0 (default) = representative mode: the normaliser is
+                               sum_i n_i e^{<q,x_i>}.  t >= 1 = Algorithm 1 as printed: every cluster keeps t uniform
+                               samples S_i of its keys and the normaliser is sum_i (n_i/t) sum_{k in S_i} e^{<q,k>}
+                               (Lemma 2 (5), QueryStreamAttn); at most 64                                      */
 } subgen_opts;
 
 /*
@@ -103,7 +106,7 @@ int subgen_update(subgen_ctx *ctx, const void *K_t, const void *V_t);
 
 /*
  * subgen_attend — QueryStreamAttn (Algorithm 1) plus the exact window terms:
- *   den = sum_{j in W} e^{<q,k_j>} + sum_i n_i e^{<q,x_i>}
+ *   den = sum_{j in W} e^{<q,k_j>} + sum_i n_i e^{<q,x_i>}      (or the t-sample form, see t_per_cluster)
  *   num = sum_{j in W} e^{<q,k_j>} v_j + sum_{j in M} mu / (s ||v_j||^2) e^{<q,k_j>} v_j
  *   out = num / den      (a common maximum is subtracted from every exponent; fp32 accumulation)
  *   Q_t   device, [streams, g, d] contiguous, context dtype
@@ -194,6 +197,7 @@ typedef struct subgen_state_view {
     int64_t assign_cap;       /* in: entries assign can hold                              */
     int32_t *assign;          /* host: center index of evicted token 0.. (needs assign_log_tokens > 0) */
     int64_t assign_len;       /* out: entries written                                     */
+    void *reservoirs;         /* host [centers_cap, t, d]: S_i of every cluster (t_per_cluster >= 1) */
 } subgen_state_view;
 
 int subgen_export_state(subgen_ctx *ctx, int64_t stream, subgen_state_view *host_view);

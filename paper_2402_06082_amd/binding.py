@@ -37,7 +37,7 @@ class subgen_opts(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("dtype", C.c_int32), ("q_per_stream", C.c_int32),
                 ("max_centers", C.c_int32), ("assign_log_tokens", C.c_int64), ("seed", C.c_uint64),
                 ("hip_stream", C.c_void_p), ("device", C.c_int32), ("device_set", C.c_int32),
-                ("kernel_path", C.c_int32), ("reserved", C.c_int32)]
+                ("kernel_path", C.c_int32), ("t_per_cluster", C.c_int32)]
 
 
 class subgen_stats_t(C.Structure):
@@ -52,7 +52,8 @@ class subgen_state_view(C.Structure):
                 ("centers_cap", C.c_int64), ("centers", C.c_void_p), ("counts", C.c_void_p),
                 ("sample_K", C.c_void_p), ("sample_V", C.c_void_p), ("sample_idx", C.c_void_p),
                 ("sample_vn", C.c_void_p), ("window_K", C.c_void_p), ("window_V", C.c_void_p),
-                ("assign_cap", C.c_int64), ("assign", C.c_void_p), ("assign_len", C.c_int64)]
+                ("assign_cap", C.c_int64), ("assign", C.c_void_p), ("assign_len", C.c_int64),
+                ("reservoirs", C.c_void_p)]
 
 
 def lib_path() -> Path:
@@ -136,7 +137,7 @@ def _rows_to_f32(a: np.ndarray) -> np.ndarray:
 class StreamState:
     """Host copy of one stream's state (rows converted to float32 values)."""
     __slots__ = ("m", "n_seen", "n_evicted", "mu", "flags", "window_fill", "centers", "counts", "sample_k",
-                 "sample_v", "sample_idx", "sample_vn", "window_k", "window_v", "assign")
+                 "sample_v", "sample_idx", "sample_vn", "window_k", "window_v", "assign", "reservoirs")
 
 
 class SubGen:
@@ -145,7 +146,7 @@ class SubGen:
     def __init__(self, streams: int, d: int, delta: float, sample_budget: int, window: int, *,
                  dtype: torch.dtype = torch.float32, q_per_stream: int = 1, max_centers: int = 0,
                  assign_log_tokens: int = 0, seed: int = 0, device: Optional[torch.device] = None,
-                 kernel_path: int = 0):
+                 kernel_path: int = 0, t_per_cluster: int = 0):
         self._L = load()
         self._h = C.c_void_p()
         if not torch.cuda.is_available():
@@ -169,6 +170,7 @@ class SubGen:
         o.device = self.device.index or 0
         o.device_set = 1
         o.kernel_path = int(kernel_path)
+        o.t_per_cluster = self.t = int(t_per_cluster)
         _check(self._L.subgen_create(C.byref(self._h), self.streams, self.d, C.c_float(self.delta), self.s, self.w,
                                      C.byref(o)), "subgen_create")
 
@@ -250,6 +252,8 @@ class SubGen:
             "window_K": _np_rows(self.dtype_code, max(self.w, 1), self.d),
             "window_V": _np_rows(self.dtype_code, max(self.w, 1), self.d),
         }
+        if self.t > 0:
+            bufs["reservoirs"] = _np_rows(self.dtype_code, cap * self.t, self.d)
         v.centers_cap = cap
         for k, a in bufs.items():
             setattr(v, k, a.ctypes.data)
@@ -263,8 +267,10 @@ class SubGen:
         v.struct_size = C.sizeof(subgen_state_view)
         v.m, v.n_seen, v.mu, v.flags = state["m"], state["n_seen"], state["mu"], state["flags"]
         v.centers_cap = state["centers"].shape[0]
-        for k in ("centers", "counts", "sample_K", "sample_V", "sample_idx", "sample_vn", "window_K", "window_V"):
-            setattr(v, k, np.ascontiguousarray(state[k]).ctypes.data)
+        for k in ("centers", "counts", "sample_K", "sample_V", "sample_idx", "sample_vn", "window_K", "window_V",
+                  "reservoirs"):
+            if k in state:
+                setattr(v, k, np.ascontiguousarray(state[k]).ctypes.data)
         _check(self._L.subgen_import_state(self._h, int(stream), C.byref(v)), "subgen_import_state")
 
     def export_state(self, stream: int, rows: bool = True) -> StreamState:
@@ -284,6 +290,10 @@ class SubGen:
             wk, wv = _np_rows(self.dtype_code, self.w, self.d), _np_rows(self.dtype_code, self.w, self.d)
             v.centers, v.sample_K, v.sample_V = centers.ctypes.data, sk.ctypes.data, sv.ctypes.data
             v.window_K, v.window_V = wk.ctypes.data, wv.ctypes.data
+        res = None
+        if rows and self.t > 0:
+            res = _np_rows(self.dtype_code, cap * self.t, self.d)
+            v.reservoirs = res.ctypes.data
         assign = None
         if self.assign_log_tokens > 0:
             assign = np.zeros(self.assign_log_tokens, dtype=np.int32)
@@ -299,7 +309,10 @@ class SubGen:
             st.centers = _rows_to_f32(centers[: v.m])
             st.sample_k, st.sample_v = _rows_to_f32(sk), _rows_to_f32(sv)
             st.window_k, st.window_v = _rows_to_f32(wk)[: v.window_fill], _rows_to_f32(wv)[: v.window_fill]
+            st.reservoirs = (_rows_to_f32(res)[: v.m * self.t].reshape(v.m, self.t, self.d)
+                             if res is not None else None)
         else:
+            st.reservoirs = None
             st.centers = st.sample_k = st.sample_v = st.window_k = st.window_v = None
         return st
 

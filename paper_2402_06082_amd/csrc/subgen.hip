@@ -15,6 +15,7 @@
 #include "subgen_mfma_device.hpp"
 #include "ingest_mfma_device.hpp"
 #include "subgen_dot2_device.hpp"
+#include "subgen_res_device.hpp"
 
 using sg::Call;
 using sg::State;
@@ -142,9 +143,53 @@ void launch_mfma(int NK, int G, Mode mode, dim3 grid, hipStream_t s, const State
     }
 }
 
+template <bool BF16, int LPR, int G>
+void launch_res_mode(Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    switch (mode) {
+        case MODE_UPDATE:
+            hipLaunchKernelGGL((sg::decode_res_kernel<BF16, LPR, 1, true, false>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+        case MODE_ATTEND:
+            hipLaunchKernelGGL((sg::decode_res_kernel<BF16, LPR, G, false, true>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+        case MODE_STEP:
+            hipLaunchKernelGGL((sg::decode_res_kernel<BF16, LPR, G, true, true>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+    }
+}
+
+template <bool BF16, int LPR>
+void launch_res_g(int G, Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    if (G == 1) launch_res_mode<BF16, LPR, 1>(mode, grid, s, st, call);
+    else if (G == 2) launch_res_mode<BF16, LPR, 2>(mode, grid, s, st, call);
+    else launch_res_mode<BF16, LPR, 4>(mode, grid, s, st, call);
+}
+
+// contexts with per-cluster reservoirs (t >= 1); MODE_UPDATE with n_tokens > 1 is the prefix ingest
+void launch_res(subgen_ctx *c, Mode mode, const Call &call)
+{
+    const dim3 grid((unsigned)c->S);
+    if (c->dtype == SUBGEN_BF16) {
+        if (c->LPR == 8) launch_res_g<true, 8>(c->G, mode, grid, c->stream, c->st, call);
+        else if (c->LPR == 16) launch_res_g<true, 16>(c->G, mode, grid, c->stream, c->st, call);
+        else launch_res_g<true, 32>(c->G, mode, grid, c->stream, c->st, call);
+    } else {
+        if (c->LPR == 8) launch_res_g<false, 8>(c->G, mode, grid, c->stream, c->st, call);
+        else if (c->LPR == 16) launch_res_g<false, 16>(c->G, mode, grid, c->stream, c->st, call);
+        else launch_res_g<false, 32>(c->G, mode, grid, c->stream, c->st, call);
+    }
+}
+
 int launch_decode(subgen_ctx *c, Mode mode, const Call &call)
 {
     const dim3 grid((unsigned)c->S);
+    if (c->st.t > 0) {
+        launch_res(c, mode, call);
+        const hipError_t e = hipGetLastError();
+        return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+    }
     // bf16 rows of 128 elements, one query per stream: whole-row loads (one contiguous 1 KB access per wavefront
     // load, which the memory system serves faster than the 64-byte pieces of the matrix-core operand layout)
     // with packed-bf16 dot products.  With several queries per stream the vector ALUs would be the bound, so
@@ -237,6 +282,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     if (G != 1 && G != 2 && G != 4) return SUBGEN_EINVAL;
     if (Mcap < 1 || Mcap > (1 << 24) || o.assign_log_tokens < 0) return SUBGEN_EINVAL;
     if (o.kernel_path != 0 && o.kernel_path != 1) return SUBGEN_EINVAL;
+    if (o.t_per_cluster < 0 || o.t_per_cluster > 64) return SUBGEN_EINVAL;
 
     subgen_ctx *c = new (std::nothrow) subgen_ctx();
     if (!c) return SUBGEN_ENOMEM;
@@ -251,10 +297,11 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     c->S = streams; c->d = d; c->s = sample_budget; c->w = window; c->Mcap = Mcap; c->G = G;
     c->dtype = o.dtype; c->esz = esz; c->LPR = d * esz / 16; c->delta = delta;
     c->stream = reinterpret_cast<hipStream_t>(o.hip_stream);
-    c->mfma = o.kernel_path == 0 && mfma_supported(o.dtype, c->LPR, G);
+    c->mfma = o.kernel_path == 0 && o.t_per_cluster == 0 && mfma_supported(o.dtype, c->LPR, G);
 
     State &st = c->st;
     st.Mcap = Mcap; st.s = sample_budget; st.w = window; st.d = d;
+    st.t = o.t_per_cluster;
     st.McapS = (Mcap + 15) / 16 * 16; st.sS = (sample_budget + 15) / 16 * 16;
     st.delta2 = (double)delta * (double)delta;
     st.seed_lo = (uint32_t)o.seed; st.seed_hi = (uint32_t)(o.seed >> 32);
@@ -262,6 +309,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     const size_t S = (size_t)streams, rowb = (size_t)d * esz;
     int rc = SUBGEN_OK;
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.X, S * Mcap * rowb, 0);
+    if (rc == SUBGEN_OK && st.t > 0) rc = dev_alloc(c, &st.R, S * Mcap * st.t * rowb, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.cnt, S * st.McapS, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.xn, S * st.McapS, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.m, S, 0);
@@ -347,7 +395,9 @@ int subgen_ingest_prefix(subgen_ctx *c, const void *K, const void *V, int64_t n,
         call.n_tokens = (n - t0 < kChunk) ? n - t0 : kChunk;
         call.n_seen = c->n_seen;
         const dim3 grid((unsigned)c->S);
-        if (c->mfma && c->LPR == 8)
+        if (c->st.t > 0)
+            launch_res(c, MODE_UPDATE, call);
+        else if (c->mfma && c->LPR == 8)
             hipLaunchKernelGGL((sg::ingest_mfma_kernel<2>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
         else if (c->mfma && c->LPR == 16)
             hipLaunchKernelGGL((sg::ingest_mfma_kernel<4>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
@@ -484,6 +534,10 @@ int subgen_export_state(subgen_ctx *c, int64_t stream, subgen_state_view *v)
     if ((v->centers || v->counts) && v->centers_cap < m) return SUBGEN_EINVAL;
     SG_D2H(v->centers, st.X + sid * c->Mcap * rowb, (size_t)m * rowb);
     SG_D2H(v->counts, st.cnt + sid * st.McapS, (size_t)m * sizeof(int32_t));
+    if (v->reservoirs != nullptr) {
+        if (st.t == 0 || v->centers_cap < m) return SUBGEN_EINVAL;
+        SG_D2H(v->reservoirs, st.R + sid * c->Mcap * st.t * rowb, (size_t)m * st.t * rowb);
+    }
     SG_D2H(v->sample_K, st.Ks + sid * c->s * rowb, (size_t)c->s * rowb);
     SG_D2H(v->sample_V, st.Vs + sid * c->s * rowb, (size_t)c->s * rowb);
     SG_D2H(v->sample_idx, st.sidx + sid * st.sS, (size_t)c->s * sizeof(int32_t));
@@ -508,6 +562,7 @@ int subgen_import_state(subgen_ctx *c, int64_t stream, const subgen_state_view *
     if (v->struct_size != sizeof(subgen_state_view)) return SUBGEN_EINVAL;
     if (v->m < 0 || v->m > c->Mcap || v->n_seen < 0 || !std::isfinite(v->mu) || v->mu < 0.0) return SUBGEN_EINVAL;
     if (v->m > 0 && (!v->centers || !v->counts)) return SUBGEN_EINVAL;
+    if (v->m > 0 && c->st.t > 0 && !v->reservoirs) return SUBGEN_EINVAL;
     if (!v->sample_K || !v->sample_V || !v->sample_idx || !v->sample_vn) return SUBGEN_EINVAL;
     if (c->w > 0 && (!v->window_K || !v->window_V)) return SUBGEN_EINVAL;
     // all streams of a context share one token counter: the first import into an untouched context sets it
@@ -530,6 +585,7 @@ int subgen_import_state(subgen_ctx *c, int64_t stream, const subgen_state_view *
     SG_H2D(st.flags + sid, &v->flags, sizeof(uint32_t));
     SG_H2D(st.X + sid * c->Mcap * rowb, v->centers, (size_t)m * rowb);
     SG_H2D(st.cnt + sid * st.McapS, v->counts, (size_t)m * sizeof(int32_t));
+    if (st.t > 0) SG_H2D(st.R + sid * c->Mcap * st.t * rowb, v->reservoirs, (size_t)m * st.t * rowb);
     SG_H2D(st.Ks + sid * c->s * rowb, v->sample_K, (size_t)c->s * rowb);
     SG_H2D(st.Vs + sid * c->s * rowb, v->sample_V, (size_t)c->s * rowb);
     SG_H2D(st.sidx + sid * st.sS, v->sample_idx, (size_t)c->s * sizeof(int32_t));

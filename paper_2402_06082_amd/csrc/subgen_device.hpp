@@ -34,6 +34,7 @@ constexpr int kUnroll = SG_UNROLL;  // row loads in flight per lane in the scans
 struct State {
     char *X;            // [S][Mcap][d]   cluster representatives x_i
     int32_t *cnt;       // [S][McapS]     cluster sizes n_i
+    char *R;            // [S][Mcap][t][d] per-cluster reservoirs S_i (t >= 1), else null
     float *xn;          // [S][McapS]     ||x_i||^2 (fp32 rounding of the exact sum), used by the MFMA path
     int32_t *m;         // [S]            number of clusters
     char *Ks, *Vs;      // [S][s][d]      sampled pairs M
@@ -45,6 +46,7 @@ struct State {
     int32_t *assign;    // [S][assign_cap] or null
     int64_t assign_cap;
     int32_t Mcap, s, w, d;
+    int32_t t;          // reservoir slots per cluster (0 = representative mode)
     int32_t McapS, sS;  // strides of the per-center / per-slot scalar arrays (Mcap, s rounded up to 16)
     double delta2;      // delta^2
     uint32_t seed_lo, seed_hi;

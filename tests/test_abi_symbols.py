@@ -36,4 +36,4 @@ def test_binding_struct_sizes_match_the_header_layout():
     from paper_2402_06082_amd import binding
     assert ctypes.sizeof(binding.subgen_opts) == 56
     assert ctypes.sizeof(binding.subgen_stats_t) == 56
-    assert ctypes.sizeof(binding.subgen_state_view) == 136
+    assert ctypes.sizeof(binding.subgen_state_view) == 144

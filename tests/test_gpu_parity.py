@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle.subgen_oracle import exact_attention
+from oracle.subgen_oracle import OracleStream, exact_attention
 from paper_2402_06082_amd.workloads import CONFIGS, Workload
 from tests.parity_util import REL_L2_TOL, compare_state, make_oracles, rel_l2, to_f32_np
 
@@ -348,3 +348,48 @@ def test_export_import_resumes_bit_identically(cfgname, g):
     # a second import must agree on the shared token counter
     with pytest.raises(b.SubgenError):
         c.import_raw(0, a.export_raw(0) | {"n_seen": 5})
+
+
+@pytest.mark.parametrize("dtype,d,g,t", [(torch.bfloat16, 128, 1, 1), (torch.bfloat16, 128, 4, 4),
+                                         (torch.float32, 64, 1, 3), (torch.bfloat16, 64, 2, 8)])
+def test_reservoir_mode_matches_the_oracle(dtype, d, g, t):
+    """t >= 1: Algorithm 1's per-cluster reservoirs S_i and the t-sample normaliser (update, step, attend,
+    ingest, export/import), bit-exact state and outputs within tolerance."""
+    b = binding()
+    cfg = CONFIGS["cfg2"].scaled(name="res", d=d, dtype="bf16" if dtype == torch.bfloat16 else "fp32", g=g,
+                                 kv_heads=4, s=48, w=7, components=12)
+    wl = Workload(cfg, device=DEV)
+    S, n, steps = wl.S, 420, 40
+    delta = cfg.sigma * (2 * d) ** 0.5 * 1.03
+    K, V = wl.tokens(0, n + steps)
+    Q = wl.queries(0, steps)
+    mk = lambda: b.SubGen(S, d, delta, cfg.s, cfg.w, dtype=dtype, q_per_stream=g, assign_log_tokens=n + steps,
+                          seed=6, device=DEV, t_per_cluster=t)
+    sg = mk()
+    oracles = [OracleStream(d, delta, cfg.s, cfg.w, seed=6, stream=i, t=t) for i in range(S)]
+    sg.ingest_prefix(K[:, :300], V[:, :300])
+    for tt in range(300, n):
+        sg.update(K[:, tt].contiguous(), V[:, tt].contiguous())
+    for o, k, v in zip(oracles, to_f32_np(K[:, :n]), to_f32_np(V[:, :n])):
+        o.ingest(k, v)
+
+    def check_state():
+        assert compare_state(sg, oracles) == 0
+        for i, o in enumerate(oracles):
+            assert np.array_equal(sg.export_state(i).reservoirs, o.reservoirs), i
+
+    check_state()
+    assert 5 <= sg.center_counts().min() and sg.center_counts().max() <= 200
+    outs = torch.stack([sg.step(K[:, n + s_].contiguous(), V[:, n + s_].contiguous(), Q[:, s_].contiguous())
+                        for s_ in range(steps)])
+    ref = np.stack([o.decode(to_f32_np(K[i, n:]), to_f32_np(V[i, n:]), to_f32_np(Q[i])) for i, o in enumerate(oracles)], 1)
+    assert rel_l2(outs.cpu().numpy(), ref).max() <= REL_L2_TOL
+    check_state()
+    # attend alone, and a context restored from exported state, give the same answers
+    qlast = Q[:, steps - 1].contiguous()
+    again = sg.attend(qlast)
+    assert rel_l2(again.cpu().numpy(), ref[steps - 1]).max() <= REL_L2_TOL
+    c = mk()
+    for sid in range(S):
+        c.import_raw(sid, sg.export_raw(sid))
+    assert torch.equal(c.attend(qlast), again)
