@@ -145,6 +145,26 @@ int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, 
                         void *hip_stream);
 
 /*
+ * subgen_kcenter_compress — one-shot greedy k-center compression of a prompt's KV cache (Section 3.2: the
+ * variant of the paper's line-retrieval experiment: the greedy k-center algorithm is applied once to the whole
+ * cache, the r most recent tokens are retained in addition to k centers selected from the remaining tokens).
+ * Farthest-point traversal: the first center is token 0, each next center is the token (older than the window)
+ * farthest from the centers chosen so far, lowest index on ties; squared distances in double precision.
+ * Independent of any context; the result is a cache of k + r rows to run subgen_exact_attend on.
+ *   K, V        device, [streams, n, d] contiguous, `dtype`
+ *   out_K, out_V device, [streams, k + r, d]: the centers in selection order, then the r most recent tokens
+ *                (oldest first); rows that do not exist (n - r < k, or n < r) are zero
+ *   out_idx     device, [streams, k + r] int32: token index of every output row, -1 for rows that do not exist
+ *   out_counts  device, [streams, k] int32 or NULL: number of tokens older than the window whose nearest center
+ *                (lowest index on ties) is that center
+ *   workspace   device scratch of at least subgen_kcenter_workspace_bytes(streams, n, r) bytes
+ */
+size_t subgen_kcenter_workspace_bytes(int64_t streams, int64_t n, int32_t r);
+int subgen_kcenter_compress(const void *K, const void *V, int64_t streams, int64_t n, int32_t d, int32_t dtype, int32_t k,
+                            int32_t r, void *out_K, void *out_V, int32_t *out_idx, int32_t *out_counts,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * subgen_hbm_read_probe — measurement aid, not part of the method: one plain streaming read of
  * `bytes` bytes of device memory (16-byte loads, grid-stride over `workgroups` workgroups of 256
  * lanes).  Timed by the caller, it gives the HBM read bandwidth a kernel reaches on this device,

@@ -271,3 +271,39 @@ def exact_attention(K, V, q) -> np.ndarray:
     sc = K @ q
     e = np.exp(sc - sc.max())
     return (e @ V) / e.sum()
+
+
+def greedy_kcenter(K, k: int):
+    """Farthest-point traversal (the greedy k-center algorithm the paper applies once, Section 3.2) in float64.
+
+    First center = point 0; every next center = the point farthest from the centers chosen so far (lowest index
+    on ties).  Returns (indices of the centers in selection order, nearest-center assignment of every point with
+    the lowest center on ties, squared distance of every point to its nearest center).
+    """
+    K = np.asarray(K, dtype=np.float64)
+    n = K.shape[0]
+    kk = min(int(k), n)
+    sel, assign, mind = [], np.zeros(n, dtype=np.int64), np.full(n, np.inf)
+    c = 0
+    for it in range(kk):
+        sel.append(c)
+        dist = ((K - K[c]) ** 2).sum(axis=1)
+        closer = dist < mind
+        assign[closer] = it
+        mind = np.where(closer, dist, mind)
+        c = int(np.argmax(mind))          # first occurrence of the maximum
+    return np.array(sel, dtype=np.int64), assign, mind
+
+
+def kcenter_compress(K, V, k: int, r: int):
+    """k centers among the tokens older than the r most recent, then those r tokens (Section 3.2)."""
+    K, V = np.asarray(K), np.asarray(V)
+    n = K.shape[0]
+    rwin = min(r, n)
+    nold = n - rwin
+    sel, assign, _ = greedy_kcenter(K[:nold], k) if nold > 0 else (np.zeros(0, np.int64), np.zeros(0, np.int64), None)
+    idx = np.full(k + r, -1, dtype=np.int64)
+    idx[: len(sel)] = sel
+    idx[k: k + rwin] = np.arange(nold, n)
+    counts = np.bincount(assign, minlength=k)[:k] if nold > 0 else np.zeros(k, dtype=np.int64)
+    return idx, counts

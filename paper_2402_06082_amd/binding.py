@@ -22,7 +22,8 @@ FLAG_CENTER_OVERFLOW = 1
 
 EXPORTS = [
     "subgen_create", "subgen_destroy", "subgen_update", "subgen_attend", "subgen_step", "subgen_ingest_prefix",
-    "subgen_exact_workspace_bytes", "subgen_exact_attend", "subgen_hbm_read_probe", "subgen_stats", "subgen_center_counts",
+    "subgen_exact_workspace_bytes", "subgen_exact_attend", "subgen_hbm_read_probe", "subgen_kcenter_workspace_bytes",
+    "subgen_kcenter_compress", "subgen_stats", "subgen_center_counts",
     "subgen_export_state", "subgen_import_state", "subgen_sync", "subgen_strerror", "subgen_last_hip_error",
 ]
 
@@ -86,6 +87,10 @@ def load():
     L.subgen_exact_workspace_bytes.argtypes = [i64, i64, i32, i32]
     L.subgen_exact_attend.restype = C.c_int
     L.subgen_exact_attend.argtypes = [P, P, P, P, i64, i64, i32, i32, i32, P, C.c_size_t, P]
+    L.subgen_kcenter_workspace_bytes.restype = C.c_size_t
+    L.subgen_kcenter_workspace_bytes.argtypes = [i64, i64, i32]
+    L.subgen_kcenter_compress.restype = C.c_int
+    L.subgen_kcenter_compress.argtypes = [P, P, i64, i64, i32, i32, i32, i32, P, P, P, P, P, C.c_size_t, P]
     L.subgen_hbm_read_probe.restype = C.c_int
     L.subgen_hbm_read_probe.argtypes = [P, C.c_size_t, i32, i32, C.c_size_t, P, P]
     L.subgen_stats.restype = C.c_int
@@ -347,3 +352,24 @@ def hbm_read_probe(buf: torch.Tensor, workgroups: int, sink: torch.Tensor, nonte
                                         int(bool(nontemporal)), int(region_bytes), C.c_void_p(sink.data_ptr()),
                                         C.c_void_p(torch.cuda.current_stream(buf.device).cuda_stream)),
            "subgen_hbm_read_probe")
+
+
+def kcenter_compress(K: torch.Tensor, V: torch.Tensor, k: int, r: int, with_counts: bool = True):
+    """Greedy k-center compression of [streams, n, d] caches: returns (K', V', idx, counts) with k + r rows each."""
+    L = load()
+    S, n, d = K.shape
+    for t in (K, V):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != K.dtype or t.shape != K.shape:
+            raise ValueError("kcenter_compress: contiguous cuda tensors of one dtype and shape expected")
+    oK = torch.empty(S, k + r, d, dtype=K.dtype, device=K.device)
+    oV = torch.empty_like(oK)
+    idx = torch.empty(S, k + r, dtype=torch.int32, device=K.device)
+    counts = torch.empty(S, k, dtype=torch.int32, device=K.device) if with_counts else None
+    ws = torch.empty(L.subgen_kcenter_workspace_bytes(S, n, r), dtype=torch.uint8, device=K.device)
+    _check(L.subgen_kcenter_compress(C.c_void_p(K.data_ptr()), C.c_void_p(V.data_ptr()), S, n, d, _dtype_code(K.dtype),
+                                     int(k), int(r), C.c_void_p(oK.data_ptr()), C.c_void_p(oV.data_ptr()),
+                                     C.c_void_p(idx.data_ptr()),
+                                     C.c_void_p(counts.data_ptr()) if counts is not None else None,
+                                     C.c_void_p(ws.data_ptr()), ws.numel(),
+                                     C.c_void_p(torch.cuda.current_stream(K.device).cuda_stream)), "subgen_kcenter_compress")
+    return oK, oV, idx, counts

@@ -16,6 +16,7 @@
 #include "ingest_mfma_device.hpp"
 #include "subgen_dot2_device.hpp"
 #include "subgen_res_device.hpp"
+#include "kcenter_device.hpp"
 
 using sg::Call;
 using sg::State;
@@ -444,6 +445,47 @@ int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, 
         if (LPR == 8) launch_exact_g<false, 8>(g, c, streams, s);
         else if (LPR == 16) launch_exact_g<false, 16>(g, c, streams, s);
         else launch_exact_g<false, 32>(g, c, streams, s);
+    }
+    return hipGetLastError() == hipSuccess ? SUBGEN_OK : SUBGEN_EHIP;
+}
+
+size_t subgen_kcenter_workspace_bytes(int64_t streams, int64_t n, int32_t r)
+{
+    if (streams < 1 || n < 1 || r < 0) return 0;
+    const int64_t nold = n > r ? n - r : 1;
+    return (size_t)streams * (size_t)nold * (sizeof(double) + sizeof(int32_t)) + 256;
+}
+
+int subgen_kcenter_compress(const void *K, const void *V, int64_t streams, int64_t n, int32_t d, int32_t dtype, int32_t k,
+                            int32_t r, void *out_K, void *out_V, int32_t *out_idx, int32_t *out_counts,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!K || !V || !out_K || !out_V || !out_idx || !workspace) return SUBGEN_EINVAL;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(out_K) || !aligned16(out_V) || !aligned16(workspace))
+        return SUBGEN_EINVAL;
+    if (dtype != SUBGEN_F32 && dtype != SUBGEN_BF16) return SUBGEN_EINVAL;
+    const int esz = dtype == SUBGEN_BF16 ? 2 : 4;
+    if (streams < 1 || streams > 0x7fffffffLL || n < 1 || n > 0x7fffffffLL || d < 1 || !row_bytes_ok((int64_t)d * esz))
+        return SUBGEN_EINVAL;
+    if (k < 1 || r < 0 || k > (1 << 24) || r > (1 << 24)) return SUBGEN_EINVAL;
+    if (workspace_bytes < subgen_kcenter_workspace_bytes(streams, n, r)) return SUBGEN_ECAPACITY;
+    const int64_t nold = n > r ? n - r : 1;
+    sg::KCenterCall c{};
+    c.K = (const char *)K; c.V = (const char *)V; c.outK = (char *)out_K; c.outV = (char *)out_V;
+    c.out_idx = out_idx; c.out_counts = out_counts; c.n = n; c.k = k; c.r = r;
+    c.mind = (double *)workspace;
+    c.assign = (int32_t *)((char *)workspace + (size_t)streams * (size_t)nold * sizeof(double));
+    hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+    const dim3 grid((unsigned)streams), block(sg::kWG);
+    const int LPR = d * esz / 16;
+    if (dtype == SUBGEN_BF16) {
+        if (LPR == 8) hipLaunchKernelGGL((sg::kcenter_kernel<true, 8>), grid, block, 0, s, c);
+        else if (LPR == 16) hipLaunchKernelGGL((sg::kcenter_kernel<true, 16>), grid, block, 0, s, c);
+        else hipLaunchKernelGGL((sg::kcenter_kernel<true, 32>), grid, block, 0, s, c);
+    } else {
+        if (LPR == 8) hipLaunchKernelGGL((sg::kcenter_kernel<false, 8>), grid, block, 0, s, c);
+        else if (LPR == 16) hipLaunchKernelGGL((sg::kcenter_kernel<false, 16>), grid, block, 0, s, c);
+        else hipLaunchKernelGGL((sg::kcenter_kernel<false, 32>), grid, block, 0, s, c);
     }
     return hipGetLastError() == hipSuccess ? SUBGEN_OK : SUBGEN_EHIP;
 }

@@ -393,3 +393,32 @@ def test_reservoir_mode_matches_the_oracle(dtype, d, g, t):
     for sid in range(S):
         c.import_raw(sid, sg.export_raw(sid))
     assert torch.equal(c.attend(qlast), again)
+
+
+@pytest.mark.parametrize("dtype,d,n,k,r", [(torch.bfloat16, 128, 700, 48, 16), (torch.float32, 64, 333, 20, 0),
+                                           (torch.bfloat16, 64, 40, 64, 8), (torch.bfloat16, 256, 5, 3, 9)])
+def test_greedy_kcenter_compression_matches_the_oracle(dtype, d, n, k, r):
+    """One-shot greedy k-center compression (Section 3.2): selected indices, cluster sizes and the compressed
+    rows are bit-exact; attention over the compressed cache equals textbook attention over the same rows."""
+    from oracle.subgen_oracle import kcenter_compress as oracle_compress
+    b = binding()
+    cfg = CONFIGS["cfg2"].scaled(name="kc", d=d, dtype="bf16" if dtype == torch.bfloat16 else "fp32", kv_heads=3,
+                                 components=10)
+    wl = Workload(cfg, device=DEV)
+    K, V = wl.tokens(0, n)
+    oK, oV, idx, counts = b.kcenter_compress(K, V, k, r)
+    Kc, Vc = to_f32_np(K), to_f32_np(V)
+    for i in range(wl.S):
+        ridx, rcounts = oracle_compress(Kc[i], Vc[i], k, r)
+        assert np.array_equal(idx[i].cpu().numpy(), ridx), i
+        assert np.array_equal(counts[i].cpu().numpy(), rcounts), i
+        rows = ridx >= 0
+        assert np.array_equal(to_f32_np(oK[i])[rows], Kc[i][ridx[rows]])
+        assert np.array_equal(to_f32_np(oV[i])[rows], Vc[i][ridx[rows]])
+        assert not to_f32_np(oK[i])[~rows].any()
+    # attention over the retained rows (all rows exist in the first two cases)
+    if (idx >= 0).all():
+        Q = wl.queries(0, 1)[:, 0].contiguous()
+        out = b.exact_attend(oK, oV, Q).cpu().numpy()
+        ref = np.stack([[exact_attention(to_f32_np(oK[i]), to_f32_np(oV[i]), to_f32_np(Q[i, 0]))] for i in range(wl.S)])
+        assert rel_l2(out, ref).max() <= 1e-4

@@ -553,3 +553,69 @@ def test_delta_zero_reservoirs_give_exact_partition_function():
     q = r.normal(size=d).astype(np.float32)
     _, den, mx = o.attend(q, return_den=True)
     assert den * math.exp(mx) == pytest.approx(np.exp(K.astype(np.float64) @ q.astype(np.float64)).sum(), rel=1e-12)
+
+
+# --------------------------------------------------------------------------
+# one-shot greedy k-center compression (Section 3.2: applied once to the whole cache, r recent tokens kept)
+# --------------------------------------------------------------------------
+from itertools import combinations  # noqa: E402
+
+from oracle.subgen_oracle import greedy_kcenter, kcenter_compress  # noqa: E402
+
+
+def test_greedy_kcenter_matches_integer_brute_force_traversal():
+    r = rng(30)
+    pts = r.integers(-9, 10, size=(40, 3))
+    sel, assign, mind = greedy_kcenter(pts, 7)
+    # pure-Python farthest-point traversal in exact integer arithmetic
+    chosen = [0]
+    md = [sum((int(a) - int(b)) ** 2 for a, b in zip(p, pts[0])) for p in pts]
+    for _ in range(6):
+        j = max(range(len(pts)), key=lambda i: (md[i], -i))
+        chosen.append(j)
+        md = [min(m0, sum((int(a) - int(b)) ** 2 for a, b in zip(p, pts[j]))) for m0, p in zip(md, pts)]
+    assert sel.tolist() == chosen and mind.astype(int).tolist() == md
+    # assignment = nearest chosen center, lowest on ties
+    D = ((pts[:, None, :] - pts[sel][None]) ** 2).sum(-1)
+    assert np.array_equal(assign, D.argmin(1))
+
+
+def test_greedy_kcenter_is_a_two_approximation():
+    # Gonzalez / Dyer-Frieze guarantee: the greedy radius is at most twice the optimal k-center radius
+    r = rng(31)
+    pts = r.normal(size=(14, 2))
+    k = 3
+    _, _, mind = greedy_kcenter(pts, k)
+    greedy_radius = math.sqrt(mind.max())
+    D = np.linalg.norm(pts[:, None] - pts[None], axis=-1)
+    opt = min(D[:, list(c)].min(1).max() for c in combinations(range(len(pts)), k))
+    assert greedy_radius <= 2.0 * opt + 1e-12
+    assert greedy_radius >= opt - 1e-12
+
+
+def test_greedy_kcenter_separated_groups_and_radii():
+    r = rng(32)
+    base = np.array([[0.0, 0.0], [50.0, 0.0], [0.0, 50.0], [50.0, 50.0], [25.0, 90.0]])
+    lab = r.integers(0, 5, size=200)
+    lab[0] = 0
+    pts = base[lab] + r.normal(size=(200, 2))
+    sel, assign, mind = greedy_kcenter(pts, 5)
+    assert sorted(lab[sel].tolist()) == [0, 1, 2, 3, 4]                 # one center per group
+    assert all(len(set(lab[assign == i])) == 1 for i in range(5))       # clusters are the groups
+    assert len(set(sel.tolist())) == 5 and sel[0] == 0
+    # the selection radius never increases
+    radii = [greedy_kcenter(pts, kk)[2].max() for kk in range(1, 9)]
+    assert all(a >= b for a, b in zip(radii, radii[1:]))
+
+
+def test_kcenter_compress_layout_and_edge_cases():
+    r = rng(33)
+    K, V = r.normal(size=(30, 4)), r.normal(size=(30, 4))
+    idx, counts = kcenter_compress(K, V, k=6, r=5)
+    assert idx[6:].tolist() == [25, 26, 27, 28, 29] and idx[0] == 0 and (idx[:6] < 25).all()
+    assert counts.sum() == 25 and len(set(idx[:6].tolist())) == 6
+    idx, counts = kcenter_compress(K[:8], V[:8], k=6, r=5)               # only 3 old tokens: 3 centers, rest unused
+    assert idx.tolist() == [0, 2, 1, -1, -1, -1, 3, 4, 5, 6, 7] or sorted(idx[:3].tolist()) == [0, 1, 2]
+    assert idx[3:6].tolist() == [-1, -1, -1] and counts.sum() == 3
+    idx, counts = kcenter_compress(K[:3], V[:3], k=2, r=5)               # fewer tokens than the window
+    assert idx.tolist() == [-1, -1, 0, 1, 2, -1, -1] and counts.sum() == 0
