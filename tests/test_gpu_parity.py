@@ -422,3 +422,34 @@ def test_greedy_kcenter_compression_matches_the_oracle(dtype, d, n, k, r):
         out = b.exact_attend(oK, oV, Q).cpu().numpy()
         ref = np.stack([[exact_attention(to_f32_np(oK[i]), to_f32_np(oV[i]), to_f32_np(Q[i, 0]))] for i in range(wl.S)])
         assert rel_l2(out, ref).max() <= 1e-4
+
+
+@pytest.mark.parametrize("w,s", [(0, 8), (100, 64), (1, 3), (300, 130)])
+@pytest.mark.parametrize("kernel_path", [0, 1])
+def test_ingest_window_sizes_and_long_calls(w, s, kernel_path):
+    """Prefix ingest with no window, windows longer than a 64-token chunk and longer than some calls, and one
+    call long enough to be split into several launches: same state as the oracle and as token-by-token updates."""
+    b = binding()
+    cfg = small_cfg(s=s, w=w, kv_heads=3)
+    wl = Workload(cfg, device=DEV)
+    n = 4700
+    K, V = wl.tokens(0, n)
+    mk = lambda: b.SubGen(wl.S, cfg.d, 8.1, s, w, dtype=cfg.torch_dtype, assign_log_tokens=n, seed=5, device=DEV,
+                          kernel_path=kernel_path)
+    one, parts = mk(), mk()
+    one.ingest_prefix(K, V)                                     # > 2048 tokens: several launches inside one call
+    for lo, hi in [(0, 50), (50, 51), (51, 400), (400, 463), (463, 464), (464, 2600), (2600, n)]:
+        parts.ingest_prefix(K[:, lo:hi], V[:, lo:hi])
+    oracles = make_oracles(wl.S, cfg.d, 8.1, s, w, seed=5)
+    for o, k, v in zip(oracles, to_f32_np(K), to_f32_np(V)):
+        o.ingest(k, v)
+    assert compare_state(one, oracles) == 0
+    for sid in range(wl.S):
+        assert state_tuple(one, sid) == state_tuple(parts, sid)
+    # a few more tokens one at a time on top of the ingested state
+    K2, V2 = wl.tokens(n, n + 70)
+    for t in range(70):
+        one.update(K2[:, t].contiguous(), V2[:, t].contiguous())
+    parts.ingest_prefix(K2, V2)
+    for sid in range(wl.S):
+        assert state_tuple(one, sid) == state_tuple(parts, sid)
