@@ -58,7 +58,9 @@ enum { SUBGEN_F32 = 0, SUBGEN_BF16 = 1 };
 
 /* bits of the sticky per-stream flag word (subgen_stats, subgen_export_state) */
 enum {
-    SUBGEN_FLAG_CENTER_OVERFLOW = 1u /* the center table was full: a token joined its nearest center regardless of delta */
+    SUBGEN_FLAG_CENTER_OVERFLOW = 1u, /* the center table was full: a token joined its nearest center regardless of delta */
+    SUBGEN_FLAG_NONFINITE = 2u        /* a token that left the window held NaN or Inf (or a squared norm beyond fp32):
+                                         it was dropped, i.e. neither clustered nor sampled                           */
 };
 
 /* Options of subgen_create.  Zero-initialise, set struct_size = sizeof(subgen_opts), then override. */

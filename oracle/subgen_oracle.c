@@ -129,6 +129,7 @@ typedef struct sgo_stream {
     int64_t log_cap;
 
     int overflowed;           /* a token was force-joined because max_centers was hit */
+    int64_t dropped;          /* tokens with NaN/Inf that were dropped when they left the window */
 } sgo_stream;
 
 sgo_stream *sgo_create(int d, double delta, int s, int w, uint64_t seed, uint32_t stream, int max_centers, int t)
@@ -262,6 +263,27 @@ static void sample_update(sgo_stream *o, int64_t token, const float *k, const fl
     o->mu += (double)vn;
 }
 
+/* The paper is silent on tokens that hold NaN or Inf.  Reading taken here:
+ * a token whose squared key norm or squared value norm (double sums, then
+ * rounded to fp32) is not finite is dropped at the moment it leaves the
+ * window: it is neither clustered nor offered to the sampler, mu does not
+ * move, and it is counted in `dropped`.  Its decision-log entry is -1. */
+static void compress_token(sgo_stream *o, int64_t token, const float *k, const float *v)
+{
+    double kk = 0.0, vv = 0.0;
+    for (int c = 0; c < o->d; ++c) {
+        kk += (double)k[c] * (double)k[c];
+        vv += (double)v[c] * (double)v[c];
+    }
+    if (!((float)kk < INFINITY) || !((float)vv < INFINITY)) {
+        o->dropped += 1;
+        log_decision(o, -1, 0, INFINITY, INFINITY);
+        return;
+    }
+    cluster_update(o, token, k);
+    sample_update(o, token, k, v);
+}
+
 /* One token arrives.  It enters the window; the token it pushes out (if
  * any) is the one that is clustered and offered to the sampler. */
 void sgo_update(sgo_stream *o, const float *k, const float *v)
@@ -270,8 +292,7 @@ void sgo_update(sgo_stream *o, const float *k, const float *v)
     const int64_t i = o->n_seen;
     o->n_seen += 1;
     if (o->w == 0) {
-        cluster_update(o, i, k);
-        sample_update(o, i, k, v);
+        compress_token(o, i, k, v);
         o->n_evicted += 1;
         return;
     }
@@ -280,8 +301,7 @@ void sgo_update(sgo_stream *o, const float *k, const float *v)
         const float *ek = o->win_k + (size_t)slot * d;
         const float *ev = o->win_v + (size_t)slot * d;
         const int64_t ei = o->win_idx[slot];
-        cluster_update(o, ei, ek);
-        sample_update(o, ei, ek, ev);
+        compress_token(o, ei, ek, ev);
         o->n_evicted += 1;
     }
     memcpy(o->win_k + (size_t)slot * d, k, (size_t)d * sizeof(float));
@@ -389,6 +409,7 @@ int64_t sgo_n_seen(const sgo_stream *o) { return o->n_seen; }
 int64_t sgo_n_evicted(const sgo_stream *o) { return o->n_evicted; }
 double sgo_mu(const sgo_stream *o) { return o->mu; }
 int sgo_overflowed(const sgo_stream *o) { return o->overflowed; }
+int64_t sgo_dropped(const sgo_stream *o) { return o->dropped; }
 const float *sgo_centers(const sgo_stream *o) { return o->X; }
 const float *sgo_reservoirs(const sgo_stream *o) { return o->R; }
 const int64_t *sgo_counts(const sgo_stream *o) { return o->cnt; }

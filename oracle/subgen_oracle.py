@@ -59,7 +59,7 @@ def _load():
     L.sgo_uniform24_res.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32]
     L.sgo_philox4x32_10.argtypes = [C.POINTER(C.c_uint32)] * 3
     for name, rt in [("sgo_m", C.c_int), ("sgo_n_seen", C.c_int64), ("sgo_n_evicted", C.c_int64),
-                     ("sgo_mu", C.c_double), ("sgo_overflowed", C.c_int)]:
+                     ("sgo_mu", C.c_double), ("sgo_overflowed", C.c_int), ("sgo_dropped", C.c_int64)]:
         getattr(L, name).restype = rt
         getattr(L, name).argtypes = [P]
     for name in ["sgo_centers", "sgo_reservoirs", "sgo_counts", "sgo_sample_k", "sgo_sample_v", "sgo_sample_idx", "sgo_sample_vn",
@@ -182,6 +182,11 @@ class OracleStream:
     @property
     def overflowed(self) -> bool:
         return bool(self._L.sgo_overflowed(self._h))
+
+    @property
+    def dropped(self) -> int:
+        """Tokens with NaN/Inf (or a squared norm beyond fp32) dropped when they left the window."""
+        return int(self._L.sgo_dropped(self._h))
 
     @property
     def centers(self):

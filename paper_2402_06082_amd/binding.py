@@ -19,6 +19,7 @@ _lib = None
 
 SUBGEN_F32, SUBGEN_BF16 = 0, 1
 FLAG_CENTER_OVERFLOW = 1
+FLAG_NONFINITE = 2
 
 EXPORTS = [
     "subgen_create", "subgen_destroy", "subgen_update", "subgen_attend", "subgen_step", "subgen_ingest_prefix",

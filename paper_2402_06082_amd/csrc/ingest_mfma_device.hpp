@@ -119,9 +119,13 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 }
                 a = group_sum<LPR>(a);
                 b = group_sum<LPR>(b);
+                // a token with NaN or Inf in it (or a norm beyond fp32) is dropped: it joins nothing, opens
+                // nothing and is never sampled; it is marked by ||k||^2 = +inf, ||v||^2 = 0
+                const bool bad = !((float)a < INFINITY) || !((float)b < INFINITY);
                 if (col == 0) {
-                    sm.nk[grp + it * RPB] = (float)a;
-                    sm.vn[grp + it * RPB] = (float)b;
+                    sm.nk[grp + it * RPB] = bad ? INFINITY : (float)a;
+                    sm.vn[grp + it * RPB] = bad ? 0.f : (float)b;
+                    if (bad && grp + it * RPB < nt) atomicOr(&st.flags[sid], 2u);
                 }
             }
         }
@@ -250,7 +254,8 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
         // ---- resolve in token order: lane j = token j of the chunk; every wavefront runs the same loop
         //      (same LDS inputs, same results), wavefront 0 applies the side effects
         const int j = lane;
-        const bool valid = j < nt;
+        const float nkj = sm.nk[j];
+        const bool valid = j < nt && nkj < INFINITY;
         float ob1 = sm.wb1[0][j], ob2 = sm.wb2[0][j];
         int oi1 = sm.wi1[0][j];
         float nxold = sm.wnx[0];
@@ -267,7 +272,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             }
             nxold = fmaxf(nxold, sm.wnx[wv]);
         }
-        const float nkj = sm.nk[j];
         uint64_t cmask = 0;   // tokens of this chunk that opened a cluster (uniform)
         int done = 0;         // tokens below `done` are final (uniform)
         const uint64_t below = j == 0 ? 0ull : (~0ull >> (64 - j));
@@ -295,6 +299,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             const int e = evmask ? __builtin_ctzll(evmask) : nt;   // first creation / ambiguous token
             // tokens before the event are final: they join (or are force-joined to) their nearest cluster
             if (wave == 0 && live && j < e) {
+                if (ci < 0) ci = 0;   // only with non-finite representatives (imported state)
                 atomicAdd(&cnt[ci], 1);
                 if (forced) atomicOr(&st.flags[sid], 1u);
                 if (st.assign != nullptr && c0 + j < st.assign_cap) st.assign[sid * (size_t)st.assign_cap + c0 + j] = ci;
@@ -311,6 +316,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 exact_nearest<LPR>(X, me, ld16(krow_of(c0 + e) + col * 16), sm.wbest, sm.widx, best, bidx);
                 const bool ejoin = bidx >= 0 && best <= st.delta2;
                 const bool eforced = !ejoin && me > 0 && me >= st.Mcap;
+                if (eforced && bidx < 0) bidx = 0;
                 create = !ejoin && !eforced;
                 if (!create) {
                     target = bidx;

@@ -225,12 +225,31 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
         for (int g = 0; g < G; ++g) unpack<BF16>(ld16(qrows + (size_t)g * ROWB + col * 16), q[g]);
     }
     double ekd[VEC];
+    double kk2 = 0.0;   // ||k'||^2
+    float vn = 0.f;     // ||v'||^2
     float bnew[G];  // <q, evicted key>: score of the cluster this token would open
     if constexpr (UPD) {
         float ekf[VEC];
         unpack<BF16>(ek, ekf);
 #pragma unroll
         for (int v = 0; v < VEC; ++v) ekd[v] = (double)ekf[v];
+        // ||k'||^2 and ||v'||^2 in double; a token with NaN or Inf in it is dropped and flagged
+        {
+            float evf[VEC];
+            unpack<BF16>(ev, evf);
+            double vv2 = 0.0;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                kk2 = fma(ekd[v], ekd[v], kk2);
+                vv2 = fma((double)evf[v], (double)evf[v], vv2);
+            }
+            kk2 = group_sum<LPR>(kk2);
+            vn = (float)group_sum<LPR>(vv2);
+            if (evict && (!((float)kk2 < INFINITY) || !(vn < INFINITY))) {
+                evict = false;
+                if (tid == 0) st.flags[sid] |= 2u;
+            }
+        }
         if constexpr (ATT) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
@@ -350,13 +369,10 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
             }
             // ---- join iff ||k - x_i*||^2 <= delta^2, else open a cluster (or force-join when full)
             const bool join = bidx >= 0 && best <= st.delta2;
+            if (!join && bidx < 0 && m >= st.Mcap) bidx = 0;   // only with non-finite representatives (imported state)
             const bool forced = !join && bidx >= 0 && m >= st.Mcap;
             const bool created = !join && !forced;
             const int target = created ? m : bidx;
-            double kk2 = 0.0;
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) kk2 = fma(ekd[v], ekd[v], kk2);
-            kk2 = group_sum<LPR>(kk2);
             if (created) {
                 if (tid < LPR) st16(X + (size_t)m * ROWB + tid * 16, ek);
                 if (tid == 0) {
@@ -384,13 +400,6 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
             if (created) m += 1;
 
             // ---- sampling update: p from the old mu, one coin per slot, then mu += ||v||^2
-            float vf[VEC];
-            unpack<BF16>(ev, vf);
-            double a = 0.0;
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) a = fma((double)vf[v], (double)vf[v], a);
-            a = group_sum<LPR>(a);
-            const float vn = (float)a;
             float p;
             if (mu == 0.0) p = 1.f;
             else if (vn == 0.f) p = 0.f;

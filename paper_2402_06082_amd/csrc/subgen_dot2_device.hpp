@@ -119,6 +119,10 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             }
             nk = (float)group_sum<LPR>(a);
             vn = (float)group_sum<LPR>(b);
+            if (!(nk < INFINITY) || !(vn < INFINITY)) {   // NaN or Inf in the token: it is dropped and flagged
+                evict = false;
+                if (tid == 0) st.flags[sid] |= 2u;
+            }
         }
         __syncthreads();  // every lane holds the evicted row (registers, LDS) before the slot is overwritten
         if (st.w > 0 && tid < LPR) {
@@ -235,6 +239,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             } else {
                 join = m > 0 && b1 <= thr;
             }
+            if (!join && bidx < 0 && m >= st.Mcap) bidx = 0;   // only with non-finite representatives (imported state)
             const bool forced = !join && m > 0 && m >= st.Mcap;
             const bool created = !join && !forced;
             const int target = created ? m : bidx;

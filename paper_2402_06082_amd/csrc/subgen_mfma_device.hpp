@@ -253,6 +253,10 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
         }
         nk = (float)group_sum<LPR>(a);
         vn = (float)group_sum<LPR>(b);
+        if (evict && (!(nk < INFINITY) || !(vn < INFINITY))) {   // NaN or Inf in the token: dropped and flagged
+            evict = false;
+            if (tid == 0) st.flags[sid] |= 2u;
+        }
     }
 
     // online softmax state of this lane's query role: lazily raised reference, denominator
@@ -380,6 +384,7 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
             } else {
                 join = m > 0 && b1 <= thr;
             }
+            if (!join && bidx < 0 && m >= st.Mcap) bidx = 0;   // only with non-finite representatives (imported state)
             const bool forced = !join && m > 0 && m >= st.Mcap;
             const bool created = !join && !forced;
             const int target = created ? m : bidx;

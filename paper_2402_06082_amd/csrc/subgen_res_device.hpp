@@ -79,19 +79,27 @@ __device__ __forceinline__ void token_step_res(const State &st, const size_t sid
             st16(kw + tid * 16, ld16(krow + tid * 16));
             st16(vw + tid * 16, ld16(vrow + tid * 16));
         }
-        if (evict) {
-            float ekf[VEC], evf[VEC];
-            unpack<BF16>(ek, ekf);
+        float ekf[VEC];
+        unpack<BF16>(ek, ekf);
+        double kk2 = 0.0;   // ||k'||^2
+        float vn = 0.f;     // ||v'||^2
+        {
+            float evf[VEC];
             unpack<BF16>(ev, evf);
-            double kk2 = 0.0, vv2 = 0.0;
+            double vv2 = 0.0;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 kk2 = fma((double)ekf[v], (double)ekf[v], kk2);
                 vv2 = fma((double)evf[v], (double)evf[v], vv2);
             }
             kk2 = group_sum<LPR>(kk2);
-            const float vn = (float)group_sum<LPR>(vv2);
-
+            vn = (float)group_sum<LPR>(vv2);
+            if (evict && (!((float)kk2 < INFINITY) || !(vn < INFINITY))) {   // NaN or Inf in the token: dropped and flagged
+                evict = false;
+                if (tid == 0) st.flags[sid] |= 2u;
+            }
+        }
+        if (evict) {
             // ---- nearest representative in double precision (lowest index on ties)
             double best = INFINITY;
             int bidx = -1;
@@ -147,6 +155,7 @@ __device__ __forceinline__ void token_step_res(const State &st, const size_t sid
             }
             // ---- join (count bump + reservoir coins) or open a cluster (t copies of the key)
             const bool join = bidx >= 0 && best <= st.delta2;
+            if (!join && bidx < 0 && m >= st.Mcap) bidx = 0;   // only with non-finite representatives (imported state)
             const bool forced = !join && bidx >= 0 && m >= st.Mcap;
             const bool created = !join && !forced;
             const int target = created ? m : bidx;

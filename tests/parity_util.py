@@ -19,9 +19,9 @@ def rel_l2(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     return num / np.maximum(den, 1e-300)
 
 
-def make_oracles(streams, d, delta, s, w, seed=0, max_centers=0, stream_ids=None):
+def make_oracles(streams, d, delta, s, w, seed=0, max_centers=0, stream_ids=None, t=0):
     ids = list(stream_ids) if stream_ids is not None else list(range(streams))
-    return [OracleStream(d, delta, s, w, seed=seed, stream=i, max_centers=max_centers) for i in ids]
+    return [OracleStream(d, delta, s, w, seed=seed, stream=i, max_centers=max_centers, t=t) for i in ids]
 
 
 def compare_state(sg, oracles, stream_ids=None, check_rows=True):
@@ -50,7 +50,8 @@ def compare_state(sg, oracles, stream_ids=None, check_rows=True):
                 continue          # later state of this stream legitimately differs
         assert st.m == o.m, (sid, st.m, o.m)
         assert np.array_equal(st.counts.astype(np.int64), o.counts), f"stream {sid}: counts differ"
-        assert st.counts.sum() + st.window_fill == st.n_seen
+        assert st.counts.sum() + st.window_fill == st.n_seen - o.dropped
+        assert bool(st.flags & 2) == (o.dropped > 0), (sid, st.flags, o.dropped)
         assert np.array_equal(st.sample_idx.astype(np.int64), o.sample_idx), f"stream {sid}: sampled indices differ"
         assert np.array_equal(st.sample_vn, o.sample_vn), f"stream {sid}: sample norms differ"
         assert st.mu == o.mu, (sid, st.mu, o.mu)

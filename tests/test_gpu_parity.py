@@ -252,6 +252,54 @@ def test_delta_zero_duplicates_and_center_overflow():
     assert all(o.overflowed for o in oracles)
 
 
+@pytest.mark.parametrize("dtype,d,g,kernel_path,t", [(torch.bfloat16, 128, 1, 0, 0), (torch.bfloat16, 128, 4, 0, 0),
+                                                     (torch.bfloat16, 64, 2, 0, 0), (torch.bfloat16, 128, 1, 1, 0),
+                                                     (torch.float32, 64, 1, 0, 0), (torch.bfloat16, 128, 1, 0, 2)])
+@pytest.mark.parametrize("ingest", [False, True])
+def test_nonfinite_tokens_are_dropped_and_flagged(dtype, d, g, kernel_path, t, ingest):
+    """A token with NaN or Inf is neither clustered nor sampled once it leaves the window; flag bit 2 is raised,
+    the other streams and the later tokens of the same stream stay bit-exact."""
+    b = binding()
+    gen = torch.Generator(device="cpu").manual_seed(d + g + t)
+    S, n, s, w = 3, 150, 6, 3
+    cent = torch.randn(S, 5, d, generator=gen) * 2.0
+    comp = torch.randint(0, 5, (S, n), generator=gen)
+    K = torch.gather(cent, 1, comp[..., None].expand(S, n, d)) + 0.2 * torch.randn(S, n, d, generator=gen)
+    V = torch.randn(S, n, d, generator=gen)
+    Q = torch.randn(S, n, g, d, generator=gen) / d ** 0.5
+    K[0, 17, 5] = float("nan")
+    V[0, 70, 0] = float("inf")
+    K[1, 71, d - 1] = float("-inf")
+    V[1, 72, 9] = float("nan")
+    V[1, 140, 1] = float("nan")
+    K, V, Q = (x.to(dtype).to(DEV) for x in (K, V, Q))
+    delta = 0.2 * (2 * d) ** 0.5 * 1.05
+    sg = b.SubGen(S, d, delta, s, w, dtype=dtype, q_per_stream=g, assign_log_tokens=n, seed=4, device=DEV,
+                  kernel_path=kernel_path, t_per_cluster=t)
+    oracles = make_oracles(S, d, delta, s, w, seed=4, t=t)
+    Kc, Vc, Qc = to_f32_np(K), to_f32_np(V), to_f32_np(Q)
+    t0 = 0
+    if ingest:
+        t0 = 100
+        sg.ingest_prefix(K[:, :t0].contiguous(), V[:, :t0].contiguous())
+        for i, o in enumerate(oracles):
+            o.ingest(Kc[i, :t0], Vc[i, :t0])
+        assert compare_state(sg, oracles) == 0
+    for tt in range(t0, n):
+        out = sg.step(K[:, tt].contiguous(), V[:, tt].contiguous(), Q[:, tt].contiguous()).cpu().numpy()
+        ref = np.stack([o.decode(Kc[i, tt:tt + 1], Vc[i, tt:tt + 1], Qc[i, tt:tt + 1])[0]
+                        for i, o in enumerate(oracles)])
+        ok = np.isfinite(ref).all(axis=(1, 2))          # a bad token inside the window poisons that stream's output
+        assert ok[2] and rel_l2(out[ok], ref[ok]).max() <= REL_L2_TOL, tt
+    assert compare_state(sg, oracles) == 0
+    assert [o.dropped for o in oracles] == [2, 3, 0]
+    if t > 0:
+        for i, o in enumerate(oracles):
+            assert np.array_equal(sg.export_state(i).reservoirs, o.reservoirs), i
+    st = sg.stats()
+    assert st.flags_or == b.FLAG_NONFINITE and st.flagged_streams == 2
+
+
 def test_error_codes():
     b = binding()
     sg = b.SubGen(2, 128, 1.0, 4, 2, dtype=torch.bfloat16, device=DEV)

@@ -619,3 +619,42 @@ def test_kcenter_compress_layout_and_edge_cases():
     assert idx[3:6].tolist() == [-1, -1, -1] and counts.sum() == 3
     idx, counts = kcenter_compress(K[:3], V[:3], k=2, r=5)               # fewer tokens than the window
     assert idx.tolist() == [-1, -1, 0, 1, 2, -1, -1] and counts.sum() == 0
+
+
+# --------------------------------------------------------------------------
+# tokens with NaN / Inf (the paper is silent; reading: dropped when they leave the window)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("w", [0, 3])
+def test_nonfinite_tokens_are_dropped_and_leave_the_rest_untouched(w):
+    r = rng(31)
+    n, d = 120, 8
+    K = (r.normal(size=(5, d))[r.integers(0, 5, size=n)] * 3 + 0.2 * r.normal(size=(n, d))).astype(np.float32)
+    V = r.normal(size=(n, d)).astype(np.float32)
+    bad = {17: ("k", np.nan), 40: ("v", np.inf), 41: ("k", -np.inf), 90: ("v", np.nan)}
+    Kb, Vb = K.copy(), V.copy()
+    for i, (which, val) in bad.items():
+        (Kb if which == "k" else Vb)[i, 3] = val
+    keep = np.array([i for i in range(n) if i not in bad])
+    a = OracleStream(d, 1.0, s=6, w=w, seed=9)
+    a.ingest(Kb, Vb)
+    # clustering and mu do not depend on token numbers: they must equal those of the stream with the bad
+    # tokens removed beforehand (once every bad token has left the window, i.e. compare on evicted tokens)
+    n_ev = n - w
+    keep_ev = keep[keep < n_ev]
+    c = OracleStream(d, 1.0, s=6, w=0, seed=9)
+    c.ingest(K[keep_ev], V[keep_ev])
+    assert a.dropped == sum(1 for i in bad if i < n_ev) and c.dropped == 0
+    assert a.m == c.m and np.array_equal(a.counts, c.counts) and np.array_equal(a.centers, c.centers)
+    assert a.mu == c.mu
+    assert a.counts.sum() + a.window_fill == n - a.dropped
+    full = a.assign
+    assert np.array_equal(full[keep_ev], c.assign) and all(full[i] == -1 for i in bad if i < n_ev)
+    # a dropped token is never a sample; the coins of the others keep their own token numbers
+    assert not set(a.sample_idx.tolist()) & set(bad)
+    for j, tok in enumerate(a.sample_idx):
+        assert tok in keep_ev and np.array_equal(a.sample_k[j], K[tok]) and np.array_equal(a.sample_v[j], V[tok])
+    # squared norms beyond fp32 count as non-finite
+    b = OracleStream(d, 1.0, s=2, w=0, seed=1)
+    big = np.full((1, d), 3e19, dtype=np.float32)
+    b.ingest(big, V[:1])
+    assert b.dropped == 1 and b.m == 0
