@@ -182,3 +182,31 @@ class Workload:
         if not out:
             return torch.empty(self.S, 0, cfg.g, cfg.d, dtype=cfg.torch_dtype, device=self.device)
         return torch.cat(out, 1).contiguous()
+
+
+def clusterable_streams(streams: int, n: int, d: int, m: int, delta: float, r: float, g: int = 1, seed: int = 0,
+                        device="cpu", dtype=torch.float32, center_norm: float = 0.0):
+    """Streams whose keys are (m, delta)-clusterable in the sense of Definition 1 of the paper.
+
+    Per stream: m centers of norm ``center_norm`` (default 4*delta) in random directions; every key lies within
+    0.45*delta of its center, so two keys of one cluster are at most 0.9*delta apart (the slack absorbs the
+    rounding to ``dtype``); cluster membership is uniform.  Values are N(0, I) with a per-token log-normal
+    scale, queries have norm r (scaled by 1 - 2^-7 so that rounding cannot push them above r).
+    Returns K [S, n, d], V [S, n, d], Q [S, g, d] in ``dtype`` and the membership [S, n] (int64).
+    """
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(_mix(seed, 0xC1, streams, n, d, m))
+    cn = center_norm if center_norm > 0.0 else 4.0 * delta
+    cent = torch.randn(streams, m, d, generator=gen, device=dev)
+    cent = cn * cent / cent.norm(dim=-1, keepdim=True)
+    member = torch.randint(0, m, (streams, n), generator=gen, device=dev)
+    off = torch.randn(streams, n, d, generator=gen, device=dev)
+    off = off / off.norm(dim=-1, keepdim=True)
+    off = off * (0.45 * delta * torch.rand(streams, n, 1, generator=gen, device=dev))
+    K = torch.gather(cent, 1, member.unsqueeze(-1).expand(streams, n, d)) + off
+    V = torch.randn(streams, n, d, generator=gen, device=dev)
+    V = V * torch.exp(0.5 * torch.randn(streams, n, 1, generator=gen, device=dev))
+    Q = torch.randn(streams, g, d, generator=gen, device=dev)
+    Q = Q / Q.norm(dim=-1, keepdim=True) * (r * (1.0 - 2.0 ** -7))
+    return K.to(dtype).contiguous(), V.to(dtype).contiguous(), Q.to(dtype).contiguous(), member
