@@ -118,6 +118,20 @@ int subgen_update(subgen_ctx *ctx, const void *K_t, const void *V_t);
 int subgen_attend(subgen_ctx *ctx, const void *Q_t, void *out);
 
 /*
+ * subgen_attend_many — QueryStreamAttn (Algorithm 1, with the window of Section 3.2) for a block of
+ * n_queries queries per stream against the current state: the queries of a chunk of prompt tokens, of a
+ * speculative draft, or of a wide grouped-query head group.  Every query gets exactly what subgen_attend
+ * would give it; n_queries is independent of the context's q_per_stream.  The state is not changed.
+ *   Q     device, [streams, n_queries, d] contiguous, context dtype
+ *   out   device, [streams, n_queries, d] contiguous, fp32, fully overwritten
+ * bf16 contexts with d = 64 or 128 in representative mode run both contractions (scores, weights x values)
+ * on the matrix cores and read the state once per 64 queries; other contexts answer the queries in groups of
+ * at most four with the decode kernels.
+ * Returns SUBGEN_EINVAL for n_queries outside 1..2^20, SUBGEN_EEMPTY if no token has been given yet.
+ */
+int subgen_attend_many(subgen_ctx *ctx, const void *Q, int32_t n_queries, void *out);
+
+/*
  * subgen_step — one decode step of Algorithm 1 (update with (K_t, V_t), then query with Q_t) in a
  * single pass over the center table.  State and output equal subgen_update followed by subgen_attend.
  */

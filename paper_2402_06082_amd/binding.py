@@ -22,7 +22,8 @@ FLAG_CENTER_OVERFLOW = 1
 FLAG_NONFINITE = 2
 
 EXPORTS = [
-    "subgen_create", "subgen_destroy", "subgen_update", "subgen_attend", "subgen_step", "subgen_ingest_prefix",
+    "subgen_create", "subgen_destroy", "subgen_update", "subgen_attend", "subgen_attend_many", "subgen_step",
+    "subgen_ingest_prefix",
     "subgen_exact_workspace_bytes", "subgen_exact_attend", "subgen_hbm_read_probe", "subgen_kcenter_workspace_bytes",
     "subgen_kcenter_compress", "subgen_stats", "subgen_center_counts",
     "subgen_export_state", "subgen_import_state", "subgen_sync", "subgen_strerror", "subgen_last_hip_error",
@@ -80,6 +81,8 @@ def load():
     L.subgen_update.argtypes = [P, P, P]
     L.subgen_attend.restype = C.c_int
     L.subgen_attend.argtypes = [P, P, P]
+    L.subgen_attend_many.restype = C.c_int
+    L.subgen_attend_many.argtypes = [P, P, i32, P]
     L.subgen_step.restype = C.c_int
     L.subgen_step.argtypes = [P, P, P, P, P]
     L.subgen_ingest_prefix.restype = C.c_int
@@ -208,6 +211,18 @@ class SubGen:
         q = self._rows(Q_t, (self.streams, self.g, self.d), "Q_t")
         o = self._rows(out, (self.streams, self.g, self.d), "out", torch.float32)
         _check(self._L.subgen_attend(self._h, q, o), "subgen_attend")
+        return out
+
+    def attend_many(self, Q: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Q [streams, n_queries, d] -> out [streams, n_queries, d] fp32; every query as in ``attend``."""
+        if Q.dim() != 3:
+            raise ValueError("Q must be [streams, n_queries, d]")
+        nq = int(Q.shape[1])
+        if out is None:
+            out = torch.empty(self.streams, nq, self.d, dtype=torch.float32, device=self.device)
+        q = self._rows(Q, (self.streams, nq, self.d), "Q")
+        o = self._rows(out, (self.streams, nq, self.d), "out", torch.float32)
+        _check(self._L.subgen_attend_many(self._h, q, nq, o), "subgen_attend_many")
         return out
 
     def step(self, K_t: torch.Tensor, V_t: torch.Tensor, Q_t: torch.Tensor,

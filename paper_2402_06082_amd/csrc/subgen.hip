@@ -17,6 +17,7 @@
 #include "subgen_dot2_device.hpp"
 #include "subgen_res_device.hpp"
 #include "kcenter_device.hpp"
+#include "attend_many_device.hpp"
 
 using sg::Call;
 using sg::State;
@@ -169,25 +170,27 @@ void launch_res_g(int G, Mode mode, dim3 grid, hipStream_t s, const State &st, c
 }
 
 // contexts with per-cluster reservoirs (t >= 1); MODE_UPDATE with n_tokens > 1 is the prefix ingest
-void launch_res(subgen_ctx *c, Mode mode, const Call &call)
+void launch_res(subgen_ctx *c, Mode mode, const Call &call, int G)
 {
     const dim3 grid((unsigned)c->S);
     if (c->dtype == SUBGEN_BF16) {
-        if (c->LPR == 8) launch_res_g<true, 8>(c->G, mode, grid, c->stream, c->st, call);
-        else if (c->LPR == 16) launch_res_g<true, 16>(c->G, mode, grid, c->stream, c->st, call);
-        else launch_res_g<true, 32>(c->G, mode, grid, c->stream, c->st, call);
+        if (c->LPR == 8) launch_res_g<true, 8>(G, mode, grid, c->stream, c->st, call);
+        else if (c->LPR == 16) launch_res_g<true, 16>(G, mode, grid, c->stream, c->st, call);
+        else launch_res_g<true, 32>(G, mode, grid, c->stream, c->st, call);
     } else {
-        if (c->LPR == 8) launch_res_g<false, 8>(c->G, mode, grid, c->stream, c->st, call);
-        else if (c->LPR == 16) launch_res_g<false, 16>(c->G, mode, grid, c->stream, c->st, call);
-        else launch_res_g<false, 32>(c->G, mode, grid, c->stream, c->st, call);
+        if (c->LPR == 8) launch_res_g<false, 8>(G, mode, grid, c->stream, c->st, call);
+        else if (c->LPR == 16) launch_res_g<false, 16>(G, mode, grid, c->stream, c->st, call);
+        else launch_res_g<false, 32>(G, mode, grid, c->stream, c->st, call);
     }
 }
 
-int launch_decode(subgen_ctx *c, Mode mode, const Call &call)
+// G = queries per stream of this launch (the context's own, or a group of a many-query call)
+int launch_decode(subgen_ctx *c, Mode mode, const Call &call, int G)
 {
     const dim3 grid((unsigned)c->S);
+    const bool mfma = c->mfma && mfma_supported(c->dtype, c->LPR, G);
     if (c->st.t > 0) {
-        launch_res(c, mode, call);
+        launch_res(c, mode, call, G);
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
     }
@@ -195,7 +198,7 @@ int launch_decode(subgen_ctx *c, Mode mode, const Call &call)
     // load, which the memory system serves faster than the 64-byte pieces of the matrix-core operand layout)
     // with packed-bf16 dot products.  With several queries per stream the vector ALUs would be the bound, so
     // those go to the matrix cores.
-    if (c->mfma && c->G == 1 && c->LPR == 16) {
+    if (mfma && G == 1 && c->LPR == 16) {
         switch (mode) {
             case MODE_UPDATE:
                 hipLaunchKernelGGL((sg::decode_dot2_kernel<true, false>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
@@ -210,13 +213,13 @@ int launch_decode(subgen_ctx *c, Mode mode, const Call &call)
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
     }
-    if (c->mfma) {
-        launch_mfma(c->LPR / 4, c->G, mode, grid, c->stream, c->st, call);
+    if (mfma) {
+        launch_mfma(c->LPR / 4, G, mode, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
     }
-    if (c->dtype == SUBGEN_BF16) launch_lpr<true>(c->LPR, c->G, mode, grid, c->stream, c->st, call);
-    else launch_lpr<false>(c->LPR, c->G, mode, grid, c->stream, c->st, call);
+    if (c->dtype == SUBGEN_BF16) launch_lpr<true>(c->LPR, G, mode, grid, c->stream, c->st, call);
+    else launch_lpr<false>(c->LPR, G, mode, grid, c->stream, c->st, call);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
 }
@@ -348,7 +351,7 @@ int subgen_update(subgen_ctx *c, const void *K_t, const void *V_t)
     call.K = (const char *)K_t; call.V = (const char *)V_t;
     call.stream_stride = (int64_t)c->d * c->esz; call.token_stride = call.stream_stride;
     call.n_tokens = 1; call.n_seen = c->n_seen;
-    const int rc = launch_decode(c, MODE_UPDATE, call);
+    const int rc = launch_decode(c, MODE_UPDATE, call, c->G);
     if (rc == SUBGEN_OK) c->n_seen += 1;
     return rc;
 }
@@ -360,7 +363,54 @@ int subgen_attend(subgen_ctx *c, const void *Q_t, void *out)
     DeviceGuard guard(c->device);
     Call call{};
     call.Q = (const char *)Q_t; call.out = (float *)out; call.n_seen = c->n_seen;
-    return launch_decode(c, MODE_ATTEND, call);
+    call.q_stride = (int64_t)c->G * c->d * c->esz; call.out_stride = (int64_t)c->G * c->d;
+    return launch_decode(c, MODE_ATTEND, call, c->G);
+}
+
+int subgen_attend_many(subgen_ctx *c, const void *Q, int32_t n_queries, void *out)
+{
+    if (!c || !Q || !out || !aligned16(Q) || !aligned16(out) || n_queries < 1 || n_queries > (1 << 20))
+        return SUBGEN_EINVAL;
+    if (c->n_seen == 0) return SUBGEN_EEMPTY;
+    DeviceGuard guard(c->device);
+    const int NK = c->LPR / 4;
+    if (c->mfma && (NK == 2 || NK == 4)) {
+        // bf16 rows of 64 or 128 elements, representative mode: both contractions on the matrix cores
+        const int QT = n_queries <= 16 ? 1 : (n_queries <= 32 ? 2 : 4);
+        sg::ManyCall mc{};
+        mc.Q = (const char *)Q; mc.out = (float *)out; mc.Gm = n_queries;
+        mc.tiles = (n_queries + 16 * QT - 1) / (16 * QT);
+        mc.n_seen = c->n_seen; mc.streams = c->S;
+        const int64_t blocks = (c->S + 7) / 8 * 8 * (int64_t)mc.tiles;
+        if (blocks > 0x7fffffffLL) return SUBGEN_ECAPACITY;
+        const dim3 grid((unsigned)blocks), wg(sg::kWG);
+        if (NK == 2) {
+            if (QT == 1) hipLaunchKernelGGL((sg::attend_many_kernel<2, 1, true>), grid, wg, 0, c->stream, c->st, mc);
+            else if (QT == 2) hipLaunchKernelGGL((sg::attend_many_kernel<2, 2, true>), grid, wg, 0, c->stream, c->st, mc);
+            else if (mc.tiles == 1) hipLaunchKernelGGL((sg::attend_many_kernel<2, 4, true>), grid, wg, 0, c->stream, c->st, mc);
+            else hipLaunchKernelGGL((sg::attend_many_kernel<2, 4, false>), grid, wg, 0, c->stream, c->st, mc);
+        } else {
+            if (QT == 1) hipLaunchKernelGGL((sg::attend_many_kernel<4, 1, true>), grid, wg, 0, c->stream, c->st, mc);
+            else if (QT == 2) hipLaunchKernelGGL((sg::attend_many_kernel<4, 2, true>), grid, wg, 0, c->stream, c->st, mc);
+            else if (mc.tiles == 1) hipLaunchKernelGGL((sg::attend_many_kernel<4, 4, true>), grid, wg, 0, c->stream, c->st, mc);
+            else hipLaunchKernelGGL((sg::attend_many_kernel<4, 4, false>), grid, wg, 0, c->stream, c->st, mc);
+        }
+        const hipError_t e = hipGetLastError();
+        return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+    }
+    // every other context (fp32 rows, 256-element rows, reservoirs, the generic kernel path): the decode
+    // kernels, four, two or one query at a time
+    const int64_t rowb = (int64_t)c->d * c->esz;
+    for (int32_t q0 = 0; q0 < n_queries;) {
+        const int g = n_queries - q0 >= 4 ? 4 : (n_queries - q0 >= 2 ? 2 : 1);
+        Call call{};
+        call.Q = (const char *)Q + q0 * rowb; call.out = (float *)out + (int64_t)q0 * c->d; call.n_seen = c->n_seen;
+        call.q_stride = n_queries * rowb; call.out_stride = (int64_t)n_queries * c->d;
+        const int rc = launch_decode(c, MODE_ATTEND, call, g);
+        if (rc != SUBGEN_OK) return rc;
+        q0 += g;
+    }
+    return SUBGEN_OK;
 }
 
 int subgen_step(subgen_ctx *c, const void *K_t, const void *V_t, const void *Q_t, void *out)
@@ -372,7 +422,8 @@ int subgen_step(subgen_ctx *c, const void *K_t, const void *V_t, const void *Q_t
     call.K = (const char *)K_t; call.V = (const char *)V_t;
     call.stream_stride = (int64_t)c->d * c->esz; call.token_stride = call.stream_stride;
     call.n_tokens = 1; call.Q = (const char *)Q_t; call.out = (float *)out; call.n_seen = c->n_seen;
-    const int rc = launch_decode(c, MODE_STEP, call);
+    call.q_stride = (int64_t)c->G * c->d * c->esz; call.out_stride = (int64_t)c->G * c->d;
+    const int rc = launch_decode(c, MODE_STEP, call, c->G);
     if (rc == SUBGEN_OK) c->n_seen += 1;
     return rc;
 }
@@ -397,7 +448,7 @@ int subgen_ingest_prefix(subgen_ctx *c, const void *K, const void *V, int64_t n,
         call.n_seen = c->n_seen;
         const dim3 grid((unsigned)c->S);
         if (c->st.t > 0)
-            launch_res(c, MODE_UPDATE, call);
+            launch_res(c, MODE_UPDATE, call, c->G);
         else if (c->mfma && c->LPR == 8)
             hipLaunchKernelGGL((sg::ingest_mfma_kernel<2>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
         else if (c->mfma && c->LPR == 16)

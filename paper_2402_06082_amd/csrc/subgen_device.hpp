@@ -59,6 +59,8 @@ struct Call {
     const char *Q;            // [S][G][d] or null
     float *out;               // [S][G][d] fp32 or null
     int64_t n_seen;           // tokens seen by every stream before this call
+    int64_t q_stride;         // bytes between the query blocks of two streams
+    int64_t out_stride;       // floats between the output blocks of two streams
 };
 
 // ---------------------------------------------------------------------------
@@ -562,11 +564,10 @@ __global__ __launch_bounds__(kWG) void decode_kernel(const State st, const Call 
     const size_t sid = blockIdx.x;
     int m = st.m[sid];
     double mu = st.mu[sid];
-    const size_t rowb = (size_t)LPR * 16;
     const char *krow = UPD ? call.K + sid * call.stream_stride : nullptr;
     const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
-    const char *qrows = ATT ? call.Q + sid * G * rowb : nullptr;
-    float *outrows = ATT ? call.out + sid * (size_t)G * LPR * VEC : nullptr;
+    const char *qrows = ATT ? call.Q + sid * call.q_stride : nullptr;
+    float *outrows = ATT ? call.out + sid * call.out_stride : nullptr;
     token_step<BF16, LPR, G, UPD, ATT>(st, sid, krow, vrow, qrows, outrows, call.n_seen, m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {

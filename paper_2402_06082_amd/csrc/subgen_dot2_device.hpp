@@ -389,8 +389,8 @@ __global__ __launch_bounds__(kWG) void decode_dot2_kernel(const State st, const 
     double mu = st.mu[sid];
     const char *krow = UPD ? call.K + sid * call.stream_stride : nullptr;
     const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
-    const char *qrow = ATT ? call.Q + sid * 256 : nullptr;
-    float *outrow = ATT ? call.out + sid * 128 : nullptr;
+    const char *qrow = ATT ? call.Q + sid * call.q_stride : nullptr;
+    float *outrow = ATT ? call.out + sid * call.out_stride : nullptr;
     token_step_dot2<UPD, ATT>(st, sid, krow, vrow, qrow, outrow, call.n_seen, m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {

@@ -157,7 +157,7 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
 {
     constexpr int CPR = 4 * NK;                    // 16-byte chunks per row
     constexpr int LPR = CPR;                       // lanes per row in the plain row layout (copies, norms)
-    constexpr int RPW = 64 / LPR, RPB = RPW * kWaves;
+    constexpr int RPW = 64 / LPR;
     constexpr size_t ROWB = (size_t)NK * 64;
     constexpr int D = NK * 32;
     constexpr int VL = CPR > 16 ? CPR / 16 : 1;    // value loads per row per lane (d = 256: 2)
@@ -617,11 +617,10 @@ __global__ __launch_bounds__(kWG, 3) void decode_mfma_kernel(const State st, con
     const size_t sid = blockIdx.x;
     int m = st.m[sid];
     double mu = st.mu[sid];
-    const size_t rowb = (size_t)NK * 64;
     const char *krow = UPD ? call.K + sid * call.stream_stride : nullptr;
     const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
-    const char *qrows = ATT ? call.Q + sid * G * rowb : nullptr;
-    float *outrows = ATT ? call.out + sid * (size_t)G * NK * 32 : nullptr;
+    const char *qrows = ATT ? call.Q + sid * call.q_stride : nullptr;
+    float *outrows = ATT ? call.out + sid * call.out_stride : nullptr;
     token_step_mfma<NK, G, UPD, ATT>(st, sid, krow, vrow, qrows, outrows, call.n_seen, m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {

@@ -353,11 +353,10 @@ __global__ __launch_bounds__(kWG) void decode_res_kernel(const State st, const C
     const size_t sid = blockIdx.x;
     int m = st.m[sid];
     double mu = st.mu[sid];
-    const size_t rowb = (size_t)LPR * 16;
     const char *kbase = UPD ? call.K + sid * call.stream_stride : nullptr;
     const char *vbase = UPD ? call.V + sid * call.stream_stride : nullptr;
-    const char *qrows = ATT ? call.Q + sid * G * rowb : nullptr;
-    float *outrows = ATT ? call.out + sid * (size_t)G * LPR * VEC : nullptr;
+    const char *qrows = ATT ? call.Q + sid * call.q_stride : nullptr;
+    float *outrows = ATT ? call.out + sid * call.out_stride : nullptr;
     const int64_t nt = UPD ? call.n_tokens : 1;
     for (int64_t t = 0; t < nt; ++t)
         token_step_res<BF16, LPR, G, UPD, ATT>(st, sid, UPD ? kbase + t * call.token_stride : nullptr,

@@ -300,6 +300,45 @@ def test_nonfinite_tokens_are_dropped_and_flagged(dtype, d, g, kernel_path, t, i
     assert st.flags_or == b.FLAG_NONFINITE and st.flagged_streams == 2
 
 
+@pytest.mark.parametrize("dtype,d,kernel_path,t", [(torch.bfloat16, 128, 0, 0), (torch.bfloat16, 64, 0, 0),
+                                                   (torch.bfloat16, 256, 0, 0), (torch.bfloat16, 128, 1, 0),
+                                                   (torch.float32, 64, 0, 0), (torch.bfloat16, 128, 0, 2)])
+@pytest.mark.parametrize("s,w,n", [(130, 17, 700), (64, 0, 333), (40, 50, 30), (512, 128, 1500)])
+def test_attend_many_matches_the_oracle_query_by_query(dtype, d, kernel_path, t, s, w, n):
+    """subgen_attend_many: every query of a block gets QueryStreamAttn's answer for the current state (matrix-core
+    kernel for bf16 d = 64 / 128, grouped decode kernels otherwise); query counts around the tile sizes, row counts
+    that are not multiples of the 32-row tiles, a window that is not full, no window."""
+    b = binding()
+    gen = torch.Generator(device="cpu").manual_seed(d + s + n + t)
+    S = 3
+    cent = torch.randn(S, 40, d, generator=gen) * 2.0
+    comp = torch.randint(0, 40, (S, n), generator=gen)
+    K = torch.gather(cent, 1, comp[..., None].expand(S, n, d)) + 0.2 * torch.randn(S, n, d, generator=gen)
+    V = torch.randn(S, n, d, generator=gen) * torch.exp(0.5 * torch.randn(S, n, 1, generator=gen))
+    K, V = K.to(dtype).to(DEV), V.to(dtype).to(DEV)
+    delta = 0.2 * (2 * d) ** 0.5 * 0.95            # a little below the typical spread: a few hundred clusters
+    sg = b.SubGen(S, d, delta, s, w, dtype=dtype, seed=2, device=DEV, kernel_path=kernel_path, t_per_cluster=t,
+                  max_centers=1024)
+    oracles = make_oracles(S, d, delta, s, w, seed=2, t=t, max_centers=1024)
+    sg.ingest_prefix(K, V)
+    Kc, Vc = to_f32_np(K), to_f32_np(V)
+    for i, o in enumerate(oracles):
+        o.ingest(Kc[i], Vc[i])
+    assert compare_state(sg, oracles) == 0
+    for nq in ([1, 5, 16, 17, 33, 64, 100, 130] if (s, w, n) == (130, 17, 700) else [7, 48]):
+        Q = (torch.randn(S, nq, d, generator=gen) / d ** 0.5 * 2.0).to(dtype).to(DEV)
+        out = sg.attend_many(Q).cpu().numpy()
+        Qc = to_f32_np(Q)
+        ref = np.stack([[o.attend(Qc[i, h]) for h in range(nq)] for i, o in enumerate(oracles)])
+        assert np.isfinite(out).all()
+        assert rel_l2(out, ref).max() <= REL_L2_TOL, (nq, rel_l2(out, ref).max())
+    # the state is untouched
+    assert compare_state(sg, oracles) == 0
+    with pytest.raises(b.SubgenError) as e:
+        sg.attend_many(torch.zeros(S, 0, d, dtype=dtype, device=DEV))
+    assert e.value.code == -1
+
+
 def test_error_codes():
     b = binding()
     sg = b.SubGen(2, 128, 1.0, 4, 2, dtype=torch.bfloat16, device=DEV)
