@@ -27,12 +27,9 @@
 #pragma once
 #include <type_traits>
 
-#include "subgen_mfma_device.hpp"
+#include "subgen_tile_device.hpp"
 
 namespace sg {
-
-typedef short shortx4_t __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
 struct ManyCall {
     const char *Q;   // [S][Gm][d] bf16
@@ -43,10 +40,6 @@ struct ManyCall {
     int64_t streams;
 };
 
-constexpr int kTileRows = 32;
-constexpr int kTiles = 4;                       // tiles staged per iteration
-constexpr int kSuper = kTileRows * kTiles;      // rows staged per iteration
-
 template <int NK>
 struct SmemMany {
     static constexpr int KS = NK * 64 + 16;   // key tile row stride (bytes): 16-byte operand reads hit distinct banks
@@ -56,26 +49,6 @@ struct SmemMany {
     alignas(16) float wrow[kSuper];
     float wmx[kWaves][16], wden[kWaves][16];
 };
-
-// rows k0..k0+3 of columns 16 cb .. 16 cb + 15 of a row-major bf16 tile, transposed: lane i of each 16-lane group
-// receives column 16 cb + i (element e = row k0 + e)
-__device__ __forceinline__ u32x2_t lds_read_tr16(const char *p)
-{
-    const shortx4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (shortx4_t __attribute__((address_space(3))) *)(p));
-    return __builtin_bit_cast(u32x2_t, v);
-}
-
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
-{
-    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-    bf16x2_t v;
-    v[0] = (__bf16)a;
-    v[1] = (__bf16)b;
-    return __builtin_bit_cast(uint32_t, v);
-}
-__device__ __forceinline__ float bf16_lo(uint32_t p) { return __uint_as_float(p << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
 
 template <int NK, int QT, bool NT>
 __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, const ManyCall call)

@@ -13,6 +13,7 @@
 #include "exact_device.hpp"
 #include "subgen_device.hpp"
 #include "subgen_mfma_device.hpp"
+#include "subgen_tile_device.hpp"
 #include "ingest_mfma_device.hpp"
 #include "subgen_dot2_device.hpp"
 #include "subgen_res_device.hpp"
@@ -129,16 +130,34 @@ void launch_mfma_mode(Mode mode, dim3 grid, hipStream_t s, const State &st, cons
 // matrix-core path: bf16 rows of 64, 128 or 256 elements, as long as the fp32 accumulators fit in registers
 bool mfma_supported(int dtype, int LPR, int G) { return dtype == SUBGEN_BF16 && (LPR / 4) * G <= 16; }
 
+// rows of 64 or 128 elements: the update alone scans the representatives straight from HBM; attend and step
+// stage the rows through LDS tiles and run the value products on the matrix cores as well
+template <int NK, int G>
+void launch_tile_mode(Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    switch (mode) {
+        case MODE_UPDATE:
+            hipLaunchKernelGGL((sg::decode_mfma_kernel<NK, 1, true, false>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+        case MODE_ATTEND:
+            hipLaunchKernelGGL((sg::decode_tile_kernel<NK, G, false>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+        case MODE_STEP:
+            hipLaunchKernelGGL((sg::decode_tile_kernel<NK, G, true>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+    }
+}
+
 void launch_mfma(int NK, int G, Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
 {
     if (NK == 2) {
-        if (G == 1) launch_mfma_mode<2, 1>(mode, grid, s, st, call);
-        else if (G == 2) launch_mfma_mode<2, 2>(mode, grid, s, st, call);
-        else launch_mfma_mode<2, 4>(mode, grid, s, st, call);
+        if (G == 1) launch_tile_mode<2, 1>(mode, grid, s, st, call);
+        else if (G == 2) launch_tile_mode<2, 2>(mode, grid, s, st, call);
+        else launch_tile_mode<2, 4>(mode, grid, s, st, call);
     } else if (NK == 4) {
-        if (G == 1) launch_mfma_mode<4, 1>(mode, grid, s, st, call);
-        else if (G == 2) launch_mfma_mode<4, 2>(mode, grid, s, st, call);
-        else launch_mfma_mode<4, 4>(mode, grid, s, st, call);
+        if (G == 1) launch_tile_mode<4, 1>(mode, grid, s, st, call);
+        else if (G == 2) launch_tile_mode<4, 2>(mode, grid, s, st, call);
+        else launch_tile_mode<4, 4>(mode, grid, s, st, call);
     } else {
         if (G == 1) launch_mfma_mode<8, 1>(mode, grid, s, st, call);
         else launch_mfma_mode<8, 2>(mode, grid, s, st, call);

@@ -40,6 +40,29 @@ __device__ __forceinline__ floatx4_t mfma_bf16(const uint4 &a, const uint4 &b, f
 constexpr float kDistEps = 1.0f / 16384.0f;
 constexpr float kLazy = 8.0f;  // the running softmax reference is raised only when a score exceeds it by this much
 
+typedef short shortx4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+
+// rows k0..k0+3 of columns 16 cb .. 16 cb + 15 of a row-major bf16 tile in LDS, transposed: lane i of each 16-lane
+// group passes the address of row k0 + i/4, columns 4 (i%4) .. +3, and receives column i (element e = row k0 + e)
+__device__ __forceinline__ u32x2_t lds_read_tr16(const char *p)
+{
+    const shortx4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (shortx4_t __attribute__((address_space(3))) *)(p));
+    return __builtin_bit_cast(u32x2_t, v);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b)   // round to nearest even
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    bf16x2_t v;
+    v[0] = (__bf16)a;
+    v[1] = (__bf16)b;
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+
 template <int NK, int G>
 struct SmemMfma {
     alignas(16) uint4 ekrow[NK * 4], evrow[NK * 4];   // the evicted (key, value) rows, for the sampling copies
