@@ -27,8 +27,9 @@ HBM_PEAK_GBS = 8000.0
 
 # Measured HBM traffic of one step-kernel launch (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script, each scaled by what the counter reads for a plain 1 GiB device copy
-# (profiles/step_kernel_cfg3_pmc_hbm_traffic.txt).  Workloads without a measurement report null.
-MEASURED_TRAFFIC_BYTES = {"cfg3": 4.0381e9}
+# (profiles/step_kernel_cfg3_pmc_hbm_traffic.txt, profiles/step_kernel_cfg5_pmc_hbm_traffic.txt).
+# Workloads without a measurement report null.
+MEASURED_TRAFFIC_BYTES = {"cfg3": 4.0381e9, "cfg5": 4.0381e9}
 
 
 def algorithmic_bytes(cfg, streams, total_centers, t=0):
