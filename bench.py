@@ -113,6 +113,8 @@ def main():
     ap.add_argument("--prefix", type=int, default=-1, help="override the prefix length (debugging)")
     ap.add_argument("--delta", type=float, default=0.0, help="skip tuning and use this threshold")
     ap.add_argument("--split", action="store_true", help="time subgen_update + subgen_attend instead of subgen_step")
+    ap.add_argument("--many", type=str, default="",
+                    help="comma-separated query counts: also time subgen_attend_many on the final state")
     ap.add_argument("--t", type=int, default=0, help="per-cluster reservoir slots (0 = representative mode)")
     ap.add_argument("--generic", action="store_true", help="force the generic vector-ALU kernels (kernel_path = 1)")
     ap.add_argument("--no-exact", action="store_true")
@@ -247,6 +249,31 @@ def main():
         exact = {"ms_per_step": ems, "steps_per_s": 1e3 / ems, "GB_per_s": kv_bytes / (ems * 1e-3) / 1e9,
                  "n": a.prefix}
         del Kall, Vall, ws
+    # ---- blocks of queries against the final state (subgen_attend_many), on request
+    many = None
+    if a.many:
+        many = []
+        state_bytes = alg - S * (cfg.elem_bytes * cfg.d * (4 + cfg.g) + 4 * cfg.g * cfg.d)   # the stored rows only
+        rows_per_stream = total_centers / S + 2 * cfg.s + 2 * cfg.w
+        for nq in [int(x) for x in a.many.split(",")]:
+            Qm = (torch.randn(S, nq, cfg.d, device=dev) / cfg.d ** 0.5).to(cfg.torch_dtype)
+            om = torch.empty(S, nq, cfg.d, dtype=torch.float32, device=dev)
+            for _ in range(3):
+                sg.attend_many(Qm, om)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 20
+            e0.record()
+            for _ in range(reps):
+                sg.attend_many(Qm, om)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            io = state_bytes + S * nq * cfg.d * (cfg.elem_bytes + 4)
+            many.append({"queries": nq, "ms": ms, "GB_per_s": io / (ms * 1e-3) / 1e9,
+                         "frac_hbm": io / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "TFLOP_per_s": 2.0 * S * nq * cfg.d * rows_per_stream / (ms * 1e-3) / 1e12})
+            del Qm, om
     setup_s = time.perf_counter() - t_setup
 
     cpu = None
@@ -279,6 +306,8 @@ def main():
         "cpu_baseline": cpu,
         "exact_full_kv": exact,
     }
+    if many is not None:
+        result["attend_many"] = many
     print(json.dumps(result))
     return 0
 
