@@ -188,7 +188,9 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
         }
     }
 
-    bool extra = false;
+    bool extra = false, decided = false, d_created = false, d_forced = false;
+    int d_target = 0;
+    uint4 xr = make_uint4(0, 0, 0, 0);
     if constexpr (UPD) {
         if (evict) {
             // ---- best / runner-up of the approximate distances over the workgroup
@@ -244,27 +246,20 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             const bool created = !join && !forced;
             const int target = created ? m : bidx;
             if constexpr (ATT) {
-                // score of the cluster that gained this token: one more term of the normaliser
+                // the cluster that gained this token adds one more term to the normaliser: its row is only
+                // requested here, the product waits until the row has landed (before the final merge)
                 if (wave == 0 && sub == 0) {
-                    uint4 xr = ek;
+                    xr = ek;
                     if (!created) xr = ld16(X + (size_t)target * ROWB + col * 16);
-                    const float a = row_sum16(dot8_bf16(xr, qp));
-                    if (col == 0) sm.bx = a;
                 }
                 extra = true;
             }
-            if (created) {
-                if (tid < LPR) st16(X + (size_t)m * ROWB + tid * 16, ek);
-                if (tid == 0) {
-                    cnt[m] = 1;
-                    xn[m] = nk;
-                }
-            } else if (tid == 0) {
-                cnt[target] += 1;
-                if (forced) st.flags[sid] |= 1u;
-            }
-            if (tid == 0 && st.assign != nullptr && etoken < st.assign_cap)
-                st.assign[sid * (size_t)st.assign_cap + etoken] = target;
+            // the cluster table is written at the very end of the step: nothing below reads it, and the barrier
+            // in between would have to wait for those stores (and the count's read-modify-write)
+            decided = true;
+            d_created = created;
+            d_forced = forced;
+            d_target = target;
             if (created) m += 1;
 
             // ---- sampling update: p from the old mu, one coin per slot, then mu += ||v||^2.  Accepts are rare
@@ -343,6 +338,10 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
         const int fill = (int)(n_after < st.w ? n_after : st.w);
         scan(Kw, Vw, nullptr, 1.f, fill, true);
 
+        if (extra && wave == 0 && sub == 0) {
+            const float a = row_sum16(dot8_bf16(xr, qp));
+            if (col == 0) sm.bx = a;
+        }
         // ---- merge the four row groups of the wavefront, then the wavefronts through LDS
         float M = fmaxf(mx, __shfl_xor(mx, 16));
         M = fmaxf(M, __shfl_xor(M, 32));
@@ -376,6 +375,23 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                 num = fmaf(sm.wacc[wv][tid], sc, num);
             }
             outrow[tid] = num / dn;
+        }
+    }
+    // ---- the update's writes to the cluster table (see the decision above)
+    if constexpr (UPD) {
+        if (decided) {
+            if (d_created) {
+                if (tid < LPR) st16(X + (size_t)d_target * ROWB + tid * 16, sm.ekrow[tid]);
+                if (tid == 0) {
+                    cnt[d_target] = 1;
+                    xn[d_target] = nk;
+                }
+            } else if (tid == 0) {
+                atomicAdd(&cnt[d_target], 1);
+                if (d_forced) st.flags[sid] |= 1u;
+            }
+            if (tid == 0 && st.assign != nullptr && etoken < st.assign_cap)
+                st.assign[sid * (size_t)st.assign_cap + etoken] = d_target;
         }
     }
 }
