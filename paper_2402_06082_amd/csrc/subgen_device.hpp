@@ -120,6 +120,15 @@ __device__ __forceinline__ T group_sum(T v)
     return v;
 }
 
+// Workgroup barrier that orders LDS traffic only: global loads that are in flight (the prefetched rows) stay in
+// flight across it.  Use __syncthreads() where global memory written by one lane is read by another.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // online-softmax partial of one row group for one query
 template <int VEC>
 struct Partial {

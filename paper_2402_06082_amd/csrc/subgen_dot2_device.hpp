@@ -47,6 +47,7 @@ __device__ __forceinline__ float row_sum16(float v)
 
 struct SmemDot2 {
     alignas(16) uint4 ekrow[16], evrow[16];   // the evicted (key, value) rows, for the sampling copies
+    alignas(16) uint4 nkrow[16], nvrow[16];   // the new token's rows (they enter the ring at the end of the step)
     float wb1[kWaves], wb2[kWaves], wnx[kWaves];
     int wi1[kWaves];
     double wbest[kWaves];
@@ -78,23 +79,23 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
     uint4 qp = make_uint4(0, 0, 0, 0);   // this lane's 8 packed query elements
     if constexpr (ATT) qp = ld16(qrow + col * 16);
 
-    // ---- window push; the token that leaves the window is the one that is compressed
+    // ---- window push; the token that leaves the window is the one that is compressed.  The new token's rows
+    //      are parked in LDS: the ring slot in HBM is rewritten at the very end of the step (nothing has to wait
+    //      for that store) and the window scan takes the slot's rows out of LDS instead.
     bool evict = false;
     int64_t etoken = 0;
+    int wslot = -1;
     uint4 ek = make_uint4(0, 0, 0, 0), ev = make_uint4(0, 0, 0, 0);
     float nk = 0.f, vn = 0.f;
     if constexpr (UPD) {
         const char *esk = krow, *esv = vrow;
-        char *kw = nullptr, *vw = nullptr;
         if (st.w == 0) {
             evict = true;
             etoken = n_seen;
         } else {
-            const int slot = (int)(n_seen % st.w);
-            kw = Kw + (size_t)slot * ROWB;
-            vw = Vw + (size_t)slot * ROWB;
-            esk = kw;
-            esv = vw;
+            wslot = (int)(n_seen % st.w);
+            esk = Kw + (size_t)wslot * ROWB;
+            esv = Vw + (size_t)wslot * ROWB;
             if (n_seen >= st.w) {
                 evict = true;
                 etoken = n_seen - st.w;
@@ -103,6 +104,16 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
         if (evict) {
             ek = ld16(esk + col * 16);
             ev = ld16(esv + col * 16);
+        }
+        if (st.w > 0 && tid < LPR) {
+            sm.nkrow[tid] = ld16(krow + tid * 16);
+            sm.nvrow[tid] = ld16(vrow + tid * 16);
+        }
+    }
+    // the evicted rows are consumed only after the first rows of the representatives have been requested
+    auto take_evicted = [&]() __attribute__((always_inline)) {
+        if constexpr (UPD) {
+            if (!evict) return;
             if (tid < LPR) {
                 sm.ekrow[tid] = ek;
                 sm.evrow[tid] = ev;
@@ -124,12 +135,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                 if (tid == 0) st.flags[sid] |= 2u;
             }
         }
-        __syncthreads();  // every lane holds the evicted row (registers, LDS) before the slot is overwritten
-        if (st.w > 0 && tid < LPR) {
-            st16(kw + tid * 16, ld16(krow + tid * 16));
-            st16(vw + tid * 16, ld16(vrow + tid * 16));
-        }
-    }
+    };
     const int64_t n_after = UPD ? n_seen + 1 : n_seen;
     const int64_t n_evicted_after = st.w == 0 ? n_after : (n_after > st.w ? n_after - st.w : 0);
 
@@ -142,10 +148,10 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
     //      count-weighted exp(<q, x_i>) for the softmax normaliser
     float b1 = INFINITY, b2 = INFINITY, nxmax = 0.f;
     int i1 = -1;
-    if ((UPD && evict) || ATT) {
-        for (int r0 = wave * RPW; r0 < m; r0 += RPB * U) {
-            uint4 raw[U];
-            float nx[U], cf[U];
+    {
+        uint4 raw[U];
+        float nx[U], cf[U];
+        auto issue = [&](const int r0) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int r = r0 + u * RPB + sub;
@@ -154,6 +160,12 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                 if constexpr (UPD) nx[u] = xn[rr];
                 if constexpr (ATT) cf[u] = (float)cnt[rr];
             }
+        };
+        const bool need = ATT || evict;   // an update without an evicted token has nothing to look up
+        int r0 = wave * RPW;
+        if (need && r0 < m) issue(r0);
+        take_evicted();
+        for (; need && r0 < m; r0 += RPB * U) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int r = r0 + u * RPB + sub;
@@ -185,6 +197,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                     }
                 }
             }
+            if (r0 + RPB * U < m) issue(r0 + RPB * U);
         }
     }
 
@@ -213,7 +226,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                 sm.wi1[wave] = i1;
                 sm.wnx[wave] = nxmax;
             }
-            __syncthreads();
+            lds_barrier();
             b1 = sm.wb1[0]; b2 = sm.wb2[0]; i1 = sm.wi1[0]; nxmax = sm.wnx[0];
 #pragma unroll
             for (int wv = 1; wv < kWaves; ++wv) {
@@ -284,19 +297,22 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                             }
                             st.sidx[sid * (size_t)st.sS + j] = (int32_t)etoken;
                             st.svn[sid * (size_t)st.sS + j] = vn;
+                            // the other lanes read these rows after the barrier below: wait for the stores here,
+                            // in the rare lane that made them, rather than in a full barrier for everybody
+                            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                         }
                     }
                 }
             }
             mu += (double)vn;
         }
-        __syncthreads();  // window slot, center row and sample rows are visible to the whole workgroup
+        lds_barrier();  // the new token's rows (LDS) and freshly sampled rows (released above) are visible
     }
 
     if constexpr (ATT) {
         // rows with values: sampled pairs (importance weights, numerator only), then the window (weight 1, both)
         auto scan = [&](const char *Kb, const char *Vb, const float *vnorm, const float wmul, const int nrows,
-                        const bool to_den) __attribute__((always_inline)) {
+                        const bool to_den, const int lds_row) __attribute__((always_inline)) {
             for (int r0 = wave * RPW; r0 < nrows; r0 += RPB * U) {
                 uint4 rk[U], rv[U];
                 float vnj[U];
@@ -307,6 +323,10 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                     rk[u] = ldnt16(Kb + (size_t)rr * ROWB + col * 16);
                     rv[u] = ldnt16(Vb + (size_t)rr * ROWB + col * 16);
                     vnj[u] = vnorm != nullptr ? vnorm[rr] : 1.f;
+                    if (rr == lds_row) {   // the new token's rows are not in the ring yet
+                        rk[u] = sm.nkrow[col];
+                        rv[u] = sm.nvrow[col];
+                    }
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -334,9 +354,9 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             }
         };
         if (n_evicted_after > 0)
-            scan(Ks, Vs, st.svn + sid * (size_t)st.sS, (float)(mu / (double)st.s), st.s, false);
+            scan(Ks, Vs, st.svn + sid * (size_t)st.sS, (float)(mu / (double)st.s), st.s, false, -1);
         const int fill = (int)(n_after < st.w ? n_after : st.w);
-        scan(Kw, Vw, nullptr, 1.f, fill, true);
+        scan(Kw, Vw, nullptr, 1.f, fill, true, wslot);
 
         if (extra && wave == 0 && sub == 0) {
             const float a = row_sum16(dot8_bf16(xr, qp));
@@ -377,8 +397,12 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             outrow[tid] = num / dn;
         }
     }
-    // ---- the update's writes to the cluster table (see the decision above)
+    // ---- the update's writes to the ring and to the cluster table (see above)
     if constexpr (UPD) {
+        if (wslot >= 0 && tid < LPR) {
+            st16(Kw + (size_t)wslot * ROWB + tid * 16, sm.nkrow[tid]);
+            st16(Vw + (size_t)wslot * ROWB + tid * 16, sm.nvrow[tid]);
+        }
         if (decided) {
             if (d_created) {
                 if (tid < LPR) st16(X + (size_t)d_target * ROWB + tid * 16, sm.ekrow[tid]);

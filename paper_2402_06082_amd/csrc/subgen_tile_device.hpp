@@ -30,15 +30,6 @@ constexpr int kTileRows = 32;
 constexpr int kTiles = 4;                       // tiles staged per iteration = wavefronts
 constexpr int kSuper = kTileRows * kTiles;      // rows staged per iteration
 
-// Workgroup barrier that orders LDS traffic only: global loads that are in flight (the prefetched rows) stay in
-// flight across it.  Use __syncthreads() where global memory written by one lane is read by another.
-__device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
 template <int NK, int G>
 struct SmemTile {
     static constexpr int KS = NK * 64 + 16;   // key tile row stride (bytes): 16-byte operand reads hit distinct banks
