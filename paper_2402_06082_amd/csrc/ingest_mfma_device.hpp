@@ -36,6 +36,11 @@ struct SmemIngest {
     float tt[kChunkT][kChunkT + 1];
     double wbest[kWaves];
     int widx[kWaves];
+    // per-cluster reservoirs (t >= 1): cluster of every token of the chunk, its coin probability 1/n_i, and
+    // which reservoir slots it wins
+    int tgt[kChunkT];
+    float pr[kChunkT];
+    uint8_t win[kChunkT][16];
 };
 
 // merge candidate (d, idx) into best / runner-up; lower index wins exact ties of the approximate value
@@ -50,7 +55,7 @@ __device__ __forceinline__ void cand_merge(float d, int idx, float &b1, int &i1,
     }
 }
 
-template <int NK>
+template <int NK, bool RES>
 __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, const Call call)
 {
     static_assert(kWaves == 4, "the chunk layout assumes four wavefronts per workgroup");
@@ -249,6 +254,9 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) nxmax = fmaxf(nxmax, __shfl_xor(nxmax, o));
         if (lane == 0) sm.wnx[wave] = nxmax;
+        if constexpr (RES) {
+            if (wave == 0) sm.tgt[lane] = -1;   // dropped tokens and the ragged tail keep -1
+        }
         __syncthreads();
 
         // ---- resolve in token order: lane j = token j of the chunk; every wavefront runs the same loop
@@ -300,6 +308,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             // tokens before the event are final: they join (or are force-joined to) their nearest cluster
             if (wave == 0 && live && j < e) {
                 if (ci < 0) ci = 0;   // only with non-finite representatives (imported state)
+                if constexpr (RES) sm.tgt[j] = ci;
                 atomicAdd(&cnt[ci], 1);
                 if (forced) atomicOr(&st.flags[sid], 1u);
                 if (st.assign != nullptr && c0 + j < st.assign_cap) st.assign[sid * (size_t)st.assign_cap + c0 + j] = ci;
@@ -336,9 +345,63 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             }
             if (tid == 0 && st.assign != nullptr && c0 + e < st.assign_cap)
                 st.assign[sid * (size_t)st.assign_cap + c0 + e] = target;
+            if constexpr (RES) {
+                if (tid == 0) sm.tgt[e] = target;
+            }
             done = e + 1;
         }
         m = m0 + __builtin_popcountll(cmask);
+
+        // ---- per-cluster reservoirs (UpdateSoftmaxNormalizer of Algorithm 1 as printed): a token that joins a
+        //      cluster of (then) n members takes each of the t slots with probability 1/n; the opener of a
+        //      cluster takes them all (n = 1).  Within the chunk the last winner of a (cluster, slot) stays.
+        if constexpr (RES) {
+            const int TT = st.t, TB = (TT + 3) >> 2;
+            char *const R = st.R + sid * (size_t)st.Mcap * TT * ROWB;
+            __syncthreads();   // every token's cluster is in LDS, the counts of the chunk are in memory
+            if (tid < T) {
+                const int c = tid < nt ? sm.tgt[tid] : -1;
+                float prj = -1.f;
+                if (c >= 0) {
+                    int later = 0;
+                    for (int l = tid + 1; l < nt; ++l) later += sm.tgt[l] == c;
+                    const int nj = atomicAdd(&cnt[c], 0) - later;   // members when this token arrived (itself included)
+                    prj = 1.0f / (float)nj;
+                }
+                sm.pr[tid] = prj;
+            }
+            __syncthreads();
+            for (int it = tid; it < T * TB; it += kWG) {
+                const int jj = it / TB, b = it % TB;
+                const float prj = sm.pr[jj];
+                uint32_t wbits = 0;
+                if (prj > 0.f) {
+                    const uint64_t ge = (uint64_t)(c0 + jj);
+                    uint32_t r[4];
+                    philox4x32_10((uint32_t)b, (uint32_t)ge, (uint32_t)(ge >> 32) | 0x80000000u, (uint32_t)sid,
+                                  st.seed_lo, st.seed_hi, r);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (4 * b + i < TT && (float)(r[i] >> 8) * (1.0f / 16777216.0f) < prj) wbits |= 1u << i;
+                }
+                sm.win[jj][b] = (uint8_t)wbits;
+            }
+            __syncthreads();
+            for (int it = tid; it < T * TT; it += kWG) {
+                const int jj = it / TT, sl = it % TT;
+                if (!((sm.win[jj][sl >> 2] >> (sl & 3)) & 1)) continue;
+                const int c = sm.tgt[jj];
+                bool last = true;
+                for (int l = jj + 1; l < nt; ++l)
+                    if (sm.tgt[l] == c && ((sm.win[l][sl >> 2] >> (sl & 3)) & 1)) last = false;
+                if (last) {
+                    const char *ks = krow_of(c0 + jj);
+                    char *dst = R + ((size_t)c * TT + sl) * ROWB;
+#pragma unroll
+                    for (int ch = 0; ch < CPR; ++ch) st16(dst + ch * 16, ld16(ks + ch * 16));
+                }
+            }
+        }
 
         // ---- sampling: p_j from the running mu (sequential double adds, token order), then the coins
         {

@@ -36,6 +36,7 @@ struct subgen_ctx {
     int device = 0;
     int last_hip = 0;
     bool mfma = false;     // bf16 rows scored on the matrix cores
+    bool ingest_mfma = false;   // bf16 rows of 64 / 128 elements: chunked prefix ingest (also with reservoirs)
     bool imported = false; // a stream state has been imported (pins n_seen)
     std::vector<void *> allocs;
 };
@@ -321,6 +322,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     c->dtype = o.dtype; c->esz = esz; c->LPR = d * esz / 16; c->delta = delta;
     c->stream = reinterpret_cast<hipStream_t>(o.hip_stream);
     c->mfma = o.kernel_path == 0 && o.t_per_cluster == 0 && mfma_supported(o.dtype, c->LPR, G);
+    c->ingest_mfma = o.kernel_path == 0 && o.dtype == SUBGEN_BF16 && (c->LPR == 8 || c->LPR == 16);
 
     State &st = c->st;
     st.Mcap = Mcap; st.s = sample_budget; st.w = window; st.d = d;
@@ -466,12 +468,16 @@ int subgen_ingest_prefix(subgen_ctx *c, const void *K, const void *V, int64_t n,
         call.n_tokens = (n - t0 < kChunk) ? n - t0 : kChunk;
         call.n_seen = c->n_seen;
         const dim3 grid((unsigned)c->S);
-        if (c->st.t > 0)
+        if (c->st.t > 0 && c->ingest_mfma && c->LPR == 8)
+            hipLaunchKernelGGL((sg::ingest_mfma_kernel<2, true>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+        else if (c->st.t > 0 && c->ingest_mfma && c->LPR == 16)
+            hipLaunchKernelGGL((sg::ingest_mfma_kernel<4, true>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+        else if (c->st.t > 0)
             launch_res(c, MODE_UPDATE, call, c->G);
         else if (c->mfma && c->LPR == 8)
-            hipLaunchKernelGGL((sg::ingest_mfma_kernel<2>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+            hipLaunchKernelGGL((sg::ingest_mfma_kernel<2, false>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
         else if (c->mfma && c->LPR == 16)
-            hipLaunchKernelGGL((sg::ingest_mfma_kernel<4>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+            hipLaunchKernelGGL((sg::ingest_mfma_kernel<4, false>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
         else if (c->dtype == SUBGEN_BF16) launch_ingest_lpr<true>(c->LPR, grid, c->stream, c->st, call);
         else launch_ingest_lpr<false>(c->LPR, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();

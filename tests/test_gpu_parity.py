@@ -437,6 +437,38 @@ def test_export_import_resumes_bit_identically(cfgname, g):
         c.import_raw(0, a.export_raw(0) | {"n_seen": 5})
 
 
+@pytest.mark.parametrize("d,t,w", [(128, 1, 5), (128, 5, 0), (64, 64, 3), (128, 7, 70)])
+def test_reservoir_chunked_ingest_matches_the_oracle_and_the_token_loop(d, t, w):
+    """Per-cluster reservoirs in the chunked prefix ingest (64 tokens at a time; several tokens of a chunk join the
+    same cluster, the last winner of a slot stays): calls of ragged sizes, few clusters, t up to the maximum."""
+    b = binding()
+    gen = torch.Generator(device="cpu").manual_seed(d + t + w)
+    S, n = 3, 500
+    cent = torch.randn(S, 6, d, generator=gen) * 2.0
+    comp = torch.randint(0, 6, (S, n), generator=gen)
+    K = torch.gather(cent, 1, comp[..., None].expand(S, n, d)) + 0.2 * torch.randn(S, n, d, generator=gen)
+    V = torch.randn(S, n, d, generator=gen)
+    K, V = K.to(torch.bfloat16).to(DEV), V.to(torch.bfloat16).to(DEV)
+    delta = 0.2 * (2 * d) ** 0.5 * 1.02
+    mk = lambda path: b.SubGen(S, d, delta, 9, w, dtype=torch.bfloat16, assign_log_tokens=n, seed=12, device=DEV,
+                               kernel_path=path, t_per_cluster=t)
+    chunked, loop = mk(0), mk(1)
+    oracles = make_oracles(S, d, delta, 9, w, seed=12, t=t)
+    Kc, Vc = to_f32_np(K), to_f32_np(V)
+    t0 = 0
+    for size in [1, 63, 64, 65, 200, n - 393]:
+        for sg in (chunked, loop):
+            sg.ingest_prefix(K[:, t0:t0 + size].contiguous(), V[:, t0:t0 + size].contiguous())
+        for i, o in enumerate(oracles):
+            o.ingest(Kc[i, t0:t0 + size], Vc[i, t0:t0 + size])
+        t0 += size
+        for sg in (chunked, loop):
+            assert compare_state(sg, oracles) == 0
+            for i, o in enumerate(oracles):
+                assert np.array_equal(sg.export_state(i).reservoirs, o.reservoirs), (t0, i)
+    assert t0 == n and chunked.center_counts().max() <= 60
+
+
 @pytest.mark.parametrize("dtype,d,g,t", [(torch.bfloat16, 128, 1, 1), (torch.bfloat16, 128, 4, 4),
                                          (torch.float32, 64, 1, 3), (torch.bfloat16, 64, 2, 8)])
 def test_reservoir_mode_matches_the_oracle(dtype, d, g, t):
