@@ -37,6 +37,7 @@ struct subgen_ctx {
     int last_hip = 0;
     bool mfma = false;     // bf16 rows scored on the matrix cores
     bool ingest_mfma = false;   // bf16 rows of 64 / 128 elements: chunked prefix ingest (also with reservoirs)
+    bool wide = false;          // few streams: 16 wavefronts per workgroup on the row path
     bool imported = false; // a stream state has been imported (pins n_seen)
     std::vector<void *> allocs;
 };
@@ -204,6 +205,23 @@ void launch_res(subgen_ctx *c, Mode mode, const Call &call, int G)
     }
 }
 
+template <int NW>
+void launch_dot2(Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    const dim3 wg(NW * 64);
+    switch (mode) {
+        case MODE_UPDATE:
+            hipLaunchKernelGGL((sg::decode_dot2_kernel<true, false, NW>), grid, wg, 0, s, st, call);
+            break;
+        case MODE_ATTEND:
+            hipLaunchKernelGGL((sg::decode_dot2_kernel<false, true, NW>), grid, wg, 0, s, st, call);
+            break;
+        case MODE_STEP:
+            hipLaunchKernelGGL((sg::decode_dot2_kernel<true, true, NW>), grid, wg, 0, s, st, call);
+            break;
+    }
+}
+
 // G = queries per stream of this launch (the context's own, or a group of a many-query call)
 int launch_decode(subgen_ctx *c, Mode mode, const Call &call, int G)
 {
@@ -219,17 +237,8 @@ int launch_decode(subgen_ctx *c, Mode mode, const Call &call, int G)
     // with packed-bf16 dot products.  With several queries per stream the vector ALUs would be the bound, so
     // those go to the matrix cores.
     if (mfma && G == 1 && c->LPR == 16) {
-        switch (mode) {
-            case MODE_UPDATE:
-                hipLaunchKernelGGL((sg::decode_dot2_kernel<true, false>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
-                break;
-            case MODE_ATTEND:
-                hipLaunchKernelGGL((sg::decode_dot2_kernel<false, true>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
-                break;
-            case MODE_STEP:
-                hipLaunchKernelGGL((sg::decode_dot2_kernel<true, true>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
-                break;
-        }
+        if (c->wide) launch_dot2<16>(mode, grid, c->stream, c->st, call);   // few streams: wide workgroups
+        else launch_dot2<4>(mode, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
     }
@@ -305,7 +314,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     if (sample_budget < 1 || sample_budget > (1 << 20) || window < 0 || window > (1 << 20)) return SUBGEN_EINVAL;
     if (G != 1 && G != 2 && G != 4) return SUBGEN_EINVAL;
     if (Mcap < 1 || Mcap > (1 << 24) || o.assign_log_tokens < 0) return SUBGEN_EINVAL;
-    if (o.kernel_path != 0 && o.kernel_path != 1) return SUBGEN_EINVAL;
+    if (o.kernel_path < 0 || o.kernel_path > 2) return SUBGEN_EINVAL;
     if (o.t_per_cluster < 0 || o.t_per_cluster > 64) return SUBGEN_EINVAL;
 
     subgen_ctx *c = new (std::nothrow) subgen_ctx();
@@ -321,8 +330,9 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     c->S = streams; c->d = d; c->s = sample_budget; c->w = window; c->Mcap = Mcap; c->G = G;
     c->dtype = o.dtype; c->esz = esz; c->LPR = d * esz / 16; c->delta = delta;
     c->stream = reinterpret_cast<hipStream_t>(o.hip_stream);
-    c->mfma = o.kernel_path == 0 && o.t_per_cluster == 0 && mfma_supported(o.dtype, c->LPR, G);
-    c->ingest_mfma = o.kernel_path == 0 && o.dtype == SUBGEN_BF16 && (c->LPR == 8 || c->LPR == 16);
+    c->mfma = o.kernel_path != 1 && o.t_per_cluster == 0 && mfma_supported(o.dtype, c->LPR, G);
+    c->ingest_mfma = o.kernel_path != 1 && o.dtype == SUBGEN_BF16 && (c->LPR == 8 || c->LPR == 16);
+    c->wide = o.kernel_path == 0 && streams <= 128;
 
     State &st = c->st;
     st.Mcap = Mcap; st.s = sample_budget; st.w = window; st.d = d;

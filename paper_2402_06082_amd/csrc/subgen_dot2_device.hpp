@@ -45,24 +45,25 @@ __device__ __forceinline__ float row_sum16(float v)
     return v;
 }
 
+template <int NW>
 struct SmemDot2 {
     alignas(16) uint4 ekrow[16], evrow[16];   // the evicted (key, value) rows, for the sampling copies
     alignas(16) uint4 nkrow[16], nvrow[16];   // the new token's rows (they enter the ring at the end of the step)
-    float wb1[kWaves], wb2[kWaves], wnx[kWaves];
-    int wi1[kWaves];
-    double wbest[kWaves];
-    int widx[kWaves];
+    float wb1[NW], wb2[NW], wnx[NW];
+    int wi1[NW];
+    double wbest[NW];
+    int widx[NW];
     float bx;
-    float wmx[kWaves], wden[kWaves];
-    float wacc[kWaves][128];
+    float wmx[NW], wden[NW];
+    float wacc[NW][128];
 };
 
-template <bool UPD, bool ATT>
+template <bool UPD, bool ATT, int NW>
 __device__ __forceinline__ void token_step_dot2(const State &st, const size_t sid, const char *krow, const char *vrow,
                                                 const char *qrow, float *outrow, const int64_t n_seen, int &m,
-                                                double &mu, SmemDot2 &sm)
+                                                double &mu, SmemDot2<NW> &sm)
 {
-    constexpr int LPR = 16, RPW = 4, RPB = RPW * kWaves;
+    constexpr int LPR = 16, RPW = 4, RPB = RPW * NW, WG = NW * 64;
     constexpr size_t ROWB = 256;
     constexpr int U = 8;   // row loads in flight per lane (8 measured slightly better than 4; 2 is 8 % slower)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -229,7 +230,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             lds_barrier();
             b1 = sm.wb1[0]; b2 = sm.wb2[0]; i1 = sm.wi1[0]; nxmax = sm.wnx[0];
 #pragma unroll
-            for (int wv = 1; wv < kWaves; ++wv) {
+            for (int wv = 1; wv < NW; ++wv) {
                 const float ob1 = sm.wb1[wv], ob2 = sm.wb2[wv];
                 const int oi1 = sm.wi1[wv];
                 if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
@@ -249,7 +250,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             const bool ambiguous = m > 0 && (!(b2 - b1 > 2.f * emax) || !(fabsf(b1 - thr) > emax + 1e-6f * thr));
             if (ambiguous) {
                 double best;
-                exact_nearest<LPR>(X, m, ek, sm.wbest, sm.widx, best, bidx);
+                exact_nearest<LPR, NW>(X, m, ek, sm.wbest, sm.widx, best, bidx);
                 join = bidx >= 0 && best <= st.delta2;
             } else {
                 join = m > 0 && b1 <= thr;
@@ -282,7 +283,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             else if (vn == 0.f) p = 0.f;
             else p = (float)((double)vn / (mu + (double)vn));
             if (p > 0.f) {
-                for (int j0 = tid * 4; j0 < st.s; j0 += kWG * 4) {
+                for (int j0 = tid * 4; j0 < st.s; j0 += WG * 4) {
                     uint32_t r[4];
                     philox4x32_10((uint32_t)(j0 >> 2), (uint32_t)etoken, (uint32_t)((uint64_t)etoken >> 32),
                                   (uint32_t)sid, st.seed_lo, st.seed_hi, r);
@@ -385,10 +386,10 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             const float bx = extra ? sm.bx : -INFINITY;
             float Mx = bx;
 #pragma unroll
-            for (int wv = 0; wv < kWaves; ++wv) Mx = fmaxf(Mx, sm.wmx[wv]);
+            for (int wv = 0; wv < NW; ++wv) Mx = fmaxf(Mx, sm.wmx[wv]);
             float dn = extra ? __expf(bx - Mx) : 0.f, num = 0.f;
 #pragma unroll
-            for (int wv = 0; wv < kWaves; ++wv) {
+            for (int wv = 0; wv < NW; ++wv) {
                 const float wm = sm.wmx[wv];
                 const float sc = (wm == -INFINITY) ? 0.f : __expf(wm - Mx);
                 dn = fmaf(sm.wden[wv], sc, dn);
@@ -420,10 +421,12 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
     }
 }
 
-template <bool UPD, bool ATT>
-__global__ __launch_bounds__(kWG) void decode_dot2_kernel(const State st, const Call call)
+// NW wavefronts per workgroup: 4 when there are streams enough to fill the chip; 16 for a few streams, where one
+// stream's rows in flight (1024 lanes x 8 loads) are what bounds the step
+template <bool UPD, bool ATT, int NW>
+__global__ __launch_bounds__(NW * 64) void decode_dot2_kernel(const State st, const Call call)
 {
-    __shared__ SmemDot2 sm;
+    __shared__ SmemDot2<NW> sm;
     const size_t sid = blockIdx.x;
     int m = st.m[sid];
     double mu = st.mu[sid];
@@ -431,7 +434,7 @@ __global__ __launch_bounds__(kWG) void decode_dot2_kernel(const State st, const 
     const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
     const char *qrow = ATT ? call.Q + sid * call.q_stride : nullptr;
     float *outrow = ATT ? call.out + sid * call.out_stride : nullptr;
-    token_step_dot2<UPD, ATT>(st, sid, krow, vrow, qrow, outrow, call.n_seen, m, mu, sm);
+    token_step_dot2<UPD, ATT, NW>(st, sid, krow, vrow, qrow, outrow, call.n_seen, m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {
             st.m[sid] = m;

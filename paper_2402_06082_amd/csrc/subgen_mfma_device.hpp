@@ -78,11 +78,11 @@ struct SmemMfma {
 };
 
 // Exact nearest representative in double precision (lowest index on ties); block-uniform result.
-template <int LPR>
+template <int LPR, int NW = kWaves>
 __device__ __forceinline__ void exact_nearest(const char *X, int m, const uint4 &ek, double *wbest, int *widx,
                                               double &best, int &bidx)
 {
-    constexpr int RPW = 64 / LPR, RPB = RPW * kWaves;
+    constexpr int RPW = 64 / LPR, RPB = RPW * NW;
     constexpr size_t ROWB = (size_t)LPR * 16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane % LPR, sub = lane / LPR;
@@ -132,7 +132,7 @@ __device__ __forceinline__ void exact_nearest(const char *X, int m, const uint4 
     best = wbest[0];
     bidx = widx[0];
 #pragma unroll
-    for (int wv = 1; wv < kWaves; ++wv) {
+    for (int wv = 1; wv < NW; ++wv) {
         const double ob = wbest[wv];
         const int oi = widx[wv];
         if (ob < best || (ob == best && (uint32_t)oi < (uint32_t)bidx)) {

@@ -82,7 +82,7 @@ def test_cfg1_single_head_fp32(name, fused):
         assert 20 <= m[0] <= 300
 
 
-@pytest.mark.parametrize("kernel_path", [0, 1])
+@pytest.mark.parametrize("kernel_path", [0, 1, 2])
 def test_cfg2_llama_layer_bf16_all_streams(kernel_path):
     b = binding()
     from paper_2402_06082_amd.tuning import tune_delta
@@ -170,7 +170,7 @@ def test_ingest_equals_updates_and_chunking_is_invariant():
     assert a.export_state(2).counts.tolist() == g.export_state(2).counts.tolist()
 
 
-@pytest.mark.parametrize("kernel_path", [0, 1])
+@pytest.mark.parametrize("kernel_path", [0, 1, 2])
 def test_step_equals_update_then_attend(kernel_path):
     b = binding()
     cfg = small_cfg(g=2)
@@ -194,7 +194,7 @@ def test_step_equals_update_then_attend(kernel_path):
 @pytest.mark.parametrize("dtype,d", [(torch.float32, 32), (torch.float32, 128), (torch.bfloat16, 64),
                                      (torch.bfloat16, 256)])
 @pytest.mark.parametrize("s,w", [(1, 0), (5, 3), (130, 17)])
-@pytest.mark.parametrize("kernel_path", [0, 1])
+@pytest.mark.parametrize("kernel_path", [0, 1, 2])
 def test_shapes_and_edge_parameters(dtype, d, s, w, kernel_path):
     """Other row sizes, w = 0 (pure Algorithm 1), s = 1, s not a multiple of 4, n < w, n = w, n = w + 1."""
     b = binding()
@@ -207,8 +207,10 @@ def test_shapes_and_edge_parameters(dtype, d, s, w, kernel_path):
     Q = torch.randn(S, n, 1, d, generator=gen) / d ** 0.5
     K, V, Q = (t.to(dtype).to(DEV) for t in (K, V, Q))
     delta = 0.2 * (2 * d) ** 0.5 * 1.05
-    if kernel_path == 1 and dtype == torch.float32:
+    if kernel_path != 0 and dtype == torch.float32:
         pytest.skip("fp32 rows always take the generic kernels")
+    if kernel_path == 2 and d != 128:
+        pytest.skip("only the row path (bf16, d = 128, one query) has a wide-workgroup variant")
     sg = b.SubGen(S, d, delta, s, w, dtype=dtype, assign_log_tokens=n, seed=11, device=DEV, kernel_path=kernel_path)
     oracles = make_oracles(S, d, delta, s, w, seed=11)
     for t in range(n):
@@ -252,7 +254,8 @@ def test_delta_zero_duplicates_and_center_overflow():
     assert all(o.overflowed for o in oracles)
 
 
-@pytest.mark.parametrize("dtype,d,g,kernel_path,t", [(torch.bfloat16, 128, 1, 0, 0), (torch.bfloat16, 128, 4, 0, 0),
+@pytest.mark.parametrize("dtype,d,g,kernel_path,t", [(torch.bfloat16, 128, 1, 0, 0), (torch.bfloat16, 128, 1, 2, 0),
+                                                     (torch.bfloat16, 128, 4, 0, 0),
                                                      (torch.bfloat16, 64, 2, 0, 0), (torch.bfloat16, 128, 1, 1, 0),
                                                      (torch.float32, 64, 1, 0, 0), (torch.bfloat16, 128, 1, 0, 2)])
 @pytest.mark.parametrize("ingest", [False, True])
