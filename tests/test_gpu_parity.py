@@ -223,32 +223,43 @@ def test_shapes_and_edge_parameters(dtype, d, s, w, kernel_path):
     assert 3 <= sg.center_counts().min() and sg.center_counts().max() <= 30
 
 
-def test_delta_zero_duplicates_and_center_overflow():
+@pytest.mark.parametrize("dtype,d,g,kernel_path", [(torch.float32, 64, 1, 0), (torch.bfloat16, 128, 1, 0),
+                                                   (torch.bfloat16, 128, 1, 2), (torch.bfloat16, 128, 4, 0),
+                                                   (torch.bfloat16, 64, 2, 0), (torch.bfloat16, 256, 1, 0)])
+def test_delta_zero_duplicates_and_center_overflow(dtype, d, g, kernel_path):
     b = binding()
-    d, S, n = 64, 2, 90
+    S, n, n_ing = 2, 90, 60
     gen = torch.Generator(device="cpu").manual_seed(5)
     pool = torch.randn(S, 12, d, generator=gen)
     pick = torch.randint(0, 12, (S, n), generator=gen)
-    K = torch.gather(pool, 1, pick[..., None].expand(S, n, d)).contiguous().to(DEV)
-    V = torch.randn(S, n, d, generator=gen).to(DEV)
-    Q = (torch.randn(S, 1, d, generator=gen) / 8).to(DEV)
+    K = torch.gather(pool, 1, pick[..., None].expand(S, n, d)).contiguous().to(dtype).to(DEV)
+    V = torch.randn(S, n, d, generator=gen).to(dtype).to(DEV)
+    Q = (torch.randn(S, n, g, d, generator=gen) / 8).to(dtype).to(DEV)
+    Kc, Vc, Qc = to_f32_np(K), to_f32_np(V), to_f32_np(Q)
+
+    def run(max_centers):
+        sg = b.SubGen(S, d, 0.0, 8, 0, dtype=dtype, q_per_stream=g, max_centers=max_centers, assign_log_tokens=n,
+                      device=DEV, kernel_path=kernel_path)
+        oracles = make_oracles(S, d, 0.0, 8, 0, max_centers=max_centers)
+        sg.ingest_prefix(K[:, :n_ing].contiguous(), V[:, :n_ing].contiguous())
+        for i, o in enumerate(oracles):
+            o.ingest(Kc[i, :n_ing], Vc[i, :n_ing])
+        assert compare_state(sg, oracles) == 0
+        for t in range(n_ing, n):   # the rest one step at a time: the fused kernels take the same decisions
+            out = sg.step(K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()).cpu().numpy()
+            ref = np.stack([o.decode(Kc[i, t:t + 1], Vc[i, t:t + 1], Qc[i, t:t + 1])[0] for i, o in enumerate(oracles)])
+            assert rel_l2(out, ref).max() <= REL_L2_TOL, t
+        assert compare_state(sg, oracles) == 0
+        return sg, oracles
+
     # delta = 0: only exact duplicates join, so the normaliser is the exact partition function
-    sg = b.SubGen(S, d, 0.0, 8, 0, assign_log_tokens=n, device=DEV)
-    oracles = make_oracles(S, d, 0.0, 8, 0)
-    sg.ingest_prefix(K, V)
-    for o, k, v in zip(oracles, to_f32_np(K), to_f32_np(V)):
-        o.ingest(k, v)
-    assert compare_state(sg, oracles) == 0 and sg.center_counts().max() <= 12
-    out = sg.attend(Q).cpu().numpy()
-    ref = np.stack([o.attend(to_f32_np(Q[i, 0]))[None] for i, o in enumerate(oracles)])
+    sg, oracles = run(0)
+    assert sg.center_counts().max() <= 12
+    out = sg.attend(Q[:, 0].contiguous()).cpu().numpy()
+    ref = np.stack([[o.attend(Qc[i, 0, h]) for h in range(g)] for i, o in enumerate(oracles)])
     assert rel_l2(out, ref).max() <= REL_L2_TOL
     # capacity 5 < 12 distinct keys: later tokens are force-joined and the sticky flag is raised
-    sg = b.SubGen(S, d, 0.0, 8, 0, max_centers=5, assign_log_tokens=n, device=DEV)
-    oracles = make_oracles(S, d, 0.0, 8, 0, max_centers=5)
-    sg.ingest_prefix(K, V)
-    for o, k, v in zip(oracles, to_f32_np(K), to_f32_np(V)):
-        o.ingest(k, v)
-    assert compare_state(sg, oracles) == 0
+    sg, oracles = run(5)
     st = sg.stats()
     assert st.max_centers == 5 and st.flags_or == b.FLAG_CENTER_OVERFLOW and st.flagged_streams == S
     assert all(o.overflowed for o in oracles)
