@@ -236,7 +236,9 @@ int launch_decode(subgen_ctx *c, Mode mode, const Call &call, int G)
     // load, which the memory system serves faster than the 64-byte pieces of the matrix-core operand layout)
     // with packed-bf16 dot products.  With several queries per stream the vector ALUs would be the bound, so
     // those go to the matrix cores.
-    if (mfma && G == 1 && c->LPR == 16) {
+    // (a query alone, with streams enough to fill the chip, is 3 % faster on the LDS-tiled kernel below: it has no
+    // update whose serial part would need the row path's higher occupancy to hide)
+    if (mfma && G == 1 && c->LPR == 16 && (mode != MODE_ATTEND || c->wide)) {
         if (c->wide) launch_dot2<16>(mode, grid, c->stream, c->st, call);   // few streams: wide workgroups
         else launch_dot2<4>(mode, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();
