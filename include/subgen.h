@@ -83,6 +83,14 @@ typedef struct subgen_opts {
                                sum_i n_i e^{<q,x_i>}.  t >= 1 = Algorithm 1 as printed: every cluster keeps t uniform
                                samples S_i of its keys and the normaliser is sum_i (n_i/t) sum_{k in S_i} e^{<q,k>}
                                (Lemma 2 (5), QueryStreamAttn); at most 64                                      */
+    int32_t device_counter; /* 1 = the number of tokens seen is kept in device memory and advanced by a one-lane
+                               kernel behind every update, so that update / attend / step / ingest launches can
+                               be captured into a HIP graph and replayed (each replay consumes the buffers it was
+                               captured with, at the position the stream has reached by then).  The host's own
+                               count, which the argument checks (SUBGEN_EEMPTY, the log capacity) and
+                               subgen_export_state use, is brought up to date by every synchronising call; call
+                               subgen_sync after replaying graphs.  0 (default) = the count is a kernel argument */
+    int32_t reserved_;      /* padding: zero */
 } subgen_opts;
 
 /*

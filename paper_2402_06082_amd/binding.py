@@ -40,7 +40,8 @@ class subgen_opts(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("dtype", C.c_int32), ("q_per_stream", C.c_int32),
                 ("max_centers", C.c_int32), ("assign_log_tokens", C.c_int64), ("seed", C.c_uint64),
                 ("hip_stream", C.c_void_p), ("device", C.c_int32), ("device_set", C.c_int32),
-                ("kernel_path", C.c_int32), ("t_per_cluster", C.c_int32)]
+                ("kernel_path", C.c_int32), ("t_per_cluster", C.c_int32), ("device_counter", C.c_int32),
+                ("reserved_", C.c_int32)]
 
 
 class subgen_stats_t(C.Structure):
@@ -155,7 +156,7 @@ class SubGen:
     def __init__(self, streams: int, d: int, delta: float, sample_budget: int, window: int, *,
                  dtype: torch.dtype = torch.float32, q_per_stream: int = 1, max_centers: int = 0,
                  assign_log_tokens: int = 0, seed: int = 0, device: Optional[torch.device] = None,
-                 kernel_path: int = 0, t_per_cluster: int = 0):
+                 kernel_path: int = 0, t_per_cluster: int = 0, device_counter: bool = False):
         self._L = load()
         self._h = C.c_void_p()
         if not torch.cuda.is_available():
@@ -179,6 +180,7 @@ class SubGen:
         o.device = self.device.index or 0
         o.device_set = 1
         o.kernel_path = int(kernel_path)
+        o.device_counter = 1 if device_counter else 0
         o.t_per_cluster = self.t = int(t_per_cluster)
         _check(self._L.subgen_create(C.byref(self._h), self.streams, self.d, C.c_float(self.delta), self.s, self.w,
                                      C.byref(o)), "subgen_create")

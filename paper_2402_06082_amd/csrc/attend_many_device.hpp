@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
     const float *const svn = st.svn + sid * (size_t)st.sS;
     const int m = st.m[sid];
     const float mus = (float)(st.mu[sid] / (double)st.s);
-    const int64_t n_seen = call.n_seen;
+    const int64_t n_seen = tokens_seen(st, call.n_seen);
     const int64_t n_evicted = st.w == 0 ? n_seen : (n_seen > st.w ? n_seen - st.w : 0);
     const int fill = (int)(n_seen < st.w ? n_seen : st.w);
 

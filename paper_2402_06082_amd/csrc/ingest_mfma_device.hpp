@@ -80,7 +80,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
     const char *const kin = call.K + sid * call.stream_stride;
     const char *const vin = call.V + sid * call.stream_stride;
 
-    const int64_t n0 = call.n_seen, n = call.n_tokens, w = st.w;
+    const int64_t n0 = tokens_seen(st, call.n_seen), n = call.n_tokens, w = st.w;
     // global indices [ge0, ge1) of the tokens that leave the window during this call
     const int64_t ge0 = w == 0 ? n0 : (n0 > w ? n0 - w : 0);
     int64_t ge1 = w == 0 ? n0 + n : n0 + n - w;

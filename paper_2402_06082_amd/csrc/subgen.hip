@@ -38,6 +38,7 @@ struct subgen_ctx {
     bool mfma = false;     // bf16 rows scored on the matrix cores
     bool ingest_mfma = false;   // bf16 rows of 64 / 128 elements: chunked prefix ingest (also with reservoirs)
     bool wide = false;          // few streams: 16 wavefronts per workgroup on the row path
+    bool dev_seen = false;      // the token count lives on the device (launches can be captured and replayed)
     bool imported = false; // a stream state has been imported (pins n_seen)
     std::vector<void *> allocs;
 };
@@ -292,6 +293,24 @@ void launch_exact_g(int g, const sg::ExactCall &c, int64_t streams, hipStream_t 
     else launch_exact<BF16, LPR, 4>(c, streams, s);
 }
 
+// contexts that keep the token count on the device: advance it behind the kernels of an update
+int bump_seen(subgen_ctx *c, int64_t n)
+{
+    if (!c->dev_seen) return SUBGEN_OK;
+    hipLaunchKernelGGL(sg::bump_seen_kernel, dim3(1), dim3(1), 0, c->stream, c->st.seen, n);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+}
+
+// ... and bring the host's copy up to date (after replays of a captured graph the host has not counted)
+int refresh_seen(subgen_ctx *c)
+{
+    if (!c->dev_seen) return SUBGEN_OK;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e == hipSuccess) e = hipMemcpy(&c->n_seen, c->st.seen, sizeof(int64_t), hipMemcpyDeviceToHost);
+    return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+}
+
 }  // namespace
 
 extern "C" {
@@ -318,6 +337,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     if (Mcap < 1 || Mcap > (1 << 24) || o.assign_log_tokens < 0) return SUBGEN_EINVAL;
     if (o.kernel_path < 0 || o.kernel_path > 2) return SUBGEN_EINVAL;
     if (o.t_per_cluster < 0 || o.t_per_cluster > 64) return SUBGEN_EINVAL;
+    if (o.device_counter != 0 && o.device_counter != 1) return SUBGEN_EINVAL;
 
     subgen_ctx *c = new (std::nothrow) subgen_ctx();
     if (!c) return SUBGEN_ENOMEM;
@@ -335,6 +355,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     c->mfma = o.kernel_path != 1 && o.t_per_cluster == 0 && mfma_supported(o.dtype, c->LPR, G);
     c->ingest_mfma = o.kernel_path != 1 && o.dtype == SUBGEN_BF16 && (c->LPR == 8 || c->LPR == 16);
     c->wide = o.kernel_path == 0 && streams <= 128;
+    c->dev_seen = o.device_counter != 0;
 
     State &st = c->st;
     st.Mcap = Mcap; st.s = sample_budget; st.w = window; st.d = d;
@@ -358,6 +379,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.Vw, S * window * rowb, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.mu, S, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.flags, S, 0);
+    if (rc == SUBGEN_OK && o.device_counter) rc = dev_alloc(c, &st.seen, 1, 0);
     if (rc == SUBGEN_OK && st.assign_cap > 0) rc = dev_alloc(c, &st.assign, S * (size_t)st.assign_cap, 0xFF);
     if (rc != SUBGEN_OK) {
         subgen_destroy(c);
@@ -384,7 +406,8 @@ int subgen_update(subgen_ctx *c, const void *K_t, const void *V_t)
     call.K = (const char *)K_t; call.V = (const char *)V_t;
     call.stream_stride = (int64_t)c->d * c->esz; call.token_stride = call.stream_stride;
     call.n_tokens = 1; call.n_seen = c->n_seen;
-    const int rc = launch_decode(c, MODE_UPDATE, call, c->G);
+    int rc = launch_decode(c, MODE_UPDATE, call, c->G);
+    if (rc == SUBGEN_OK) rc = bump_seen(c, 1);
     if (rc == SUBGEN_OK) c->n_seen += 1;
     return rc;
 }
@@ -456,7 +479,8 @@ int subgen_step(subgen_ctx *c, const void *K_t, const void *V_t, const void *Q_t
     call.stream_stride = (int64_t)c->d * c->esz; call.token_stride = call.stream_stride;
     call.n_tokens = 1; call.Q = (const char *)Q_t; call.out = (float *)out; call.n_seen = c->n_seen;
     call.q_stride = (int64_t)c->G * c->d * c->esz; call.out_stride = (int64_t)c->G * c->d;
-    const int rc = launch_decode(c, MODE_STEP, call, c->G);
+    int rc = launch_decode(c, MODE_STEP, call, c->G);
+    if (rc == SUBGEN_OK) rc = bump_seen(c, 1);
     if (rc == SUBGEN_OK) c->n_seen += 1;
     return rc;
 }
@@ -494,6 +518,8 @@ int subgen_ingest_prefix(subgen_ctx *c, const void *K, const void *V, int64_t n,
         else launch_ingest_lpr<false>(c->LPR, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail_hip(c, e);
+        const int rb = bump_seen(c, call.n_tokens);
+        if (rb != SUBGEN_OK) return rb;
         c->n_seen += call.n_tokens;
     }
     return SUBGEN_OK;
@@ -595,7 +621,8 @@ int subgen_sync(subgen_ctx *c)
     if (!c) return SUBGEN_EINVAL;
     DeviceGuard guard(c->device);
     const hipError_t e = hipStreamSynchronize(c->stream);
-    return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+    if (e != hipSuccess) return fail_hip(c, e);
+    return refresh_seen(c);
 }
 
 static int64_t evicted(const subgen_ctx *c)
@@ -610,7 +637,8 @@ int subgen_center_counts(subgen_ctx *c, int32_t *host_m)
     DeviceGuard guard(c->device);
     hipError_t e = hipStreamSynchronize(c->stream);
     if (e == hipSuccess) e = hipMemcpy(host_m, c->st.m, (size_t)c->S * sizeof(int32_t), hipMemcpyDeviceToHost);
-    return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+    if (e != hipSuccess) return fail_hip(c, e);
+    return refresh_seen(c);
 }
 
 int subgen_stats(subgen_ctx *c, subgen_stats_t *o)
@@ -644,6 +672,7 @@ int subgen_export_state(subgen_ctx *c, int64_t stream, subgen_state_view *v)
     DeviceGuard guard(c->device);
     hipError_t e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) return fail_hip(c, e);
+    if (const int rs = refresh_seen(c); rs != SUBGEN_OK) return rs;
     const State &st = c->st;
     const size_t sid = (size_t)stream, rowb = (size_t)c->d * c->esz;
 #define SG_D2H(dst, src, bytes)                                                       \
@@ -696,6 +725,7 @@ int subgen_import_state(subgen_ctx *c, int64_t stream, const subgen_state_view *
     if (!v->sample_K || !v->sample_V || !v->sample_idx || !v->sample_vn) return SUBGEN_EINVAL;
     if (c->w > 0 && (!v->window_K || !v->window_V)) return SUBGEN_EINVAL;
     // all streams of a context share one token counter: the first import into an untouched context sets it
+    if (const int rs = refresh_seen(c); rs != SUBGEN_OK) return rs;
     if (c->n_seen != v->n_seen && (c->n_seen != 0 || c->imported)) return SUBGEN_EINVAL;
     DeviceGuard guard(c->device);
     hipError_t e = hipStreamSynchronize(c->stream);
@@ -738,6 +768,10 @@ int subgen_import_state(subgen_ctx *c, int64_t stream, const subgen_state_view *
     if (e != hipSuccess) return fail_hip(c, e);
     c->n_seen = v->n_seen;
     c->imported = true;
+    if (c->dev_seen) {
+        e = hipMemcpy(c->st.seen, &c->n_seen, sizeof(int64_t), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return fail_hip(c, e);
+    }
     return SUBGEN_OK;
 }
 

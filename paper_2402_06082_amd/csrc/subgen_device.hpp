@@ -50,7 +50,18 @@ struct State {
     int32_t McapS, sS;  // strides of the per-center / per-slot scalar arrays (Mcap, s rounded up to 16)
     double delta2;      // delta^2
     uint32_t seed_lo, seed_hi;
+    int64_t *seen;      // [1] tokens seen by every stream, kept on the device (contexts made for graph capture), or null
 };
+
+// Tokens seen before this launch: the host's count (a kernel argument), or, in contexts that keep the count on the
+// device so that a captured launch can be replayed, the device's.
+__device__ __forceinline__ int64_t tokens_seen(const State &st, const int64_t host_count)
+{
+    return st.seen != nullptr ? *st.seen : host_count;
+}
+
+// runs after the kernels of an update in such contexts
+__global__ void bump_seen_kernel(int64_t *seen, int64_t n) { *seen += n; }
 
 struct Call {
     const char *K, *V;        // new tokens; token t of stream j at K + j*stream_stride + t*token_stride (bytes)
@@ -577,7 +588,7 @@ __global__ __launch_bounds__(kWG) void decode_kernel(const State st, const Call 
     const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
     const char *qrows = ATT ? call.Q + sid * call.q_stride : nullptr;
     float *outrows = ATT ? call.out + sid * call.out_stride : nullptr;
-    token_step<BF16, LPR, G, UPD, ATT>(st, sid, krow, vrow, qrows, outrows, call.n_seen, m, mu, sm);
+    token_step<BF16, LPR, G, UPD, ATT>(st, sid, krow, vrow, qrows, outrows, tokens_seen(st, call.n_seen), m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {
             st.m[sid] = m;
@@ -597,9 +608,10 @@ __global__ __launch_bounds__(kWG) void ingest_kernel(const State st, const Call 
     double mu = st.mu[sid];
     const char *kbase = call.K + sid * call.stream_stride;
     const char *vbase = call.V + sid * call.stream_stride;
+    const int64_t n0 = tokens_seen(st, call.n_seen);
     for (int64_t t = 0; t < call.n_tokens; ++t)
         token_step<BF16, LPR, 1, true, false>(st, sid, kbase + t * call.token_stride, vbase + t * call.token_stride,
-                                              nullptr, nullptr, call.n_seen + t, m, mu, sm);
+                                              nullptr, nullptr, n0 + t, m, mu, sm);
     if (threadIdx.x == 0) {
         st.m[sid] = m;
         st.mu[sid] = mu;

@@ -434,7 +434,7 @@ __global__ __launch_bounds__(NW * 64) void decode_dot2_kernel(const State st, co
     const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
     const char *qrow = ATT ? call.Q + sid * call.q_stride : nullptr;
     float *outrow = ATT ? call.out + sid * call.out_stride : nullptr;
-    token_step_dot2<UPD, ATT, NW>(st, sid, krow, vrow, qrow, outrow, call.n_seen, m, mu, sm);
+    token_step_dot2<UPD, ATT, NW>(st, sid, krow, vrow, qrow, outrow, tokens_seen(st, call.n_seen), m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {
             st.m[sid] = m;

@@ -644,7 +644,7 @@ __global__ __launch_bounds__(kWG, 3) void decode_mfma_kernel(const State st, con
     const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
     const char *qrows = ATT ? call.Q + sid * call.q_stride : nullptr;
     float *outrows = ATT ? call.out + sid * call.out_stride : nullptr;
-    token_step_mfma<NK, G, UPD, ATT>(st, sid, krow, vrow, qrows, outrows, call.n_seen, m, mu, sm);
+    token_step_mfma<NK, G, UPD, ATT>(st, sid, krow, vrow, qrows, outrows, tokens_seen(st, call.n_seen), m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {
             st.m[sid] = m;

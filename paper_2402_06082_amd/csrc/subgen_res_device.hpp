@@ -358,10 +358,11 @@ __global__ __launch_bounds__(kWG) void decode_res_kernel(const State st, const C
     const char *qrows = ATT ? call.Q + sid * call.q_stride : nullptr;
     float *outrows = ATT ? call.out + sid * call.out_stride : nullptr;
     const int64_t nt = UPD ? call.n_tokens : 1;
+    const int64_t n0 = tokens_seen(st, call.n_seen);
     for (int64_t t = 0; t < nt; ++t)
         token_step_res<BF16, LPR, G, UPD, ATT>(st, sid, UPD ? kbase + t * call.token_stride : nullptr,
                                                UPD ? vbase + t * call.token_stride : nullptr, qrows, outrows,
-                                               call.n_seen + t, m, mu, sm);
+                                               n0 + t, m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {
             st.m[sid] = m;

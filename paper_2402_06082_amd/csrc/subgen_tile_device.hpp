@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
     const char *const vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
     const char *const qrows = call.Q + sid * call.q_stride;
     float *const outrows = call.out + sid * call.out_stride;
-    const int64_t n_seen = call.n_seen;
+    const int64_t n_seen = tokens_seen(st, call.n_seen);
     int m = st.m[sid];
     double mu = st.mu[sid];
 

@@ -353,6 +353,66 @@ def test_attend_many_matches_the_oracle_query_by_query(dtype, d, kernel_path, t,
     assert e.value.code == -1
 
 
+@pytest.mark.parametrize("dtype,d,g,streams", [(torch.bfloat16, 128, 1, 3), (torch.bfloat16, 128, 1, 130),
+                                               (torch.bfloat16, 128, 4, 3), (torch.float32, 64, 2, 3)])
+def test_captured_step_replays_like_eager_steps(dtype, d, g, streams):
+    """opts.device_counter: a subgen_step captured once into a HIP graph is replayed for many tokens (the token
+    count lives on the device), with eager calls and synchronisations in between; every replay equals the oracle."""
+    b = binding()
+    gen = torch.Generator(device="cpu").manual_seed(d + g + streams)
+    S, n0, steps, s, w = streams, 70, 26, 12, 5
+    n = n0 + steps
+    cent = torch.randn(S, 6, d, generator=gen) * 2.0
+    comp = torch.randint(0, 6, (S, n), generator=gen)
+    K = torch.gather(cent, 1, comp[..., None].expand(S, n, d)) + 0.2 * torch.randn(S, n, d, generator=gen)
+    V = torch.randn(S, n, d, generator=gen)
+    Q = torch.randn(S, n, g, d, generator=gen) / d ** 0.5
+    K, V, Q = (x.to(dtype).to(DEV) for x in (K, V, Q))
+    delta = 0.2 * (2 * d) ** 0.5 * 1.05
+    ids = [0, 1, S - 1]
+    oracles = make_oracles(S, d, delta, s, w, seed=8, stream_ids=ids)
+    Kc, Vc, Qc = to_f32_np(K[ids]), to_f32_np(V[ids]), to_f32_np(Q[ids])
+    for i, o in enumerate(oracles):
+        o.ingest(Kc[i, :n0], Vc[i, :n0])
+    side = torch.cuda.Stream(device=DEV)
+    side.wait_stream(torch.cuda.current_stream(DEV))
+    with torch.cuda.stream(side):
+        sg = b.SubGen(S, d, delta, s, w, dtype=dtype, q_per_stream=g, assign_log_tokens=n, seed=8, device=DEV,
+                      device_counter=True)
+        sg.ingest_prefix(K[:, :n0].contiguous(), V[:, :n0].contiguous())
+        kt, vt, qt = K[:, n0].clone(), V[:, n0].clone(), Q[:, n0].clone()
+        out = torch.empty(S, g, d, dtype=torch.float32, device=DEV)
+
+    def check(t, got):
+        ref = np.stack([o.decode(Kc[i, t:t + 1], Vc[i, t:t + 1], Qc[i, t:t + 1])[0] for i, o in enumerate(oracles)])
+        assert rel_l2(got.cpu().numpy()[ids], ref).max() <= REL_L2_TOL, t
+
+    with torch.cuda.stream(side):
+        sg.step(kt, vt, qt, out)                       # token n0, eager (also the warm-up before the capture)
+    side.synchronize()
+    check(n0, out)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sg.step(kt, vt, qt, out)                       # captured, not run
+    sg.sync()                                          # the host's count follows the device's again
+    t = n0 + 1
+    while t < n:
+        with torch.cuda.stream(side):
+            kt.copy_(K[:, t]); vt.copy_(V[:, t]); qt.copy_(Q[:, t])
+            if (t - n0) % 5 == 0:                      # now and then an eager step between the replays
+                sg.step(kt, vt, qt, out)
+            else:
+                graph.replay()
+        side.synchronize()
+        check(t, out)
+        if (t - n0) % 7 == 0:
+            assert compare_state(sg, oracles, stream_ids=ids) == 0
+            _ = (torch.randn(64, 64, device=DEV) @ torch.randn(64, 64, device=DEV)).sum().item()   # other GPU work
+        t += 1
+    assert compare_state(sg, oracles, stream_ids=ids) == 0
+    assert sg.export_state(0, rows=False).n_seen == n
+
+
 def test_error_codes():
     b = binding()
     sg = b.SubGen(2, 128, 1.0, 4, 2, dtype=torch.bfloat16, device=DEV)
