@@ -77,7 +77,7 @@ typedef struct subgen_opts {
     int32_t kernel_path;    /* 0 = automatic (bf16 rows are scored on the matrix cores where the shape allows);
                                1 = always the generic vector-ALU kernels (any dtype; same results up to fp32
                                rounding of the outputs, identical decisions);
-                               2 = as 0, but never the 16-wavefront workgroups that 0 picks for contexts of at
+                               2 = as 0, but never the wide-workgroup kernels that 0 picks for contexts of at
                                most 128 streams (the kernels of large contexts on a small one: for tests)     */
     int32_t t_per_cluster;  /* t: reservoir slots per cluster.  0 (default) = representative mode: the normaliser is
                                sum_i n_i e^{<q,x_i>}.  t >= 1 = Algorithm 1 as printed: every cluster keeps t uniform

@@ -37,7 +37,7 @@ struct subgen_ctx {
     int last_hip = 0;
     bool mfma = false;     // bf16 rows scored on the matrix cores
     bool ingest_mfma = false;   // bf16 rows of 64 / 128 elements: chunked prefix ingest (also with reservoirs)
-    bool wide = false;          // few streams: 16 wavefronts per workgroup on the row path
+    bool wide = false;          // few streams: 8 wavefronts per workgroup and hoisted loads on the row path
     bool dev_seen = false;      // the token count lives on the device (launches can be captured and replayed)
     bool imported = false; // a stream state has been imported (pins n_seen)
     std::vector<void *> allocs;
@@ -240,7 +240,7 @@ int launch_decode(subgen_ctx *c, Mode mode, const Call &call, int G)
     // (a query alone, with streams enough to fill the chip, is 3 % faster on the LDS-tiled kernel below: it has no
     // update whose serial part would need the row path's higher occupancy to hide)
     if (mfma && G == 1 && c->LPR == 16 && (mode != MODE_ATTEND || c->wide)) {
-        if (c->wide) launch_dot2<16>(mode, grid, c->stream, c->st, call);   // few streams: wide workgroups
+        if (c->wide) launch_dot2<8>(mode, grid, c->stream, c->st, call);   // few streams: wide workgroups, hoisted loads
         else launch_dot2<4>(mode, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();
         return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);

@@ -49,6 +49,7 @@ template <int NW>
 struct SmemDot2 {
     alignas(16) uint4 ekrow[16], evrow[16];   // the evicted (key, value) rows, for the sampling copies
     alignas(16) uint4 nkrow[16], nvrow[16];   // the new token's rows (they enter the ring at the end of the step)
+    uint32_t accm[NW == 8 ? 256 : 1];         // slots that took the evicted token in this step (hoisted variant)
     float wb1[NW], wb2[NW], wnx[NW];
     int wi1[NW];
     double wbest[NW];
@@ -66,6 +67,13 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
     constexpr int LPR = 16, RPW = 4, RPB = RPW * NW, WG = NW * 64;
     constexpr size_t ROWB = 256;
     constexpr int U = 8;   // row loads in flight per lane (8 measured slightly better than 4; 2 is 8 % slower)
+    // Few streams (NW = 8, 512 lanes): one stream's step is a chain of memory round trips, so the first batch of
+    // every kind of row is requested before anything is consumed: 10 representative rows, 8 sampled pairs and 2
+    // window pairs per lane (320 + 256 + 64 rows per workgroup) are in flight together.
+    constexpr bool WIDE = NW == 8;
+    constexpr int UC = WIDE ? 10 : U;   // representative rows in flight per lane
+    constexpr int UW = WIDE ? 2 : U;    // window pairs of the hoisted first batch
+    constexpr int kAccWords = 256;      // accepted-slot mask of the hoisted variant: sample budgets up to 8192
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, sub = lane >> 4;
 
@@ -149,12 +157,33 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
     //      count-weighted exp(<q, x_i>) for the softmax normaliser
     float b1 = INFINITY, b2 = INFINITY, nxmax = 0.f;
     int i1 = -1;
+    // (key, value) row pairs: request a batch into registers / consume it (sampled pairs and window)
+    const float *const svn_base = st.svn + sid * (size_t)st.sS;
+    const int fill = (int)(n_after < st.w ? n_after : st.w);
+    const bool hoist_s = WIDE && ATT && n_evicted_after > 0 && st.s <= 32 * kAccWords;
+    auto pair_issue = [&](const char *Kb, const char *Vb, const float *vnorm, const int nrows, const int r0, auto &rk,
+                          auto &rv, auto &vnj) __attribute__((always_inline)) {
+        constexpr int N = (int)(sizeof(rk) / sizeof(rk[0]));
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int r = r0 + u * RPB + sub;
+            const int rr = r < nrows ? r : nrows - 1;
+            rk[u] = ldnt16(Kb + (size_t)rr * ROWB + col * 16);
+            rv[u] = ldnt16(Vb + (size_t)rr * ROWB + col * 16);
+            vnj[u] = vnorm != nullptr ? vnorm[rr] : 1.f;
+        }
+    };
+    uint4 hsk[WIDE ? U : 1], hsv[WIDE ? U : 1], hwk[WIDE ? UW : 1], hwv[WIDE ? UW : 1];
+    float hsn[WIDE ? U : 1], hwn[WIDE ? UW : 1];
+    if constexpr (WIDE && UPD) {
+        for (int i = tid; i < kAccWords; i += WG) sm.accm[i] = 0u;   // (visible behind the barriers of the update)
+    }
     {
-        uint4 raw[U];
-        float nx[U], cf[U];
+        uint4 raw[UC];
+        float nx[UC], cf[UC];
         auto issue = [&](const int r0) __attribute__((always_inline)) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
+            for (int u = 0; u < UC; ++u) {
                 const int r = r0 + u * RPB + sub;
                 const int rr = r < m ? r : m - 1;
                 raw[u] = ldnt16(X + (size_t)rr * ROWB + col * 16);
@@ -165,10 +194,14 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
         const bool need = ATT || evict;   // an update without an evicted token has nothing to look up
         int r0 = wave * RPW;
         if (need && r0 < m) issue(r0);
+        if constexpr (WIDE && ATT) {
+            if (hoist_s) pair_issue(Ks, Vs, svn_base, st.s, wave * RPW, hsk, hsv, hsn);
+            if (fill > 0) pair_issue(Kw, Vw, (const float *)nullptr, fill, wave * RPW, hwk, hwv, hwn);
+        }
         take_evicted();
-        for (; need && r0 < m; r0 += RPB * U) {
+        for (; need && r0 < m; r0 += RPB * UC) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
+            for (int u = 0; u < UC; ++u) {
                 const int r = r0 + u * RPB + sub;
                 const bool valid = r < m;
                 if constexpr (ATT) {
@@ -198,7 +231,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                     }
                 }
             }
-            if (r0 + RPB * U < m) issue(r0 + RPB * U);
+            if (r0 + RPB * UC < m) issue(r0 + RPB * UC);
         }
     }
 
@@ -298,6 +331,9 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                             }
                             st.sidx[sid * (size_t)st.sS + j] = (int32_t)etoken;
                             st.svn[sid * (size_t)st.sS + j] = vn;
+                            if constexpr (WIDE) {
+                                if (j < 32 * kAccWords) atomicOr(&sm.accm[j >> 5], 1u << (j & 31));
+                            }
                             // the other lanes read these rows after the barrier below: wait for the stores here,
                             // in the rare lane that made them, rather than in a full barrier for everybody
                             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -312,52 +348,81 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
 
     if constexpr (ATT) {
         // rows with values: sampled pairs (importance weights, numerator only), then the window (weight 1, both)
-        auto scan = [&](const char *Kb, const char *Vb, const float *vnorm, const float wmul, const int nrows,
-                        const bool to_den, const int lds_row) __attribute__((always_inline)) {
-            for (int r0 = wave * RPW; r0 < nrows; r0 += RPB * U) {
-                uint4 rk[U], rv[U];
-                float vnj[U];
+        // kind 1 = sampled pairs: a slot that took the evicted token in this very step may have been requested
+        // before that store (hoisted batch): its rows are then taken from LDS; kind 2 = window: the new token's
+        // rows are not in the ring yet, they come from LDS as well
+        auto pair_process = [&](const int kind, const float wmul, const int nrows, const int r0, const auto &rk,
+                                const auto &rv, const auto &vnj) __attribute__((always_inline)) {
+            constexpr int N = (int)(sizeof(rk) / sizeof(rk[0]));
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int r = r0 + u * RPB + sub;
-                    const int rr = r < nrows ? r : nrows - 1;
-                    rk[u] = ldnt16(Kb + (size_t)rr * ROWB + col * 16);
-                    rv[u] = ldnt16(Vb + (size_t)rr * ROWB + col * 16);
-                    vnj[u] = vnorm != nullptr ? vnorm[rr] : 1.f;
-                    if (rr == lds_row) {   // the new token's rows are not in the ring yet
-                        rk[u] = sm.nkrow[col];
-                        rv[u] = sm.nvrow[col];
+            for (int u = 0; u < N; ++u) {
+                const int r = r0 + u * RPB + sub;
+                const bool valid = r < nrows;
+                const int rr = valid ? r : nrows - 1;
+                uint4 k8 = rk[u], v8 = rv[u];
+                float vnr = vnj[u];
+                if (kind == 2) {
+                    if (rr == wslot) {
+                        k8 = sm.nkrow[col];
+                        v8 = sm.nvrow[col];
+                    }
+                } else if constexpr (WIDE && UPD) {
+                    if (rr < 32 * kAccWords && ((sm.accm[rr >> 5] >> (rr & 31)) & 1u)) {
+                        k8 = sm.ekrow[col];
+                        v8 = sm.evrow[col];
+                        vnr = vn;
                     }
                 }
+                const float b = row_sum16(dot8_bf16(k8, qp));
+                float e = 0.f;
+                if (valid) {
+                    if (b > mx + kLazy || mx == -INFINITY) {
+                        const float sc = __expf(mx - b);   // mx = -inf gives 0
+                        den *= sc;
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const bool valid = r0 + u * RPB + sub < nrows;
-                    const float b = row_sum16(dot8_bf16(rk[u], qp));
-                    float e = 0.f;
-                    if (valid) {
-                        if (b > mx + kLazy || mx == -INFINITY) {
-                            const float sc = __expf(mx - b);   // mx = -inf gives 0
-                            den *= sc;
-#pragma unroll
-                            for (int i = 0; i < 8; ++i) acc[i] *= sc;
-                            mx = b;
-                        }
-                        const float wgt = vnorm != nullptr ? (vnj[u] > 0.f ? wmul * __builtin_amdgcn_rcpf(vnj[u]) : 0.f)
-                                                           : 1.f;
-                        e = wgt * __expf(b - mx);
-                        if (to_den) den += e;
+                        for (int i = 0; i < 8; ++i) acc[i] *= sc;
+                        mx = b;
                     }
-                    float vf[8];
-                    unpack<true>(rv[u], vf);
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) acc[i] = fmaf(e, vf[i], acc[i]);
+                    const float wgt = kind == 1 ? (vnr > 0.f ? wmul * __builtin_amdgcn_rcpf(vnr) : 0.f) : 1.f;
+                    e = wgt * __expf(b - mx);
+                    if (kind == 2) den += e;
                 }
+                float vf[8];
+                unpack<true>(v8, vf);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = fmaf(e, vf[i], acc[i]);
             }
         };
-        if (n_evicted_after > 0)
-            scan(Ks, Vs, st.svn + sid * (size_t)st.sS, (float)(mu / (double)st.s), st.s, false, -1);
-        const int fill = (int)(n_after < st.w ? n_after : st.w);
-        scan(Kw, Vw, nullptr, 1.f, fill, true, wslot);
+        auto scan = [&](const int kind, const char *Kb, const char *Vb, const float *vnorm, const float wmul,
+                        const int nrows, const int rstart) __attribute__((always_inline)) {
+            for (int r0 = rstart; r0 < nrows; r0 += RPB * U) {
+                uint4 rk[U], rv[U];
+                float vnj[U];
+                pair_issue(Kb, Vb, vnorm, nrows, r0, rk, rv, vnj);
+                pair_process(kind, wmul, nrows, r0, rk, rv, vnj);
+            }
+        };
+        const float mus = (float)(mu / (double)st.s);
+        if (n_evicted_after > 0) {
+            int rstart = wave * RPW;
+            if constexpr (WIDE) {
+                if (hoist_s) {
+                    pair_process(1, mus, st.s, rstart, hsk, hsv, hsn);
+                    rstart += RPB * U;
+                }
+            }
+            scan(1, Ks, Vs, svn_base, mus, st.s, rstart);
+        }
+        {
+            int rstart = wave * RPW;
+            if constexpr (WIDE) {
+                if (fill > 0) {
+                    pair_process(2, 1.f, fill, rstart, hwk, hwv, hwn);
+                    rstart += RPB * UW;
+                }
+            }
+            scan(2, Kw, Vw, nullptr, 1.f, fill, rstart);
+        }
 
         if (extra && wave == 0 && sub == 0) {
             const float a = row_sum16(dot8_bf16(xr, qp));
@@ -421,8 +486,8 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
     }
 }
 
-// NW wavefronts per workgroup: 4 when there are streams enough to fill the chip; 16 for a few streams, where one
-// stream's rows in flight (1024 lanes x 8 loads) are what bounds the step
+// NW wavefronts per workgroup: 4 when there are streams enough to fill the chip; 8 for a few streams, where the
+// step of one stream is a chain of memory round trips and the first batch of every kind of row is requested at once
 template <bool UPD, bool ATT, int NW>
 __global__ __launch_bounds__(NW * 64) void decode_dot2_kernel(const State st, const Call call)
 {
