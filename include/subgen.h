@@ -78,7 +78,7 @@ typedef struct subgen_opts {
                                1 = always the generic vector-ALU kernels (any dtype; same results up to fp32
                                rounding of the outputs, identical decisions);
                                2 = as 0, but never the wide-workgroup kernels that 0 picks for contexts of at
-                               most 128 streams (the kernels of large contexts on a small one: for tests)     */
+                               most 256 streams (the kernels of large contexts on a small one: for tests)     */
     int32_t t_per_cluster;  /* t: reservoir slots per cluster.  0 (default) = representative mode: the normaliser is
                                sum_i n_i e^{<q,x_i>}.  t >= 1 = Algorithm 1 as printed: every cluster keeps t uniform
                                samples S_i of its keys and the normaliser is sum_i (n_i/t) sum_{k in S_i} e^{<q,k>}

@@ -354,7 +354,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     c->stream = reinterpret_cast<hipStream_t>(o.hip_stream);
     c->mfma = o.kernel_path != 1 && o.t_per_cluster == 0 && mfma_supported(o.dtype, c->LPR, G);
     c->ingest_mfma = o.kernel_path != 1 && o.dtype == SUBGEN_BF16 && (c->LPR == 8 || c->LPR == 16);
-    c->wide = o.kernel_path == 0 && streams <= 128;
+    c->wide = o.kernel_path == 0 && streams <= 256;   // measured crossover between 256 and 512 streams
     c->dev_seen = o.device_counter != 0;
 
     State &st = c->st;
