@@ -76,3 +76,46 @@ def test_cfg3_full_size_sampled_streams():
         assert np.array_equal(np.bincount(e.assign, minlength=e.m), e.counts)
     print(f"cfg3 full size: delta={delta:.4f} mean m={st.total_centers / S:.1f} sampled streams {ids} "
           f"max rel-L2={err.max():.2e}")
+
+
+def test_cfg5_all_streams_sampled_against_the_oracle():
+    """The GQA workload with all of its 8192 KV streams x 4 queries in one launch (the tile kernels in the launch
+    configuration bench.py times); the prefix is cut to 8192 tokens so that the oracle finishes in seconds."""
+    from paper_2402_06082_amd import binding
+    cfg = CONFIGS["cfg5"]
+    prefix, steps, delta = 8192, 12, 8.5234375
+    wl = Workload(cfg, device=DEV)
+    S = wl.S
+    ids = sampled_streams(cfg)
+    sg = binding.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=cfg.g, max_centers=2048,
+                        assign_log_tokens=prefix + steps, seed=0, device=DEV)
+    hostK, hostV = [], []
+    for t0 in range(0, prefix, 4 * BLOCK):
+        K, V = wl.tokens(t0, t0 + 4 * BLOCK)
+        sg.ingest_prefix(K, V)
+        hostK.append(to_f32_np(K[ids]))
+        hostV.append(to_f32_np(V[ids]))
+        del K, V
+    hostK, hostV = np.concatenate(hostK, 1), np.concatenate(hostV, 1)
+    oracles = make_oracles(S, cfg.d, delta, cfg.s, cfg.w, seed=0, stream_ids=ids)
+    with ThreadPoolExecutor(8) as ex:
+        list(ex.map(lambda a: a[0].ingest(a[1], a[2]), zip(oracles, hostK, hostV)))
+    assert compare_state(sg, oracles, ids) == 0
+    K, V = wl.tokens(prefix, prefix + steps)
+    Q = wl.queries(0, steps)
+    outs = torch.empty(steps, S, cfg.g, cfg.d, dtype=torch.float32, device=DEV)
+    for t in range(steps):
+        sg.step(K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous(), outs[t])
+    many = sg.attend_many(Q[:, steps - 1].contiguous())          # the same queries once more, as a block
+    sg.sync()
+    Kc, Vc, Qc = to_f32_np(K[ids]), to_f32_np(V[ids]), to_f32_np(Q[ids])
+    ref = np.stack([o.decode(k, v, q) for o, k, v, q in zip(oracles, Kc, Vc, Qc)], axis=1)
+    got = outs.cpu().numpy()
+    assert np.isfinite(got).all()
+    err = rel_l2(got[:, ids], ref)
+    assert err.max() <= REL_L2_TOL, err.max()
+    assert rel_l2(many.cpu().numpy()[ids], ref[steps - 1]).max() <= REL_L2_TOL
+    assert compare_state(sg, oracles, ids) == 0
+    st = sg.stats()
+    assert st.flags_or == 0 and st.n_seen == prefix + steps
+    print(f"cfg5 all streams: mean m={st.total_centers / S:.1f} max rel-L2={err.max():.2e}")
