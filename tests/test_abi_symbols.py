@@ -37,3 +37,42 @@ def test_binding_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(binding.subgen_opts) == 64
     assert ctypes.sizeof(binding.subgen_stats_t) == 56
     assert ctypes.sizeof(binding.subgen_state_view) == 144
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    """Everything subgen_create rejects is rejected before the first HIP call, so the checks run anywhere; the
+    pure host helpers (error strings, workspace sizes) answer without a device as well."""
+    import ctypes as C
+    import torch
+    from paper_2402_06082_amd import binding
+    L = binding.load()
+    h = C.c_void_p()
+
+    def create(streams=2, d=128, delta=1.0, s=4, w=2, **kw):
+        o = binding.subgen_opts()
+        o.struct_size = C.sizeof(binding.subgen_opts)
+        o.dtype = 1
+        for k, v in kw.items():
+            setattr(o, k, v)
+        return L.subgen_create(C.byref(h), streams, d, C.c_float(delta), s, w, C.byref(o))
+
+    bad = [dict(streams=0), dict(d=100), dict(d=0), dict(delta=-1.0), dict(delta=float("nan")), dict(delta=float("inf")),
+           dict(s=0), dict(w=-1), dict(q_per_stream=3), dict(dtype=7), dict(kernel_path=3), dict(t_per_cluster=65),
+           dict(t_per_cluster=-1), dict(max_centers=-5), dict(assign_log_tokens=-1), dict(device_counter=2),
+           dict(struct_size=2), dict(struct_size=1000)]
+    for kw in bad:
+        assert create(**kw) == -1, kw
+        assert not h.value
+    assert L.subgen_create(None, 2, 128, C.c_float(1.0), 4, 2, None) == -1
+    if not torch.cuda.is_available():
+        assert create() in (-2, -3)          # valid arguments, no device: an error code, not a crash
+        assert not h.value
+    for code, text in [(0, "ok"), (-1, "invalid argument"), (-2, "out of memory"), (-4, "attend before any token")]:
+        assert binding.strerror(code) == text
+    assert L.subgen_exact_workspace_bytes(0, 16, 128, 1) == 0 and L.subgen_exact_workspace_bytes(4, 4096, 128, 2) > 0
+    assert L.subgen_kcenter_workspace_bytes(0, 16, 4) == 0 and L.subgen_kcenter_workspace_bytes(4, 4096, 64) > 0
+    for f in (L.subgen_update, ):
+        assert f(None, None, None) == -1
+    assert L.subgen_attend(None, None, None) == -1 and L.subgen_sync(None) == -1
+    assert L.subgen_attend_many(None, None, 4, None) == -1
+    L.subgen_destroy(None)                   # a null context is ignored
