@@ -126,7 +126,7 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
         };
         prefetch(0);
         for (int r0 = 0; r0 < nrows; r0 += kSuper) {
-            __syncthreads();   // the previous tiles have been consumed
+            lds_barrier();   // the previous tiles have been consumed (prefetched rows stay in flight)
 #pragma unroll
             for (int i = 0; i < LD; ++i) {
                 const int idx = tid + kWG * i, row = idx / CPR, ch = idx % CPR;
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
                 }
                 sm.wrow[tid] = wv;
             }
-            __syncthreads();
+            lds_barrier();
             if (r0 + kSuper < nrows) prefetch(r0 + kSuper);   // in flight while the matrix cores work
 
 #pragma unroll
