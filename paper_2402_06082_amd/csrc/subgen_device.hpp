@@ -140,6 +140,27 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// all-reduce over the 16 lanes of a DPP row (row rotations by 8, 4, 2, 1)
+template <int N>
+__device__ __forceinline__ float row_ror(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf,
+                                                                 false));
+}
+template <int N>
+__device__ __forceinline__ int row_ror(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, 0x120 + N, 0xf, 0xf, false);
+}
+__device__ __forceinline__ float row_sum16(float v)
+{
+    v += row_ror<8>(v);
+    v += row_ror<4>(v);
+    v += row_ror<2>(v);
+    v += row_ror<1>(v);
+    return v;
+}
+
 // online-softmax partial of one row group for one query
 template <int VEC>
 struct Partial {

@@ -29,22 +29,6 @@ __device__ __forceinline__ float dot8_bf16(const uint4 &x, const uint4 &y)
     return dot2_bf16(x.w, y.w, s);
 }
 
-// all-reduce over the 16 lanes of a DPP row (row rotations by 8, 4, 2, 1)
-template <int N>
-__device__ __forceinline__ float row_ror(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf,
-                                                                 false));
-}
-__device__ __forceinline__ float row_sum16(float v)
-{
-    v += row_ror<8>(v);
-    v += row_ror<4>(v);
-    v += row_ror<2>(v);
-    v += row_ror<1>(v);
-    return v;
-}
-
 template <int NW>
 struct SmemDot2 {
     alignas(16) uint4 ekrow[16], evrow[16];   // the evicted (key, value) rows, for the sampling copies

@@ -368,12 +368,10 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
     };
     if constexpr (UPD) {
         if (evict) {
-            // ---- best / runner-up of the approximate distances: over the lanes (the other columns hold +inf),
-            //      then the wavefronts
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const float ob1 = __shfl_xor(b1, o), ob2 = __shfl_xor(b2, o);
-                const int oi1 = __shfl_xor(i1, o);
+            // ---- best / runner-up of the approximate distances: over the lanes (the other columns hold +inf):
+            //      the 16 lanes of a DPP row by rotations, then the four rows; then the wavefronts
+            auto merge = [&](const float ob1, const float ob2, const int oi1, const float onx)
+                             __attribute__((always_inline)) {
                 if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
                     b2 = fminf(b1, ob2);
                     b1 = ob1;
@@ -381,8 +379,15 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
                 } else {
                     b2 = fminf(b2, ob1);
                 }
-                nxmax = fmaxf(nxmax, __shfl_xor(nxmax, o));
-            }
+                nxmax = fmaxf(nxmax, onx);
+            };
+            merge(row_ror<8>(b1), row_ror<8>(b2), row_ror<8>(i1), row_ror<8>(nxmax));
+            merge(row_ror<4>(b1), row_ror<4>(b2), row_ror<4>(i1), row_ror<4>(nxmax));
+            merge(row_ror<2>(b1), row_ror<2>(b2), row_ror<2>(i1), row_ror<2>(nxmax));
+            merge(row_ror<1>(b1), row_ror<1>(b2), row_ror<1>(i1), row_ror<1>(nxmax));
+#pragma unroll
+            for (int o = 16; o < 64; o <<= 1)
+                merge(__shfl_xor(b1, o), __shfl_xor(b2, o), __shfl_xor(i1, o), __shfl_xor(nxmax, o));
             if (lane == 0) {
                 sm.wb1[wave] = b1;
                 sm.wb2[wave] = b2;
