@@ -39,6 +39,7 @@ struct SmemTile {
     alignas(16) float wrow[kSuper];           // weight of each staged row
     alignas(16) float xnrow[kSuper];          // ||x_i||^2 of each staged representative (update)
     alignas(16) uint4 ekrow[NK * 4], evrow[NK * 4];   // the evicted (key, value) rows, for the sampling copies
+    alignas(16) uint4 qrow[G][NK * 4];                // the queries in plain row layout (extra normaliser term)
     float wb1[kWaves], wb2[kWaves], wnx[kWaves];
     int wi1[kWaves];
     double wbest[kWaves];
@@ -95,6 +96,9 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
     if (qcol) {
 #pragma unroll
         for (int kk = 0; kk < NK; ++kk) Bq[kk] = ld16(qrows + (size_t)n16 * ROWB + (L + 4 * kk) * 16);
+    }
+    if constexpr (UPD) {
+        if (tid < G * LPR) sm.qrow[tid / LPR][tid % LPR] = ld16(qrows + (size_t)tid * 16);   // read after many barriers
     }
 
     // The stored rows come in three sections: 0 = representatives (weight n_i, normaliser only; distances for
@@ -347,9 +351,7 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
 
     bool extra = false, decided = false, d_created = false, d_forced = false;
     int d_target = 0;
-    uint4 xg = make_uint4(0, 0, 0, 0), qg[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) qg[g] = make_uint4(0, 0, 0, 0);
+    uint4 xg = make_uint4(0, 0, 0, 0);
     auto finish_extra = [&]() {
         if (extra && grp == 0) {
             float xf[8];
@@ -357,7 +359,7 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 float qf[8];
-                unpack<true>(qg[g], qf);
+                unpack<true>(sm.qrow[g][col], qf);
                 float a = 0.f;
 #pragma unroll
                 for (int v = 0; v < 8; ++v) a = fmaf(qf[v], xf[v], a);
@@ -432,14 +434,12 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
             d_created = created;
             d_forced = forced;
             d_target = target;
-            // score of the cluster that gained this token, one more term of the normaliser: its row and the
-            // queries are only requested here; the products wait until the loads have landed (after the
-            // next full barrier), so no wavefront sits out their latency
+            // score of the cluster that gained this token, one more term of the normaliser: its row is only
+            // requested here (the queries sit in LDS); the products wait until the load has landed (after the
+            // next full barrier), so no wavefront sits out its latency
             if (grp == 0) {
                 xg = ek;
                 if (!created) xg = ld16(X + (size_t)target * ROWB + col * 16);
-#pragma unroll
-                for (int g = 0; g < G; ++g) qg[g] = ld16(qrows + (size_t)g * ROWB + col * 16);
             }
             extra = true;
             if (created) m += 1;
