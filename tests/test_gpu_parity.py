@@ -484,8 +484,9 @@ def test_matrix_core_path_exact_decisions_on_lattice_keys(g):
         assert np.array_equal(ing.export_state(sid).assign, sg.export_state(sid).assign)
 
 
+@pytest.mark.parametrize("device_counter", [False, True])
 @pytest.mark.parametrize("cfgname,g", [("cfg2", 1), ("cfg5", 4), ("cfg1b", 1)])
-def test_export_import_resumes_bit_identically(cfgname, g):
+def test_export_import_resumes_bit_identically(cfgname, g, device_counter):
     """Checkpoint / resume: a context restored from exported state continues exactly like the original
     (the coins are counter-based, so there is no generator state to carry)."""
     b = binding()
@@ -495,8 +496,9 @@ def test_export_import_resumes_bit_identically(cfgname, g):
     delta = cfg.delta or 8.3
     K, V = wl.tokens(0, 700)
     Q = wl.queries(0, 700)
-    mk = lambda: b.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=g, seed=9, device=DEV)
-    a, c = mk(), mk()
+    mk = lambda dc: b.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=g, seed=9, device=DEV,
+                             device_counter=dc)
+    a, c = mk(False), mk(device_counter)     # the restored context may keep its token count on the device
     a.ingest_prefix(K[:, :600], V[:, :600])
     for sid in range(S):
         c.import_raw(sid, a.export_raw(sid))
@@ -504,6 +506,8 @@ def test_export_import_resumes_bit_identically(cfgname, g):
     for t in range(600, 700):
         kt, vt, qt = K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()
         assert torch.equal(a.step(kt, vt, qt), c.step(kt, vt, qt)), t
+    qm = Q[:, 699].repeat(1, 3, 1)[:, :5].contiguous()          # a block of five queries: attend_many reads the same count
+    assert torch.equal(a.attend_many(qm), c.attend_many(qm))
     for sid in range(S):
         assert state_tuple(a, sid) == state_tuple(c, sid)
     # a second import must agree on the shared token counter
