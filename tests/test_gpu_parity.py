@@ -413,6 +413,34 @@ def test_captured_step_replays_like_eager_steps(dtype, d, g, streams):
     assert sg.export_state(0, rows=False).n_seen == n
 
 
+def test_contexts_are_independent_and_release_their_memory():
+    """Two contexts alive at once do not disturb each other; creating and destroying contexts returns the device
+    memory (subgen_destroy frees what subgen_create allocated)."""
+    b = binding()
+    gen = torch.Generator(device="cpu").manual_seed(3)
+    S, d, n = 4, 128, 90
+    K = (torch.randn(S, n, d, generator=gen) * 0.5 + torch.randn(S, 1, d, generator=gen) * 2).to(torch.bfloat16).to(DEV)
+    V = torch.randn(S, n, d, generator=gen).to(torch.bfloat16).to(DEV)
+    Q = (torch.randn(S, n, 1, d, generator=gen) / d ** 0.5).to(torch.bfloat16).to(DEV)
+    mk = lambda seed: b.SubGen(S, d, 6.0, 16, 8, dtype=torch.bfloat16, seed=seed, device=DEV)
+    a, c, solo = mk(1), mk(2), mk(1)
+    for t in range(n):                       # a and c interleaved, solo alone: a must equal solo bit for bit
+        kt, vt, qt = K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()
+        oa = a.step(kt, vt, qt)
+        c.step(vt, kt, qt)                   # another stream of tokens in between
+        assert torch.equal(oa, solo.step(kt, vt, qt)), t
+    assert all(state_tuple(a, i) == state_tuple(solo, i) for i in range(S))
+    del a, c, solo
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info(DEV)[0]
+    for _ in range(40):
+        x = b.SubGen(64, d, 6.0, 256, 64, dtype=torch.bfloat16, max_centers=1024, device=DEV)
+        x.ingest_prefix(K[:, :8].repeat(16, 1, 1), V[:, :8].repeat(16, 1, 1))
+        x.close()
+    torch.cuda.synchronize()
+    assert abs(torch.cuda.mem_get_info(DEV)[0] - free0) < (64 << 20)      # no growth beyond allocator slack
+
+
 def test_error_codes():
     b = binding()
     sg = b.SubGen(2, 128, 1.0, 4, 2, dtype=torch.bfloat16, device=DEV)
