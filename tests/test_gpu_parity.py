@@ -477,13 +477,13 @@ def test_exact_attend_against_textbook_attention(dtype, d, g, n):
     assert rel_l2(out, ref).max() <= 1e-4
 
 
-@pytest.mark.parametrize("g", [1, 2, 4])
-def test_matrix_core_path_exact_decisions_on_lattice_keys(g):
+@pytest.mark.parametrize("g,d,kernel_path", [(1, 128, 0), (1, 128, 2), (2, 128, 0), (4, 128, 0), (2, 64, 0), (1, 256, 0)])
+def test_matrix_core_path_exact_decisions_on_lattice_keys(g, d, kernel_path):
     """Keys on a coarse lattice: many representatives at exactly equal distance and many distances exactly
     at the threshold, so the approximate distances of the matrix-core path are ambiguous all the time and the
     exact re-evaluation (lowest index on ties, inclusive threshold) decides."""
     b = binding()
-    d, S, n, s, w = 128, 4, 400, 16, 5
+    S, n, s, w = 4, 400, 16, 5
     gen = torch.Generator(device="cpu").manual_seed(77 + g)
     K = torch.randint(-1, 2, (S, n, d), generator=gen).float() * 0.5       # coordinates in {-0.5, 0, 0.5}
     K[:, :, 8:] = 0.0                                                      # only 8 active coordinates
@@ -491,7 +491,8 @@ def test_matrix_core_path_exact_decisions_on_lattice_keys(g):
     Q = torch.randn(S, n, g, d, generator=gen) / d ** 0.5
     K, V, Q = (t.to(torch.bfloat16).to(DEV) for t in (K, V, Q))
     delta = 1.0                                                            # distances are sqrt(j)/2: 1.0 is hit exactly
-    sg = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, q_per_stream=g, assign_log_tokens=n, seed=2, device=DEV)
+    sg = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, q_per_stream=g, assign_log_tokens=n, seed=2, device=DEV,
+                  kernel_path=kernel_path)
     oracles = make_oracles(S, d, delta, s, w, seed=2)
     outs = torch.stack([sg.step(K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()) for t in range(n)])
     ref = np.stack([o.decode(to_f32_np(K[i]), to_f32_np(V[i]), to_f32_np(Q[i])) for i, o in enumerate(oracles)], 1)
@@ -504,7 +505,8 @@ def test_matrix_core_path_exact_decisions_on_lattice_keys(g):
         assert (thr == 0).sum() > 5 and (gap == 0).sum() > 5
     assert rel_l2(outs.cpu().numpy(), ref).max() <= REL_L2_TOL
     # the chunked prefix ingest takes the same decisions on the same data (ragged chunks)
-    ing = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, q_per_stream=g, assign_log_tokens=n, seed=2, device=DEV)
+    ing = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, q_per_stream=g, assign_log_tokens=n, seed=2, device=DEV,
+                   kernel_path=kernel_path)
     for lo, hi in [(0, 3), (3, 70), (70, 71), (71, 333), (333, n)]:
         ing.ingest_prefix(K[:, lo:hi], V[:, lo:hi])
     for sid in range(S):
