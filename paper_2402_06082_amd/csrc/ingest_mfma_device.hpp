@@ -14,8 +14,12 @@
 //      iterations per chunk once the table has filled;
 //   4. ambiguous decisions (gap or threshold distance within the error bound
 //      of the matrix-core distances) are re-evaluated exactly in double;
-//   5. the sampling coins of the 64 tokens are drawn per 4-slot block, the
-//      last accepting token of a slot wins (sequential overwrite semantics).
+//   5. the sampling coins do not depend on the clustering: the chunks only
+//      leave each token's probability behind, and once per 1024 evicted
+//      tokens (or at the end of the call) one pass draws the coins per 4-slot
+//      block, newest token first; the last accepting token of a slot wins
+//      (sequential overwrite semantics), so a slot is copied at most once
+//      per pass and a lane stops as soon as its four slots are taken.
 // The window is handled by index arithmetic: the tokens that leave the window
 // during the call come first from the ring, then from the call's own input;
 // the ring is rewritten once at the end.
@@ -25,11 +29,14 @@
 namespace sg {
 
 constexpr int kChunkT = 64;  // tokens per chunk = one lane per token in the resolve loop
+constexpr int kCoinSpan = 1024;  // evicted tokens per coin pass (a multiple of the chunk)
 
 template <int NK>
 struct SmemIngest {
     alignas(16) float nk[kChunkT];
-    float vn[kChunkT], p[kChunkT];
+    float vn[kChunkT];
+    // coin probability and ||v||^2 of the evicted tokens whose coins are still to be drawn (up to kCoinSpan)
+    float pall[kCoinSpan], vnall[kCoinSpan];
     float wb1[kWaves][kChunkT], wb2[kWaves][kChunkT];
     int wi1[kWaves][kChunkT];
     float wnx[kWaves];
@@ -41,6 +48,10 @@ struct SmemIngest {
     int tgt[kChunkT];
     float pr[kChunkT];
     uint8_t win[kChunkT][16];
+    // the chunk's keys, one padded row per token (the pad spreads the 16 rows an operand read touches over
+    // all banks): the B operands of every contraction of the chunk are read from here
+    static constexpr int KS = NK * 64 + 16;
+    alignas(16) char kt[kChunkT * KS];
 };
 
 // merge candidate (d, idx) into best / runner-up; lower index wins exact ties of the approximate value
@@ -63,6 +74,8 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
     constexpr int CPR = 4 * NK, LPR = CPR;
     constexpr int RPW = 64 / LPR, RPB = RPW * kWaves;
     constexpr size_t ROWB = (size_t)NK * 64;
+    constexpr int KS = SmemIngest<NK>::KS;
+    constexpr int PF = 2;   // groups of 16 representatives in flight per wavefront (a third one spills)
     __shared__ SmemIngest<NK> sm;
 
     const size_t sid = blockIdx.x;
@@ -85,20 +98,95 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
     const int64_t ge0 = w == 0 ? n0 : (n0 > w ? n0 - w : 0);
     int64_t ge1 = w == 0 ? n0 + n : n0 + n - w;
     if (ge1 < ge0) ge1 = ge0;
+    // ring slot of token ge0 + i (i < w): one 64-bit remainder per kernel, 32-bit arithmetic per row afterwards
+    const uint32_t slot0 = w > 0 ? (uint32_t)(ge0 % w) : 0u;
+    auto ring_slot = [&](int64_t ge) -> uint32_t {
+        const uint32_t sl = slot0 + (uint32_t)(ge - ge0);
+        return sl >= (uint32_t)w ? sl - (uint32_t)w : sl;
+    };
     auto krow_of = [&](int64_t ge) -> const char * {
-        return ge < n0 ? Kw + (size_t)(ge % w) * ROWB : kin + (ge - n0) * call.token_stride;
+        return ge < n0 ? Kw + (size_t)ring_slot(ge) * ROWB : kin + (ge - n0) * call.token_stride;
     };
     auto vrow_of = [&](int64_t ge) -> const char * {
-        return ge < n0 ? Vw + (size_t)(ge % w) * ROWB : vin + (ge - n0) * call.token_stride;
+        return ge < n0 ? Vw + (size_t)ring_slot(ge) * ROWB : vin + (ge - n0) * call.token_stride;
     };
 
     int m = st.m[sid];
     double mu = st.mu[sid];
     const float thr = (float)st.delta2;
 
+    // ---- coin pass over the evicted tokens [g0, g0 + cnt) whose probabilities are in LDS: every lane takes one
+    //      4-slot block (and one sub-range of the tokens, so that all lanes have coins to draw) and walks its
+    //      tokens from the newest to the oldest; the first accept it meets per slot is the one that stays
+    auto coin_pass = [&](int64_t g0, int cnt) {
+        const int nblk = (st.s + 3) >> 2;
+        int nsplit = 1;
+        while (nsplit < 16 && nblk * nsplit * 2 <= kWG) nsplit *= 2;
+        const int per = kCoinSpan / nsplit;
+        for (int item = tid; item < ((nblk * nsplit + kWG - 1) / kWG) * kWG; item += kWG) {
+            const int blk = item / nsplit, part = item % nsplit;
+            int last[4] = {-1, -1, -1, -1};
+            if (blk < nblk) {
+                const int lo = part * per, hi = (part + 1) * per < cnt ? (part + 1) * per : cnt;
+                for (int jj = hi - 1; jj >= lo; --jj) {
+                    const float pj = sm.pall[jj];
+                    if (pj > 0.f) {
+                        const uint64_t ge = (uint64_t)(g0 + jj);
+                        uint32_t r[4];
+                        philox4x32_10((uint32_t)blk, (uint32_t)ge, (uint32_t)(ge >> 32), (uint32_t)sid, st.seed_lo,
+                                      st.seed_hi, r);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (last[i] < 0 && (float)(r[i] >> 8) * (1.0f / 16777216.0f) < pj) last[i] = jj;
+                        if ((last[0] | last[1] | last[2] | last[3]) >= 0) break;
+                    }
+                }
+            }
+            // the largest token index over the sub-ranges wins
+            for (int o = 1; o < nsplit; o <<= 1) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) last[i] = max(last[i], __shfl_xor(last[i], o));
+            }
+            if (blk < nblk) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int slot = blk * 4 + i;
+                    const int owner = nsplit >= 4 ? i : (i % nsplit);   // spread the row copies over the lanes
+                    if (part == owner && last[i] >= 0 && slot < st.s) {
+                        const char *ks = krow_of(g0 + last[i]), *vs = vrow_of(g0 + last[i]);
+#pragma unroll
+                        for (int ch = 0; ch < CPR; ++ch) {
+                            st16(Ks + (size_t)slot * ROWB + ch * 16, ld16(ks + ch * 16));
+                            st16(Vs + (size_t)slot * ROWB + ch * 16, ld16(vs + ch * 16));
+                        }
+                        st.sidx[sid * (size_t)st.sS + slot] = (int32_t)(g0 + last[i]);
+                        st.svn[sid * (size_t)st.sS + slot] = sm.vnall[last[i]];
+                    }
+                }
+            }
+        }
+    };
+    int64_t span0 = ge0;   // first evicted token of the pending coin pass
+    int span_fill = 0;     // tokens whose probabilities wait in LDS
+
     for (int64_t c0 = ge0; c0 < ge1; c0 += T) {
         const int nt = (int)(ge1 - c0 < T ? ge1 - c0 : T);
         const int m0 = m;
+
+        // ---- the first groups of representatives are requested before anything else of the chunk
+        uint4 q[PF][NK];
+        float4 qn[PF];
+        auto request = [&](uint4(&dst)[NK], float4 &dn, int r) __attribute__((always_inline)) {
+            dn = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r < m0) {
+                const int rr = r + n16 < m0 ? r + n16 : m0 - 1;
+#pragma unroll
+                for (int kk = 0; kk < NK; ++kk) dst[kk] = ld16(X + (size_t)rr * ROWB + (L + 4 * kk) * 16);
+                dn = *reinterpret_cast<const float4 *>(xn + r + 4 * L);
+            }
+        };
+#pragma unroll
+        for (int pf = 0; pf < PF; ++pf) request(q[pf], qn[pf], (wave + kWaves * pf) * 16);
 
         // ---- squared norms of the chunk's keys and values (double, exact products), one token per lane group
         {
@@ -116,6 +204,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 float kf[8], vf[8];
                 unpack<true>(rk[it], kf);
                 unpack<true>(rv[it], vf);
+                *reinterpret_cast<uint4 *>(&sm.kt[(grp + it * RPB) * KS + col * 16]) = rk[it];
                 double a = 0.0, b = 0.0;
 #pragma unroll
                 for (int v = 0; v < 8; ++v) {
@@ -134,40 +223,32 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 }
             }
         }
-        // ---- the 64 keys as four B operands (token 16 ts + n in column n)
-        uint4 Bt[4][NK];
-#pragma unroll
-        for (int ts = 0; ts < 4; ++ts) {
-            const int j = 16 * ts + n16;
-            const char *kp = krow_of(c0 + (j < nt ? j : nt - 1));
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk) Bt[ts][kk] = ld16(kp + (L + 4 * kk) * 16);
-        }
+        // ---- B operand (ts, kk): token 16 ts + n in column n, read from the LDS tile
+        auto bop = [&](int ts, int kk) __attribute__((always_inline)) {
+            return *reinterpret_cast<const uint4 *>(&sm.kt[(16 * ts + n16) * KS + (L + 4 * kk) * 16]);
+        };
         __syncthreads();
         float nkt[4];
 #pragma unroll
         for (int ts = 0; ts < 4; ++ts) nkt[ts] = sm.nk[16 * ts + n16];
 
         // ---- token-token distances: wavefront `wave` takes rows 16 wave .. 16 wave + 15 (its A operand is
-        //      B set `wave`; the branch keeps the register indices static)
+        //      B set `wave`)
         {
             const float4 nkr = *reinterpret_cast<const float4 *>(&sm.nk[16 * wave + 4 * L]);
             const float nkrow[4] = {nkr.x, nkr.y, nkr.z, nkr.w};
-            auto tt_rows = [&](const uint4(&arow)[NK]) {
+            uint4 arow[NK];
 #pragma unroll
-                for (int ts = 0; ts < 4; ++ts) {
-                    floatx4_t c = {0.f, 0.f, 0.f, 0.f};
+            for (int kk = 0; kk < NK; ++kk) arow[kk] = bop(wave, kk);
 #pragma unroll
-                    for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(arow[kk], Bt[ts][kk], c);
+            for (int ts = 0; ts < 4; ++ts) {
+                floatx4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        sm.tt[16 * wave + 4 * L + r][16 * ts + n16] = fmaf(-2.f, c[r], nkrow[r] + nkt[ts]);
-                }
-            };
-            if (wave == 0) tt_rows(Bt[0]);
-            else if (wave == 1) tt_rows(Bt[1]);
-            else if (wave == 2) tt_rows(Bt[2]);
-            else tt_rows(Bt[3]);
+                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(arow[kk], bop(ts, kk), c);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    sm.tt[16 * wave + 4 * L + r][16 * ts + n16] = fmaf(-2.f, c[r], nkrow[r] + nkt[ts]);
+            }
         }
 
         // ---- distances to the representatives that exist at the start of the chunk
@@ -179,57 +260,51 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             b2[ts] = INFINITY;
             i1[ts] = -1;
         }
-        {
+        for (int r0 = wave * 16; r0 < m0; r0 += 16 * kWaves) {
+            // the oldest request is this group; the queue moves up and takes one more request at its end
             uint4 a[NK];
-            float4 nx4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            int r0 = wave * 16;
-            if (r0 < m0) {
-                const int rr = r0 + n16 < m0 ? r0 + n16 : m0 - 1;
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) a[kk] = ld16(X + (size_t)rr * ROWB + (L + 4 * kk) * 16);
-                nx4 = *reinterpret_cast<const float4 *>(xn + r0 + 4 * L);
+            for (int kk = 0; kk < NK; ++kk) a[kk] = q[0][kk];
+            const float nxr[4] = {qn[0].x, qn[0].y, qn[0].z, qn[0].w};
+#pragma unroll
+            for (int pf = 0; pf + 1 < PF; ++pf) {
+#pragma unroll
+                for (int kk = 0; kk < NK; ++kk) q[pf][kk] = q[pf + 1][kk];
+                qn[pf] = qn[pf + 1];
             }
-            for (; r0 < m0; r0 += 16 * kWaves) {
-                // prefetch the next group while this one is on the matrix cores
-                uint4 an[NK];
-                float4 nxn = make_float4(0.f, 0.f, 0.f, 0.f);
-                const int rn = r0 + 16 * kWaves;
-                if (rn < m0) {
-                    const int rr = rn + n16 < m0 ? rn + n16 : m0 - 1;
+            request(q[PF - 1], qn[PF - 1], r0 + 16 * kWaves * PF);
+            // the B operands do not change from group to group: without this the compiler keeps all of them
+            // in registers over the loop, which is what the LDS tile is there to avoid
+            asm volatile("" ::: "memory");
+            const int row0 = r0 + 4 * L;
+            uint4 bq[NK];   // operands of the next token set, read while the current one is on the matrix cores
 #pragma unroll
-                    for (int kk = 0; kk < NK; ++kk) an[kk] = ld16(X + (size_t)rr * ROWB + (L + 4 * kk) * 16);
-                    nxn = *reinterpret_cast<const float4 *>(xn + rn + 4 * L);
-                }
-                const float nxr[4] = {nx4.x, nx4.y, nx4.z, nx4.w};
-                const int row0 = r0 + 4 * L;
+            for (int kk = 0; kk < NK; ++kk) bq[kk] = bop(0, kk);
 #pragma unroll
-                for (int ts = 0; ts < 4; ++ts) {
-                    floatx4_t c = {0.f, 0.f, 0.f, 0.f};
+            for (int ts = 0; ts < 4; ++ts) {
+                floatx4_t c = {0.f, 0.f, 0.f, 0.f};
+                uint4 b[NK];
 #pragma unroll
-                    for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(a[kk], Bt[ts][kk], c);
+                for (int kk = 0; kk < NK; ++kk) b[kk] = bq[kk];
+                if (ts + 1 < 4) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        if (row0 + r < m0) {
-                            const float dt = fmaf(-2.f, c[r], nxr[r] + nkt[ts]);
-                            if (dt < b1[ts]) {
-                                b2[ts] = b1[ts];
-                                b1[ts] = dt;
-                                i1[ts] = row0 + r;
-                            } else if (dt < b2[ts]) {
-                                b2[ts] = dt;
-                            }
-                        }
-                    }
+                    for (int kk = 0; kk < NK; ++kk) bq[kk] = bop(ts + 1, kk);
                 }
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (row0 + r < m0) nxmax = fmaxf(nxmax, nxr[r]);
-                if (rn < m0) {
+                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(a[kk], b[kk], c);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int kk = 0; kk < NK; ++kk) a[kk] = an[kk];
-                    nx4 = nxn;
+                for (int r = 0; r < 4; ++r) {
+                    // rows past the table (the clamped loads of the last group) take part as +inf
+                    const float dt = row0 + r < m0 ? fmaf(-2.f, c[r], nxr[r] + nkt[ts]) : INFINITY;
+                    const bool first = dt < b1[ts];
+                    b2[ts] = first ? b1[ts] : fminf(b2[ts], dt);
+                    i1[ts] = first ? row0 + r : i1[ts];
+                    b1[ts] = first ? dt : b1[ts];
                 }
             }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) nxmax = fmaxf(nxmax, row0 + r < m0 ? nxr[r] : 0.f);
         }
 #pragma unroll
         for (int ts = 0; ts < 4; ++ts) {
@@ -403,8 +478,9 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             }
         }
 
-        // ---- sampling: p_j from the running mu (sequential double adds, token order), then the coins
-        {
+        // ---- sampling: p_j from the running mu (sequential double adds, token order); the coins wait for the
+        //      coin pass
+        if (wave == 0) {
             double muj = mu;
             for (int l = 0; l < nt; ++l) {
                 const double v = (double)sm.vn[l];
@@ -415,56 +491,17 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             if (muj == 0.0) pj = 1.f;
             else if (vnj == 0.f) pj = 0.f;
             else pj = (float)((double)vnj / (muj + (double)vnj));
-            if (wave == 0) sm.p[j] = valid ? pj : 0.f;
+            sm.pall[span_fill + j] = valid ? pj : 0.f;
+            sm.vnall[span_fill + j] = vnj;
             const double mend = muj + (double)vnj;
             mu = __shfl(mend, nt - 1);
         }
-        __syncthreads();
-        {
-            const int nblk = (st.s + 3) >> 2;
-            int nsplit = 1;   // token sub-ranges per 4-slot block, so that every lane has coins to draw
-            while (nsplit < 16 && nblk * nsplit * 2 <= kWG) nsplit *= 2;
-            const int per = T / nsplit;
-            for (int item = tid; item < ((nblk * nsplit + kWG - 1) / kWG) * kWG; item += kWG) {
-                const int blk = item / nsplit, part = item % nsplit;
-                int last[4] = {-1, -1, -1, -1};
-                if (blk < nblk) {
-                    for (int jj = part * per; jj < (part + 1) * per && jj < nt; ++jj) {
-                        const float pj = sm.p[jj];
-                        if (pj > 0.f) {
-                            const uint64_t ge = (uint64_t)(c0 + jj);
-                            uint32_t r[4];
-                            philox4x32_10((uint32_t)blk, (uint32_t)ge, (uint32_t)(ge >> 32), (uint32_t)sid, st.seed_lo,
-                                          st.seed_hi, r);
-#pragma unroll
-                            for (int i = 0; i < 4; ++i)
-                                if ((float)(r[i] >> 8) * (1.0f / 16777216.0f) < pj) last[i] = jj;
-                        }
-                    }
-                }
-                // later tokens overwrite earlier ones: the largest token index over the sub-ranges wins
-                for (int o = 1; o < nsplit; o <<= 1) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) last[i] = max(last[i], __shfl_xor(last[i], o));
-                }
-                if (blk < nblk) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int slot = blk * 4 + i;
-                        const int owner = nsplit >= 4 ? i : (i % nsplit);   // spread the row copies over the lanes
-                        if (part == owner && last[i] >= 0 && slot < st.s) {
-                            const char *ks = krow_of(c0 + last[i]), *vs = vrow_of(c0 + last[i]);
-#pragma unroll
-                            for (int ch = 0; ch < CPR; ++ch) {
-                                st16(Ks + (size_t)slot * ROWB + ch * 16, ld16(ks + ch * 16));
-                                st16(Vs + (size_t)slot * ROWB + ch * 16, ld16(vs + ch * 16));
-                            }
-                            st.sidx[sid * (size_t)st.sS + slot] = (int32_t)(c0 + last[i]);
-                            st.svn[sid * (size_t)st.sS + slot] = sm.vn[last[i]];
-                        }
-                    }
-                }
-            }
+        span_fill += nt;
+        if (span_fill + T > kCoinSpan || c0 + T >= ge1) {
+            __syncthreads();
+            coin_pass(span0, span_fill);
+            span0 += span_fill;
+            span_fill = 0;
         }
         __syncthreads();   // LDS is reused by the next chunk; new rows are visible
     }
@@ -473,8 +510,10 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
     if (w > 0) {
         __syncthreads();
         const int64_t tfirst = n > w ? n - w : 0;
+        const uint32_t sfirst = (uint32_t)((n0 + tfirst) % w);
         for (int64_t t = tfirst + grp; t < n; t += RPB) {
-            const size_t slot = (size_t)((n0 + t) % w);
+            uint32_t slot = sfirst + (uint32_t)(t - tfirst);
+            if (slot >= (uint32_t)w) slot -= (uint32_t)w;
             st16(Kw + slot * ROWB + col * 16, ld16(kin + t * call.token_stride + col * 16));
             st16(Vw + slot * ROWB + col * 16, ld16(vin + t * call.token_stride + col * 16));
         }
