@@ -397,7 +397,8 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 __syncthreads();   // rows of this chunk's creators are visible to every wavefront
                 double best;
                 int bidx;
-                exact_nearest<LPR>(X, me, ld16(krow_of(c0 + e) + col * 16), sm.wbest, sm.widx, best, bidx);
+                exact_nearest<LPR>(X, me, *reinterpret_cast<const uint4 *>(&sm.kt[e * KS + col * 16]), sm.wbest, sm.widx, best,
+                              bidx);
                 const bool ejoin = bidx >= 0 && best <= st.delta2;
                 const bool eforced = !ejoin && me > 0 && me >= st.Mcap;
                 if (eforced && bidx < 0) bidx = 0;
@@ -411,7 +412,8 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 }
             }
             if (create) {
-                if (tid < LPR) st16(X + (size_t)me * ROWB + tid * 16, ld16(krow_of(c0 + e) + tid * 16));
+                if (tid < LPR)   // the new representative's row comes out of the LDS tile
+                    st16(X + (size_t)me * ROWB + tid * 16, *reinterpret_cast<const uint4 *>(&sm.kt[e * KS + tid * 16]));
                 if (tid == 0) {
                     atomicAdd(&cnt[me], 1);
                     xn[me] = sm.nk[e];
@@ -481,12 +483,16 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
         // ---- sampling: p_j from the running mu (sequential double adds, token order); the coins wait for the
         //      coin pass
         if (wave == 0) {
-            double muj = mu;
-            for (int l = 0; l < nt; ++l) {
-                const double v = (double)sm.vn[l];
-                if (l < j) muj += v;
-            }
             const float vnj = sm.vn[j];
+            const double vd = (double)vnj;
+            const int vlo = (int)(__builtin_bit_cast(uint64_t, vd) & 0xffffffffull);
+            const int vhi = (int)(__builtin_bit_cast(uint64_t, vd) >> 32);
+            double muj = mu;
+            for (int l = 0; l < nt; ++l) {   // lane l's value through the scalar unit, no LDS round trip per step
+                const uint64_t bits = (uint64_t)(uint32_t)__builtin_amdgcn_readlane(vlo, l) |
+                                      ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(vhi, l) << 32);
+                if (l < j) muj += __builtin_bit_cast(double, bits);
+            }
             float pj;
             if (muj == 0.0) pj = 1.f;
             else if (vnj == 0.f) pj = 0.f;
