@@ -112,6 +112,7 @@ def main():
     ap.add_argument("--streams", type=int, default=0, help="override the stream count (debugging)")
     ap.add_argument("--prefix", type=int, default=-1, help="override the prefix length (debugging)")
     ap.add_argument("--delta", type=float, default=0.0, help="skip tuning and use this threshold")
+    ap.add_argument("--no-parts", action="store_true", help="skip the subgen_update / subgen_attend timings")
     ap.add_argument("--split", action="store_true", help="time subgen_update + subgen_attend instead of subgen_step")
     ap.add_argument("--many", type=str, default="",
                     help="comma-separated query counts: also time subgen_attend_many on the final state")
@@ -247,6 +248,39 @@ def main():
         alg += total_centers * cfg.elem_bytes * cfg.d      # the split path reads the center table twice
     achieved = alg / (kernel_ms * 1e-3) / 1e9
 
+    # ---- the two entry points of the step on their own (same state, same launch shape): subgen_attend reads the
+    #      whole state, subgen_update the center table and the token rows
+    parts = None
+    if not a.no_parts:
+        reps = 16
+        Kx, Vx = wl.tokens(a.prefix + warm + steps, a.prefix + warm + steps + reps + 2)
+        Kx, Vx = Kx.permute(1, 0, 2).contiguous(), Vx.permute(1, 0, 2).contiguous()
+        e, d = cfg.elem_bytes, cfg.d
+        m_now = sg.stats().total_centers
+
+        def timed(fn):
+            for i in range(2):
+                fn(i)
+            torch.cuda.synchronize()
+            t0e, t1e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0e.record()
+            for i in range(reps):
+                fn(2 + i)
+            t1e.record()
+            torch.cuda.synchronize()
+            return t0e.elapsed_time(t1e) / reps
+
+        att_ms = timed(lambda i: sg.attend(Qt[i % (warm + steps)], out))
+        att_b = S * (e * d * (2 * cfg.s + 2 * cfg.w) + 4 * cfg.s + e * d * cfg.g + 4 * cfg.g * d) \
+            + m_now * (e * d * (1 + a.t) + 4)
+        # the update alone: center rows and their norms, the new token (read, written to the ring), the evicted one
+        upd_ms = timed(lambda i: sg.update(Kx[i], Vx[i])) if a.t == 0 else None
+        upd_b = S * 6 * e * d + m_now * (e * d + 4)
+        parts = {"subgen_attend": {"ms": att_ms, "GB_per_s": att_b / (att_ms * 1e-3) / 1e9, "bytes": att_b}}
+        if upd_ms is not None:
+            parts["subgen_update"] = {"ms": upd_ms, "GB_per_s": upd_b / (upd_ms * 1e-3) / 1e9, "bytes": upd_b}
+        del Kx, Vx
+
     # ---- exact full-KV decode attention from the same library, for context
     exact = None
     if keep:
@@ -325,6 +359,8 @@ def main():
         "exact_full_kv": exact,
         "compressed_vs_exact": quality,
     }
+    if parts is not None:
+        result["entry_points"] = parts
     if many is not None:
         result["attend_many"] = many
     print(json.dumps(result))
