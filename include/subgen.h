@@ -237,7 +237,9 @@ typedef struct subgen_state_view {
     void *centers;            /* host [centers_cap, d]                                    */
     int32_t *counts;          /* host [centers_cap]                                       */
     void *sample_K, *sample_V;/* host [s, d]                                              */
-    int32_t *sample_idx;      /* host [s]: token index held by each slot, -1 = null       */
+    int32_t *sample_idx;      /* host [s]: token index held by each slot, -1 = null; the index is kept in 32
+                                 bits for reporting only (exact below 2^31 tokens per stream) — the sampler's
+                                 counter-based coins use the full 64-bit token index                       */
     float *sample_vn;         /* host [s]: ||v||^2 of that token                          */
     void *window_K, *window_V;/* host [w, d], ring order: slot = token index mod w        */
     int64_t assign_cap;       /* in: entries assign can hold                              */
