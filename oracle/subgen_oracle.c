@@ -130,7 +130,14 @@ typedef struct sgo_stream {
 
     int overflowed;           /* a token was force-joined because max_centers was hit */
     int64_t dropped;          /* tokens with NaN/Inf that were dropped when they left the window */
+
+    /* near-tie protocol of the parity harness: decisions forced from outside, sorted by token */
+    int64_t *ov_token;
+    int32_t *ov_decision;     /* >= 0: join that cluster; SGO_FORCE_NEW: open a new cluster */
+    int64_t n_ov, ov_used;
 } sgo_stream;
+
+#define SGO_FORCE_NEW (-2)
 
 sgo_stream *sgo_create(int d, double delta, int s, int w, uint64_t seed, uint32_t stream, int max_centers, int t)
 {
@@ -157,8 +164,35 @@ void sgo_destroy(sgo_stream *o)
     free(o->X); free(o->cnt); free(o->R);
     free(o->Mk); free(o->Mv); free(o->Midx); free(o->Mvn);
     free(o->assign); free(o->created); free(o->dist1); free(o->dist2);
+    free(o->ov_token); free(o->ov_decision);
     free(o);
 }
+
+/* The paper's algorithm is stated over the reals; in floating point a distance can sit so close to delta, or
+ * two distances so close to each other, that two correct implementations decide differently.  A parity harness
+ * that has checked that such a decision of the other implementation lies inside the near-tie margin can force
+ * it here and replay the stream, so that everything after that token is still compared.  tokens[] must be
+ * strictly increasing; decision >= 0 joins that (existing) cluster, SGO_FORCE_NEW opens a new one.  Must be
+ * called before the first update.  Returns 0, or -1 on bad arguments. */
+int sgo_set_overrides(sgo_stream *o, const int64_t *tokens, const int32_t *decisions, int64_t n)
+{
+    if (!o || n < 0 || o->n_seen != 0) return -1;
+    for (int64_t i = 0; i < n; ++i) {
+        if (tokens[i] < 0 || (i > 0 && tokens[i] <= tokens[i - 1])) return -1;
+        if (decisions[i] < 0 && decisions[i] != SGO_FORCE_NEW) return -1;
+    }
+    free(o->ov_token); free(o->ov_decision);
+    o->ov_token = (int64_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(int64_t));
+    o->ov_decision = (int32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(int32_t));
+    if (n > 0) {
+        memcpy(o->ov_token, tokens, (size_t)n * sizeof(int64_t));
+        memcpy(o->ov_decision, decisions, (size_t)n * sizeof(int32_t));
+    }
+    o->n_ov = n; o->ov_used = 0;
+    return 0;
+}
+
+int64_t sgo_overrides_used(const sgo_stream *o) { return o->ov_used; }
 
 static void append_center(sgo_stream *o, const float *k)
 {
@@ -224,6 +258,20 @@ static void cluster_update(sgo_stream *o, int64_t token, const float *k)
         else if (acc < second) { second = acc; }
     }
     const double thr = o->delta * o->delta;
+    for (int64_t e = 0; e < o->n_ov; ++e) {          /* a decision forced by the parity harness (near-tie) */
+        if (o->ov_token[e] != token) continue;
+        const int32_t dec = o->ov_decision[e];
+        o->ov_used += 1;
+        if (dec == SGO_FORCE_NEW || dec >= o->m) {
+            append_center(o, k);
+            log_decision(o, o->m - 1, 1, best, second);
+        } else {
+            o->cnt[dec] += 1;
+            reservoir_update(o, dec, token, k);
+            log_decision(o, dec, 0, best, second);
+        }
+        return;
+    }
     if (arg >= 0 && best <= thr) {
         o->cnt[arg] += 1;
         reservoir_update(o, arg, token, k);

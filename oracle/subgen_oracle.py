@@ -58,6 +58,10 @@ def _load():
     L.sgo_uniform24_res.restype = C.c_float
     L.sgo_uniform24_res.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32]
     L.sgo_philox4x32_10.argtypes = [C.POINTER(C.c_uint32)] * 3
+    L.sgo_set_overrides.restype = C.c_int
+    L.sgo_set_overrides.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.c_int64]
+    L.sgo_overrides_used.restype = C.c_int64
+    L.sgo_overrides_used.argtypes = [P]
     for name, rt in [("sgo_m", C.c_int), ("sgo_n_seen", C.c_int64), ("sgo_n_evicted", C.c_int64),
                      ("sgo_mu", C.c_double), ("sgo_overflowed", C.c_int), ("sgo_dropped", C.c_int64)]:
         getattr(L, name).restype = rt
@@ -115,6 +119,22 @@ class OracleStream:
         h, self._h = getattr(self, "_h", None), None
         if h:
             self._L.sgo_destroy(h)
+
+    FORCE_NEW = -2
+
+    def set_overrides(self, overrides: dict) -> None:
+        """Near-tie protocol: force the clustering decision of some tokens ({token: cluster index to join, or
+        FORCE_NEW}).  Only a parity harness that has checked the decision margin calls this, before any update."""
+        toks = np.array(sorted(overrides), dtype=np.int64)
+        decs = np.array([overrides[int(t)] for t in toks], dtype=np.int32)
+        rc = self._L.sgo_set_overrides(self._h, toks.ctypes.data_as(C.POINTER(C.c_int64)),
+                                       decs.ctypes.data_as(C.POINTER(C.c_int32)), len(toks))
+        if rc:
+            raise ValueError("bad override list (or the stream has already seen tokens)")
+
+    @property
+    def overrides_used(self) -> int:
+        return int(self._L.sgo_overrides_used(self._h))
 
     # -- the three operations ------------------------------------------------
     def update(self, k, v) -> None:

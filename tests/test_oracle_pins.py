@@ -658,3 +658,92 @@ def test_nonfinite_tokens_are_dropped_and_leave_the_rest_untouched(w):
     big = np.full((1, d), 3e19, dtype=np.float32)
     b.ingest(big, V[:1])
     assert b.dropped == 1 and b.m == 0
+
+
+# --------------------------------------------------------------------------
+# decision log and near-tie margins (what the parity harness forgives by)
+# --------------------------------------------------------------------------
+def test_decision_log_distances_and_margins_on_hand_built_line():
+    """1-D keys with distances known by hand (Algorithm 1, UpdateSoftmaxNormalizer: nearest representative,
+    threshold delta).  delta = 1, representatives end up at 0 and 1.5."""
+    o = OracleStream(1, 1.0, s=1, w=0, max_centers=2)
+    keys = [0.0,      # opens cluster 0: no representative yet
+            1.5,      # 1.5 > delta from 0: opens cluster 1, nearest is 0 at 1.5
+            1.0,      # 1.0 from 0, 0.5 from 1.5: joins 1; runner-up 0 exactly at delta
+            -1.0,     # exactly delta from 0 (threshold hit, margin 0); runner-up 1.5 at 2.5, outside delta
+            0.7,      # 0.7 from 0, 0.8 from 1.5: both within delta, gap (0.8-0.7)/0.7
+            0.25,     # 0.25 from 0, 1.25 from 1.5: runner-up outside delta
+            9.5]      # 8 from 1.5, table full (capacity 2): forced join to cluster 1
+    o.ingest(np.array(keys)[:, None], np.ones((len(keys), 1)))
+    assert o.assign.tolist() == [0, 1, 1, 0, 0, 0, 1]
+    assert o.created.tolist() == [1, 1, 0, 0, 0, 0, 0]
+    assert o.counts.tolist() == [4, 3] and o.overflowed
+    # squared distances in binary floating point of these decimal keys, computed the long way round
+    f = lambda x: float(np.float32(x))
+    d1 = [math.inf, 2.25, 0.25, 1.0, (f(0.7) - 0.0) ** 2, 0.0625, 64.0]
+    d2 = [math.inf, math.inf, 1.0, 6.25, (1.5 - f(0.7)) ** 2, 1.5625, 90.25]
+    assert o.dist1.tolist() == d1
+    assert o.dist2.tolist() == d2
+    thr, gap = o.margins()
+    assert thr[0] == math.inf and gap[0] == math.inf             # nothing to compare with
+    assert thr[1] == 0.5 and gap[1] == math.inf                  # |1.5 - 1| / 1, no runner-up
+    assert thr[2] == 0.5 and gap[2] == 1.0                       # runner-up exactly at delta counts as inside: (1-.5)/.5
+    assert thr[3] == 0.0 and gap[3] == math.inf                  # exact threshold hit; runner-up outside delta
+    assert thr[4] == pytest.approx(0.3, rel=1e-6) and gap[4] == pytest.approx(0.1 / 0.7, rel=1e-6)
+    assert thr[5] == 0.75 and gap[5] == math.inf                 # runner-up at 1.25 > delta
+    assert thr[6] == 7.0 and gap[6] == math.inf                  # forced join: far outside the threshold
+
+
+def test_margins_flag_exactly_the_planted_near_ties():
+    """A key at delta(1 + eps) from its nearest representative has threshold margin eps; two representatives at
+    distances r and r(1 + eps), both inside delta, have gap eps.  Anything the harness forgives must look like that."""
+    for eps in (3e-6, 1e-3):
+        o = OracleStream(1, 2.0, s=1, w=0)
+        o.ingest(np.array([0.0, 2.0 * (1.0 + eps), -3.0, -3.0 + 1.0, -3.0 - (1.0 + eps) + 2.0 * (1.0 + eps)])[:, None],
+                 np.ones((5, 1)))
+        thr, gap = o.margins()
+        assert thr[1] == pytest.approx(eps, rel=2e-2) and (thr[1] < 1e-5) == (eps < 1e-5)
+        assert o.assign.tolist()[:4] == [0, 1, 2, 2] and thr[3] == 0.5
+    o = OracleStream(1, 2.0, s=1, w=0)
+    r = 1.0
+    for eps in (4e-6, 1e-2):
+        o = OracleStream(1, 2.0, s=1, w=0)
+        o.ingest(np.array([0.0, 2.0 * r + r * eps, r])[:, None], np.ones((3, 1)))     # r from 0, r(1+eps) from the other
+        thr, gap = o.margins()
+        assert o.assign.tolist() == [0, 1, 0]
+        assert gap[2] == pytest.approx(eps, rel=2e-2) and (gap[2] < 1e-5) == (eps < 1e-5)
+        assert thr[2] == 0.5
+    # on generic data no decision is anywhere near a tie
+    g = rng(5)
+    o = OracleStream(8, 2.5, s=2, w=3)
+    o.ingest(g.normal(size=(400, 8)), g.normal(size=(400, 8)))
+    thr, gap = o.margins()
+    assert min(thr.min(), gap.min()) > 1e-5 and o.m > 5
+
+
+def test_forced_decisions_replace_the_rule_only_at_their_token():
+    """The override list of the near-tie protocol: the forced token takes the given decision, every other
+    token follows Algorithm 1 on the state that results (integer keys on a line, expectations worked out by hand)."""
+    keys = np.array([0, 10, 4, 5, 9, 14, 3, -2])[:, None].astype(float)
+    vals = np.ones((8, 1))
+    plain = OracleStream(1, 4.0, s=2, w=0)
+    plain.ingest(keys, vals)
+    assert plain.assign.tolist() == [0, 1, 0, 2, 1, 1, 2, 0]           # 4 joins 0 (distance 4 = delta), 5 opens 2
+    forced = OracleStream(1, 4.0, s=2, w=0)
+    forced.set_overrides({2: OracleStream.FORCE_NEW, 5: 0})
+    forced.ingest(keys, vals)
+    # token 2 (key 4) opens cluster 2 instead; then 5 joins it (distance 1), 9 joins 1, 14 is forced into 0,
+    # 3 is nearest to 4 (cluster 2), -2 joins 0
+    assert forced.assign.tolist() == [0, 1, 2, 2, 1, 0, 2, 0]
+    assert forced.created.tolist() == [1, 1, 1, 0, 0, 0, 0, 0]
+    assert forced.counts.tolist() == [3, 2, 3] and forced.overrides_used == 2
+    assert forced.centers[:, 0].tolist() == [0.0, 10.0, 4.0]
+    # sampling is untouched by the clustering decision
+    assert forced.mu == plain.mu and forced.sample_idx.tolist() == plain.sample_idx.tolist()
+    # an empty list changes nothing; a list may not be given to a stream that has started
+    again = OracleStream(1, 4.0, s=2, w=0)
+    again.set_overrides({})
+    again.ingest(keys, vals)
+    assert again.assign.tolist() == plain.assign.tolist()
+    with pytest.raises(ValueError):
+        again.set_overrides({1: 0})
