@@ -26,8 +26,8 @@ __global__ __launch_bounds__(kWG) void exact_partial_kernel(const ExactCall c)
     __shared__ float wmx[kWaves][G], wden[kWaves][G], wacc[kWaves][G][D];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane % LPR, sub = lane / LPR;
-    const size_t sid = blockIdx.y;
-    const int split = blockIdx.x;
+    const size_t sid = blockIdx.x;
+    const int split = blockIdx.y;
     const int64_t per = (c.n + c.splits - 1) / c.splits;
     const int64_t t0 = split * per, t1 = (t0 + per < c.n) ? t0 + per : c.n;
     const char *K = c.K + sid * (size_t)c.n * ROWB;

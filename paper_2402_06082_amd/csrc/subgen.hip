@@ -280,7 +280,7 @@ template <bool BF16, int LPR, int G>
 void launch_exact(const sg::ExactCall &c, int64_t streams, hipStream_t s)
 {
     constexpr int D = LPR * (BF16 ? 8 : 4);
-    hipLaunchKernelGGL((sg::exact_partial_kernel<BF16, LPR, G>), dim3(c.splits, (unsigned)streams), dim3(sg::kWG), 0,
+    hipLaunchKernelGGL((sg::exact_partial_kernel<BF16, LPR, G>), dim3((unsigned)streams, c.splits), dim3(sg::kWG), 0,
                        s, c);
     hipLaunchKernelGGL((sg::exact_combine_kernel<D, G>), dim3((unsigned)streams), dim3(sg::kWG), 0, s, c);
 }
@@ -533,16 +533,17 @@ size_t subgen_exact_workspace_bytes(int64_t streams, int64_t n, int32_t d, int32
     return (size_t)streams * exact_splits(streams, n) * g * (d + 2) * sizeof(float);
 }
 
-int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, int64_t streams, int64_t n,
-                        int32_t d, int32_t g, int32_t dtype, void *workspace, size_t workspace_bytes,
-                        void *hip_stream)
+static int exact_attend_impl(const void *K, const void *V, const void *Q, void *out, int64_t streams, int64_t n,
+                             int32_t d, int32_t g, int32_t dtype, void *workspace, size_t workspace_bytes,
+                             void *hip_stream)
 {
     if (!K || !V || !Q || !out || !workspace) return SUBGEN_EINVAL;
     if (!aligned16(K) || !aligned16(V) || !aligned16(Q) || !aligned16(out) || !aligned16(workspace))
         return SUBGEN_EINVAL;
     if (dtype != SUBGEN_F32 && dtype != SUBGEN_BF16) return SUBGEN_EINVAL;
     const int esz = dtype == SUBGEN_BF16 ? 2 : 4;
-    if (streams < 1 || streams > 65535 * 64LL || n < 1 || d < 1 || !row_bytes_ok((int64_t)d * esz))
+    // one workgroup column per stream on grid.x (up to 2^31 - 1), the sequence splits on grid.y (at most 1024)
+    if (streams < 1 || streams > 0x7fffffffLL || n < 1 || d < 1 || !row_bytes_ok((int64_t)d * esz))
         return SUBGEN_EINVAL;
     if (g != 1 && g != 2 && g != 4) return SUBGEN_EINVAL;
     if (workspace_bytes < subgen_exact_workspace_bytes(streams, n, d, g)) return SUBGEN_ECAPACITY;
@@ -561,6 +562,13 @@ int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, 
         else launch_exact_g<false, 32>(g, c, streams, s);
     }
     return hipGetLastError() == hipSuccess ? SUBGEN_OK : SUBGEN_EHIP;
+}
+
+int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, int64_t streams, int64_t n,
+                        int32_t d, int32_t g, int32_t dtype, void *workspace, size_t workspace_bytes,
+                        void *hip_stream)
+{
+    return exact_attend_impl(K, V, Q, out, streams, n, d, g, dtype, workspace, workspace_bytes, hip_stream);
 }
 
 size_t subgen_kcenter_workspace_bytes(int64_t streams, int64_t n, int32_t r)
