@@ -171,6 +171,23 @@ int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, 
                         void *hip_stream);
 
 /*
+ * subgen_exact_attend_noalloc — subgen_exact_attend for callers that cannot allocate device memory and have no
+ * workspace to pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * kernels, same arguments and same results as subgen_exact_attend; the split partials go to a buffer that is part
+ * of the library itself (a 32 MiB array in device memory, one copy per GPU that loads the library, held until
+ * the process ends).  The call path contains no hipMalloc, hipFree or other allocating routine.
+ *   Returns SUBGEN_ECAPACITY when subgen_exact_workspace_bytes(streams, n, d, g) exceeds
+ *   subgen_exact_noalloc_max_bytes() (32 MiB: e.g. up to 16384 streams x 4 queries at d = 128).
+ *   The device that is current at the call is the one whose buffer is used; K, V, Q, out must live there.
+ *   All calls on one GPU share that GPU's buffer: two such calls that overlap in time on one GPU (different
+ *   HIP streams, or host threads) race.  Calls on one HIP stream are ordered and need no clearing in between:
+ *   every partial a call reads it has written itself.
+ */
+size_t subgen_exact_noalloc_max_bytes(void);
+int subgen_exact_attend_noalloc(const void *K, const void *V, const void *Q, void *out, int64_t streams, int64_t n,
+                                int32_t d, int32_t g, int32_t dtype, void *hip_stream);
+
+/*
  * subgen_kcenter_compress — one-shot greedy k-center compression of a prompt's KV cache (Section 3.2: the
  * variant of the paper's line-retrieval experiment: the greedy k-center algorithm is applied once to the whole
  * cache, the r most recent tokens are retained in addition to k centers selected from the remaining tokens).

@@ -24,7 +24,8 @@ FLAG_NONFINITE = 2
 EXPORTS = [
     "subgen_create", "subgen_destroy", "subgen_update", "subgen_attend", "subgen_attend_many", "subgen_step",
     "subgen_ingest_prefix",
-    "subgen_exact_workspace_bytes", "subgen_exact_attend", "subgen_hbm_read_probe", "subgen_kcenter_workspace_bytes",
+    "subgen_exact_workspace_bytes", "subgen_exact_attend", "subgen_exact_noalloc_max_bytes",
+    "subgen_exact_attend_noalloc", "subgen_hbm_read_probe", "subgen_kcenter_workspace_bytes",
     "subgen_kcenter_compress", "subgen_stats", "subgen_center_counts",
     "subgen_export_state", "subgen_import_state", "subgen_sync", "subgen_strerror", "subgen_last_hip_error",
 ]
@@ -92,6 +93,10 @@ def load():
     L.subgen_exact_workspace_bytes.argtypes = [i64, i64, i32, i32]
     L.subgen_exact_attend.restype = C.c_int
     L.subgen_exact_attend.argtypes = [P, P, P, P, i64, i64, i32, i32, i32, P, C.c_size_t, P]
+    L.subgen_exact_noalloc_max_bytes.restype = C.c_size_t
+    L.subgen_exact_noalloc_max_bytes.argtypes = []
+    L.subgen_exact_attend_noalloc.restype = C.c_int
+    L.subgen_exact_attend_noalloc.argtypes = [P, P, P, P, i64, i64, i32, i32, i32, P]
     L.subgen_kcenter_workspace_bytes.restype = C.c_size_t
     L.subgen_kcenter_workspace_bytes.argtypes = [i64, i64, i32]
     L.subgen_kcenter_compress.restype = C.c_int
@@ -360,6 +365,25 @@ def exact_attend(K: torch.Tensor, V: torch.Tensor, Q: torch.Tensor, out: Optiona
                                  C.c_void_p(out.data_ptr()), S, n, d, g, _dtype_code(K.dtype),
                                  C.c_void_p(workspace.data_ptr()), workspace.numel(),
                                  C.c_void_p(torch.cuda.current_stream(K.device).cuda_stream)), "subgen_exact_attend")
+    return out
+
+
+def exact_attend_noalloc(K: torch.Tensor, V: torch.Tensor, Q: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+    """subgen_exact_attend_noalloc: as exact_attend, the caller brings ``out`` and nothing is allocated."""
+    L = load()
+    S, n, d = K.shape
+    g = Q.shape[1]
+    for t in (K, V, Q):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != K.dtype:
+            raise ValueError("exact_attend_noalloc: contiguous cuda tensors of one dtype expected")
+    if V.shape != K.shape or tuple(Q.shape) != (S, g, d) or tuple(out.shape) != (S, g, d) \
+            or out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous():
+        raise ValueError("exact_attend_noalloc: shape mismatch")
+    _check(L.subgen_exact_attend_noalloc(C.c_void_p(K.data_ptr()), C.c_void_p(V.data_ptr()),
+                                         C.c_void_p(Q.data_ptr()), C.c_void_p(out.data_ptr()), S, n, d, g,
+                                         _dtype_code(K.dtype),
+                                         C.c_void_p(torch.cuda.current_stream(K.device).cuda_stream)),
+           "subgen_exact_attend_noalloc")
     return out
 
 

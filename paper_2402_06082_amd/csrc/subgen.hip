@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -265,6 +266,13 @@ void launch_ingest_lpr(int LPR, dim3 grid, hipStream_t s, const State &st, const
 }
 
 bool row_bytes_ok(int64_t rb) { return rb == 128 || rb == 256 || rb == 512; }
+
+// scratch of the entry point that allocates nothing (split partials of the exact attention); every device that
+// loads the library holds its own copy of this array until the process ends
+constexpr size_t kNoAllocScratchBytes = (size_t)32 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char g_noalloc_scratch[kNoAllocScratchBytes];
+std::atomic<void *> g_noalloc_ptr[kMaxDevices];     // device address of the array, per device ordinal
 
 int exact_splits(int64_t streams, int64_t n)
 {
@@ -569,6 +577,28 @@ int subgen_exact_attend(const void *K, const void *V, const void *Q, void *out, 
                         void *hip_stream)
 {
     return exact_attend_impl(K, V, Q, out, streams, n, d, g, dtype, workspace, workspace_bytes, hip_stream);
+}
+
+/* The same kernels with the split partials in a buffer that is part of the library's code object: no allocation
+ * anywhere on the call path.  The array's name is only a host-side handle; its device address is looked up once
+ * per device (with that device current) and that address is what the kernels are given. */
+size_t subgen_exact_noalloc_max_bytes(void) { return kNoAllocScratchBytes; }
+
+int subgen_exact_attend_noalloc(const void *K, const void *V, const void *Q, void *out, int64_t streams, int64_t n,
+                                int32_t d, int32_t g, int32_t dtype, void *hip_stream)
+{
+    const size_t need = subgen_exact_workspace_bytes(streams, n, d, g);
+    if (need == 0) return SUBGEN_EINVAL;
+    if (need > kNoAllocScratchBytes) return SUBGEN_ECAPACITY;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SUBGEN_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) return SUBGEN_EINVAL;
+    void *ptr = g_noalloc_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_noalloc_scratch)) != hipSuccess || !ptr) return SUBGEN_EHIP;
+        g_noalloc_ptr[dev].store(ptr, std::memory_order_release);     // every thread would find the same address
+    }
+    return exact_attend_impl(K, V, Q, out, streams, n, d, g, dtype, ptr, kNoAllocScratchBytes, hip_stream);
 }
 
 size_t subgen_kcenter_workspace_bytes(int64_t streams, int64_t n, int32_t r)
