@@ -27,9 +27,9 @@ HBM_PEAK_GBS = 8000.0
 
 # Measured HBM traffic of one step-kernel launch (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script, each scaled by what the counter reads for a plain 1 GiB device copy
-# (profiles/step_kernel_cfg3_pmc_hbm_traffic.txt, profiles/step_kernel_cfg5_pmc_hbm_traffic.txt).
-# Workloads without a measurement report null.
-MEASURED_TRAFFIC_BYTES = {"cfg3": 4.0387e9, "cfg5": 4.0381e9}
+# (profiles/step_kernel_cfg3.txt, profiles/step_kernel_cfg4.txt, profiles/step_kernel_cfg5.txt): a constant
+# taken from those runs, not measured in the run that prints it.  Workloads without a measurement report null.
+MEASURED_TRAFFIC_BYTES = {"cfg3": 4.0395e9, "cfg4": 5.3677e9, "cfg5": 4.0379e9}
 
 
 def algorithmic_bytes(cfg, streams, total_centers, t=0):
@@ -43,35 +43,58 @@ def algorithmic_bytes(cfg, streams, total_centers, t=0):
 
 
 # --------------------------------------------------------------------------------------
-# CPU baseline leg: runs in a child process that never touches the GPU
+# CPU baseline leg: runs in a child process that never touches the GPU.  It is given the bytes of
+# a sample of the launch's own streams (copied back from the device generator) and, for the same
+# streams, the library's decision log, so that it also reports how the two sides' decisions compare.
 # --------------------------------------------------------------------------------------
 def _oracle_worker(args):
     import numpy as np
     from oracle.subgen_oracle import OracleStream
-    (d, delta, s, w, stream_id, K, V, Q, prefix) = args
+    (d, delta, s, w, stream_id, K, V, Q, prefix, gpu_assign) = args
     o = OracleStream(d, delta, s, w, seed=0, stream=stream_id)
     o.ingest(K[:prefix], V[:prefix])
     t0 = time.perf_counter()
     o.decode(K[prefix:], V[prefix:], Q)
-    return time.perf_counter() - t0, o.m
+    dt = time.perf_counter() - t0
+    # decisions of the tokens the library had evicted when its log was read, against the oracle's
+    n = len(gpu_assign)
+    oa = o.assign[:n]
+    compared, near_tie, mismatch = n, 0, 0
+    if not np.array_equal(gpu_assign, oa):
+        first = int(np.flatnonzero(gpu_assign != oa)[0])
+        thr, gap = o.margins()
+        compared = first + 1                       # later decisions of this stream legitimately differ
+        if min(thr[first], gap[first]) < 1e-5:
+            near_tie = 1
+        else:
+            mismatch = 1
+    return dt, o.m, compared, near_tie, mismatch
 
 
 def cpu_baseline_main(a):
-    """Oracle decode steps on `cores` streams in parallel (one process per core)."""
+    """Oracle decode steps on the sampled streams, one process per core."""
     import multiprocessing as mp
+    import numpy as np
     import torch
-    from paper_2402_06082_amd.workloads import CONFIGS, Workload
+    from paper_2402_06082_amd.workloads import CONFIGS
     torch.set_num_threads(1)
     cfg = CONFIGS[a.config]
     cores = len(os.sched_getaffinity(0))
     if os.environ.get("OMP_NUM_THREADS", "").isdigit():
         cores = min(cores, int(os.environ["OMP_NUM_THREADS"]))
-    nstreams = cores * a.cpu_streams_per_core
-    wl = Workload(cfg, device="cpu", streams=nstreams)
-    K, V = wl.tokens(0, a.prefix + a.cpu_steps)
-    Q = wl.queries(0, a.cpu_steps)
-    f32 = lambda t: t.to(torch.float32).numpy()
-    jobs = [(cfg.d, a.delta, cfg.s, cfg.w, i, f32(K[i]), f32(V[i]), f32(Q[i]), a.prefix) for i in range(nstreams)]
+    z = {k: np.load(os.path.join(a.cpu_baseline_worker, k + ".npy"), mmap_mode="r") for k in ("K", "V", "Q", "ids")}
+    ids = [int(i) for i in z["ids"]]
+    assign = np.load(os.path.join(a.cpu_baseline_worker, "assign.npy"))
+    cores = min(cores, len(ids))
+
+    def f32(x):                                    # rows travel as raw bits (bf16 as int16)
+        x = np.ascontiguousarray(x)
+        if x.dtype == np.int16:
+            return torch.from_numpy(x).view(torch.bfloat16).float().numpy()
+        return x.astype(np.float32)
+
+    jobs = [(cfg.d, a.delta, cfg.s, cfg.w, sid, f32(z["K"][i]), f32(z["V"][i]), f32(z["Q"][i]), a.prefix, assign[i])
+            for i, sid in enumerate(ids)]
     t0 = time.perf_counter()
     with mp.get_context("fork").Pool(cores) as pool:
         res = pool.map(_oracle_worker, jobs, chunksize=1)
@@ -79,27 +102,50 @@ def cpu_baseline_main(a):
     # decode phase: every core runs its streams back to back; take the slowest core's decode time
     per_core = [sum(r[0] for r in res[c::cores]) for c in range(cores)]
     decode_wall = max(per_core)
-    stream_steps = nstreams * a.cpu_steps
-    print(json.dumps({"stream_steps_per_s": stream_steps / decode_wall, "cores": cores, "streams": nstreams,
-                      "steps": a.cpu_steps, "decode_wall_s": decode_wall, "total_wall_s": wall_all,
-                      "mean_centers": sum(r[1] for r in res) / len(res)}))
+    steps = z["Q"].shape[1]
+    print(json.dumps({"stream_steps_per_s": len(ids) * steps / decode_wall, "cores": cores, "streams": len(ids),
+                      "steps": steps, "decode_wall_s": decode_wall, "total_wall_s": wall_all,
+                      "mean_centers": sum(r[1] for r in res) / len(res),
+                      "decisions_compared": int(sum(r[2] for r in res)), "near_ties": int(sum(r[3] for r in res)),
+                      "mismatches": int(sum(r[4] for r in res))}))
 
 
-def run_cpu_baseline(a, cfg, delta, streams_total):
-    cmd = [sys.executable, os.path.abspath(__file__), "--cpu-baseline-worker", "--config", a.config,
-           "--delta", repr(delta), "--prefix", str(a.prefix), "--cpu-steps", str(a.cpu_steps),
-           "--cpu-streams-per-core", str(a.cpu_streams_per_core)]
-    out = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+def sampled_streams(cfg, S, total, seed=0):
+    """First / last index on every (batch, layer, head) axis plus random picks (all streams if there are few)."""
+    import numpy as np
+    if S <= total:
+        return list(range(S))
+    ids = {0, S - 1}
+    if S == cfg.streams:
+        B, L, H = cfg.batch, cfg.layers, cfg.kv_heads
+        ids |= {(b * L + l) * H + h for b in (0, B - 1) for l in (0, L - 1) for h in (0, H - 1)}
+    r = np.random.default_rng(seed)
+    while len(ids) < total:
+        ids.add(int(r.integers(0, S)))
+    return sorted(ids)
+
+
+def run_cpu_baseline(a, cfg, delta, streams_total, workdir):
+    cmd = [sys.executable, os.path.abspath(__file__), "--cpu-baseline-worker", workdir, "--config", a.config,
+           "--delta", repr(delta), "--prefix", str(a.prefix)]
+    out = subprocess.run(cmd, capture_output=True, text=True, timeout=900)
     if out.returncode != 0:
         raise RuntimeError("cpu baseline failed: " + out.stderr[-2000:])
     r = json.loads(out.stdout.strip().splitlines()[-1])
-    return {
+    cpu = {
         "value": r["stream_steps_per_s"] / streams_total, "unit": "decode steps/s", "cores": r["cores"],
         "kind": "oracle",
-        "sample": (f"{r['streams']} streams of the same generator (prefix {a.prefix} ingested untimed, then "
-                   f"{r['steps']} timed decode steps each, {r['decode_wall_s']:.1f} s on the slowest core); "
-                   f"{r['stream_steps_per_s']:.0f} stream-steps/s scaled to {streams_total} streams"),
+        "sample": (f"{r['streams']} streams of this launch (first/last of every batch, layer and head axis plus "
+                   f"random picks; their bytes copied back from the device generator), prefix {a.prefix} ingested "
+                   f"untimed, then {r['steps']} timed decode steps each, {r['decode_wall_s']:.1f} s on the slowest "
+                   f"core, {r['total_wall_s']:.1f} s in all; {r['stream_steps_per_s']:.0f} stream-steps/s scaled to "
+                   f"{streams_total} streams"),
     }
+    parity = {"streams": r["streams"], "decisions_compared": r["decisions_compared"], "near_ties": r["near_ties"],
+              "mismatches": r["mismatches"],
+              "note": "library's center assignments of the sampled streams against the oracle's; a near-tie is a "
+                      "differing assignment whose logged decision margin is below 1e-5 relative"}
+    return cpu, parity
 
 
 # --------------------------------------------------------------------------------------
@@ -120,11 +166,11 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the generic vector-ALU kernels (kernel_path = 1)")
     ap.add_argument("--no-exact", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=2048)
+    ap.add_argument("--cpu-steps", type=int, default=1024)
     ap.add_argument("--pmc-copy-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (calibrates rocprofv3 byte counters)")
-    ap.add_argument("--cpu-streams-per-core", type=int, default=2)
-    ap.add_argument("--cpu-baseline-worker", action="store_true", help=argparse.SUPPRESS)
+    ap.add_argument("--cpu-streams", type=int, default=64, help="streams of the launch the CPU oracle is timed on")
+    ap.add_argument("--cpu-baseline-worker", default="", help=argparse.SUPPRESS)
     a = ap.parse_args()
 
     from paper_2402_06082_amd.workloads import CONFIGS
@@ -154,9 +200,25 @@ def main():
         delta, probe_m = tune_delta(cfg, dev, prefix=a.prefix)
     wl = Workload(cfg, device=dev, streams=S)
     max_centers = max(2048, 3 * (cfg.target_centers or 1024))
-    sg = binding.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=cfg.g,
-                        max_centers=max_centers, seed=0, device=dev, kernel_path=1 if a.generic else 0,
-                        t_per_cluster=a.t)
+    # load the library's code object and warm the launch path up before anything is timed
+    warmup_ctx = binding.SubGen(4, cfg.d, delta, 8, 4, dtype=cfg.torch_dtype, q_per_stream=cfg.g, device=dev)
+    z = torch.zeros(4, 16, cfg.d, dtype=cfg.torch_dtype, device=dev)
+    warmup_ctx.ingest_prefix(z, z)
+    warmup_ctx.step(z[:, 0].contiguous(), z[:, 0].contiguous(), z[:, :cfg.g].contiguous())
+    warmup_ctx.sync()
+    warmup_ctx.close()
+    del z
+    want_cpu = not a.no_cpu_baseline and a.t == 0
+    cpu_ids = sampled_streams(cfg, S, a.cpu_streams) if want_cpu else []
+    cpu_idx = torch.tensor(cpu_ids, device=dev, dtype=torch.long)
+    mk = lambda log: binding.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=cfg.g,
+                                    max_centers=max_centers, seed=0, device=dev, kernel_path=1 if a.generic else 0,
+                                    t_per_cluster=a.t, assign_log_tokens=log)
+    sg = mk(0)                   # the context that is timed
+    # a twin of it that keeps the decision log the parity report needs: same launch shape, same inputs, untimed
+    # (the log's scattered stores cost the prefix ingest about 13 %, so the timed context runs without it)
+    sgp = mk(a.prefix + warm + steps) if want_cpu else None
+    cpuK, cpuV = [], []          # rows of the sampled streams, for the CPU leg
 
     # ---- prefix: generate on the device block by block, ingest; keep it resident for the exact kernel
     keep = not a.no_exact
@@ -177,11 +239,16 @@ def main():
         if keep:
             Kall[:, t0:t1] = K
             Vall[:, t0:t1] = V
+        if want_cpu:
+            cpuK.append(K[cpu_idx].cpu())
+            cpuV.append(V[cpu_idx].cpu())
         torch.cuda.synchronize()
         ti = time.perf_counter()
         sg.ingest_prefix(K, V)
         sg.sync()
         ingest_s += time.perf_counter() - ti
+        if sgp is not None:
+            sgp.ingest_prefix(K, V)
         del K, V
     st0 = sg.stats()
 
@@ -241,6 +308,18 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     st1 = sg.stats()
+    gpu_assign = None
+    if want_cpu:                 # the library's decisions for the sampled streams, as of the end of the timed steps
+        import numpy as np
+        for i in range(warm + steps):
+            sgp.step(Kt[i], Vt[i], Qt[i], out)
+        logs = [sgp.export_state(i, rows=False) for i in cpu_ids]
+        gpu_assign = np.stack([e.assign for e in logs])
+        for i, e in zip(cpu_ids, logs):          # the twin and the timed context hold the same state
+            t = sg.export_state(i, rows=False)
+            assert t.m == e.m and np.array_equal(t.counts, e.counts) and np.array_equal(t.sample_idx, e.sample_idx)
+        sgp.close()
+        del logs
     kernel_ms = sum(x.elapsed_time(y) for x, y in zip(ev0, ev1)) / steps
     total_centers = 0.5 * (m_before + st1.total_centers)
     alg = algorithmic_bytes(cfg, S, total_centers, a.t)
@@ -326,11 +405,52 @@ def main():
                          "frac_hbm": io / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "TFLOP_per_s": 2.0 * S * nq * cfg.d * rows_per_stream / (ms * 1e-3) / 1e12})
             del Qm, om
+    # ---- the streaming-read bandwidth this machine reaches with the access pattern of the step kernel (every
+    #      workgroup streams its own contiguous region with non-temporal 16-byte loads): the practical ceiling
+    probe_bytes = 4 << 30
+    region = 512 << 10
+    pbuf = torch.empty(probe_bytes, dtype=torch.uint8, device=dev)
+    pbuf.fill_(1)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    for _ in range(3):
+        binding.hbm_read_probe(pbuf, probe_bytes // region, sink, True, region)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        binding.hbm_read_probe(pbuf, probe_bytes // region, sink, True, region)
+    e1.record()
+    torch.cuda.synchronize()
+    ceiling = probe_bytes / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
+    del pbuf
     setup_s = time.perf_counter() - t_setup
 
-    cpu = None
-    if not a.no_cpu_baseline:
-        cpu = run_cpu_baseline(a, cfg, delta, S)
+    cpu = parity = None
+    if want_cpu:
+        import shutil
+        import tempfile
+        import numpy as np
+        # decode inputs of the sampled streams for the CPU leg: the same positions the timed steps consumed, and on
+        # beyond them, block by block (only the sampled rows are kept)
+        dK, dV, dQ = [], [], []
+        for b0 in range(0, a.cpu_steps, BLOCK):
+            b1 = min(a.cpu_steps, b0 + BLOCK)
+            Kb, Vb = wl.tokens(a.prefix + b0, a.prefix + b1)
+            Qb = wl.queries(b0, b1)
+            dK.append(Kb[cpu_idx].cpu()); dV.append(Vb[cpu_idx].cpu()); dQ.append(Qb[cpu_idx].cpu())
+            del Kb, Vb, Qb
+        raw = lambda t: (t.view(torch.int16) if t.dtype == torch.bfloat16 else t).numpy()
+        workdir = tempfile.mkdtemp(prefix="subgen_bench_")
+        try:
+            np.save(os.path.join(workdir, "K.npy"), raw(torch.cat(cpuK + dK, 1)))
+            np.save(os.path.join(workdir, "V.npy"), raw(torch.cat(cpuV + dV, 1)))
+            np.save(os.path.join(workdir, "Q.npy"), raw(torch.cat(dQ, 1)))
+            np.save(os.path.join(workdir, "ids.npy"), np.array(cpu_ids, dtype=np.int64))
+            np.save(os.path.join(workdir, "assign.npy"), gpu_assign)
+            del cpuK, cpuV, dK, dV, dQ
+            cpu, parity = run_cpu_baseline(a, cfg, delta, S, workdir)
+        finally:
+            shutil.rmtree(workdir, ignore_errors=True)
 
     name = a.config + ("" if S == cfg.streams and a.prefix == cfg.prefix else f" (streams={S}, prefix={a.prefix})")
     kernel = "subgen_update+subgen_attend" if a.split else "subgen_step"
@@ -354,8 +474,12 @@ def main():
                                                                     and a.prefix == cfg.prefix and a.t == 0
                                                                     and not a.generic) else None,
             "kernel": kernel, "kernel_ms": kernel_ms, "algorithmic_bytes_per_launch": alg,
+            "ceiling_GBs": ceiling, "frac_of_ceiling": achieved / ceiling,
+            "ceiling_note": "subgen_hbm_read_probe in this run: 4 GiB, one 512 KiB region per workgroup, non-temporal "
+                            "16-byte loads (the step kernel's access pattern)",
         },
         "cpu_baseline": cpu,
+        "parity": parity,
         "exact_full_kv": exact,
         "compressed_vs_exact": quality,
     }

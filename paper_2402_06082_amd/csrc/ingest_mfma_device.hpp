@@ -17,9 +17,8 @@
 //   5. the sampling coins do not depend on the clustering: the chunks only
 //      leave each token's probability behind, and once per 1024 evicted
 //      tokens (or at the end of the call) one pass draws the coins per 4-slot
-//      block, newest token first; the last accepting token of a slot wins
-//      (sequential overwrite semantics), so a slot is copied at most once
-//      per pass and a lane stops as soon as its four slots are taken.
+//      block; the last accepting token of a slot wins (sequential overwrite
+//      semantics), so a slot is copied at most once per pass.
 // The window is handled by index arithmetic: the tokens that leave the window
 // during the call come first from the ring, then from the call's own input;
 // the ring is rewritten once at the end.
@@ -29,14 +28,21 @@
 namespace sg {
 
 constexpr int kChunkT = 64;  // tokens per chunk = one lane per token in the resolve loop
-constexpr int kCoinSpan = 1024;  // evicted tokens per coin pass (a multiple of the chunk)
+#ifndef SG_COINSPAN
+#define SG_COINSPAN 1024
+#endif
+constexpr int kCoinSpan = SG_COINSPAN;  // evicted tokens per coin pass (a multiple of the chunk)
 
 template <int NK>
 struct SmemIngest {
     alignas(16) float nk[kChunkT];
     float vn[kChunkT];
-    // coin probability and ||v||^2 of the evicted tokens whose coins are still to be drawn (up to kCoinSpan)
-    float pall[kCoinSpan], vnall[kCoinSpan];
+    // coin threshold and ||v||^2 of the evicted tokens whose coins are still to be drawn (up to kCoinSpan).
+    // The coin u = (r >> 8) 2^-24 of a 32-bit word r is accepted iff u < p; p 2^24 is exact in fp32, so this is
+    // (r >> 8) < ceil(p 2^24), i.e. r <= 256 ceil(p 2^24) - 1 in 32-bit arithmetic (p = 1 wraps to 0xffffffff:
+    // always).  plim holds that bound; 0 stands for p = 0 (never; a bound of a positive p is at least 255).
+    uint32_t plim[kCoinSpan];
+    float vnall[kCoinSpan];
     float wb1[kWaves][kChunkT], wb2[kWaves][kChunkT];
     int wi1[kWaves][kChunkT];
     float wnx[kWaves];
@@ -117,7 +123,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
 
     // ---- coin pass over the evicted tokens [g0, g0 + cnt) whose probabilities are in LDS: every lane takes one
     //      4-slot block (and one sub-range of the tokens, so that all lanes have coins to draw) and walks its
-    //      tokens from the newest to the oldest; the first accept it meets per slot is the one that stays
+    //      tokens from the oldest to the newest; the last accept per slot is the one that stays
     auto coin_pass = [&](int64_t g0, int cnt) {
         const int nblk = (st.s + 3) >> 2;
         int nsplit = 1;
@@ -128,17 +134,15 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             int last[4] = {-1, -1, -1, -1};
             if (blk < nblk) {
                 const int lo = part * per, hi = (part + 1) * per < cnt ? (part + 1) * per : cnt;
-                for (int jj = hi - 1; jj >= lo; --jj) {
-                    const float pj = sm.pall[jj];
-                    if (pj > 0.f) {
+                for (int jj = lo; jj < hi; ++jj) {   // oldest first: a later accept overwrites an earlier one
+                    const uint32_t lim = sm.plim[jj];
+                    if (lim != 0u) {
                         const uint64_t ge = (uint64_t)(g0 + jj);
                         uint32_t r[4];
                         philox4x32_10((uint32_t)blk, (uint32_t)ge, (uint32_t)(ge >> 32), (uint32_t)sid, st.seed_lo,
                                       st.seed_hi, r);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            if (last[i] < 0 && (float)(r[i] >> 8) * (1.0f / 16777216.0f) < pj) last[i] = jj;
-                        if ((last[0] | last[1] | last[2] | last[3]) >= 0) break;
+                        for (int i = 0; i < 4; ++i) last[i] = r[i] <= lim ? jj : last[i];
                     }
                 }
             }
@@ -497,7 +501,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             if (muj == 0.0) pj = 1.f;
             else if (vnj == 0.f) pj = 0.f;
             else pj = (float)((double)vnj / (muj + (double)vnj));
-            sm.pall[span_fill + j] = valid ? pj : 0.f;
+            sm.plim[span_fill + j] = valid && pj > 0.f ? (uint32_t)ceilf(pj * 16777216.0f) * 256u - 1u : 0u;
             sm.vnall[span_fill + j] = vnj;
             const double mend = muj + (double)vnj;
             mu = __shfl(mend, nt - 1);

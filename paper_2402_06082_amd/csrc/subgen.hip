@@ -269,7 +269,10 @@ bool row_bytes_ok(int64_t rb) { return rb == 128 || rb == 256 || rb == 512; }
 
 // scratch of the entry point that allocates nothing (split partials of the exact attention); every device that
 // loads the library holds its own copy of this array until the process ends
-constexpr size_t kNoAllocScratchBytes = (size_t)32 << 20;
+#ifndef SG_NOALLOC_BYTES
+#define SG_NOALLOC_BYTES ((size_t)32 << 20)
+#endif
+constexpr size_t kNoAllocScratchBytes = SG_NOALLOC_BYTES;
 constexpr int kMaxDevices = 64;
 static __device__ __align__(256) unsigned char g_noalloc_scratch[kNoAllocScratchBytes];
 std::atomic<void *> g_noalloc_ptr[kMaxDevices];     // device address of the array, per device ordinal
