@@ -51,7 +51,10 @@ enum {
     SUBGEN_ENOMEM = -2,    /* device or host allocation failed                                     */
     SUBGEN_EHIP = -3,      /* a HIP call failed; see subgen_last_hip_error                         */
     SUBGEN_EEMPTY = -4,    /* attend before any token                                              */
-    SUBGEN_ECAPACITY = -5  /* a per-context capacity would be exceeded (assignment log, sizes)     */
+    SUBGEN_ECAPACITY = -5  /* a size given to this call exceeds what it can take (a workspace that is too
+                              small, more workgroups than a launch holds).  Device-side capacities do not
+                              use it: a full center table raises SUBGEN_FLAG_CENTER_OVERFLOW, and the
+                              assignment log simply stops after assign_log_tokens entries                 */
 };
 
 enum { SUBGEN_F32 = 0, SUBGEN_BF16 = 1 };
@@ -90,14 +93,16 @@ typedef struct subgen_opts {
                                count, which the argument checks (SUBGEN_EEMPTY, the log capacity) and
                                subgen_export_state use, is brought up to date by every synchronising call; call
                                subgen_sync after replaying graphs.  0 (default) = the count is a kernel argument */
-    int32_t reserved_;      /* padding: zero */
+    int32_t out_dtype;      /* element type of the attention outputs: SUBGEN_F32 (default; what the 2e-3 parity bar is
+                               stated on) or SUBGEN_BF16 (the fp32 result rounded to nearest even at the store)  */
 } subgen_opts;
 
 /*
  * subgen_create — allocate the state of `streams` independent streams (Section 2.1: the data
  * structure of the streaming attention problem; Algorithm 1, initialisation: mu = 0, D empty,
  * M all null).
- *   d              head dimension; row bytes (d * element size) must be 128, 256, 512 or 1024
+ *   d              head dimension; row bytes (d * element size) must be 128, 256 or 512
+ *                  (fp32: d = 32, 64, 128; bf16: d = 64, 128, 256)
  *   delta          cluster threshold (Definition 1; Algorithm 1 joins iff ||k - x|| <= delta), >= 0
  *   sample_budget  s >= 1, number of slots of M
  *   window         w >= 0, recent tokens kept exactly (Section 3.2)
@@ -122,7 +127,7 @@ int subgen_update(subgen_ctx *ctx, const void *K_t, const void *V_t);
  *   num = sum_{j in W} e^{<q,k_j>} v_j + sum_{j in M} mu / (s ||v_j||^2) e^{<q,k_j>} v_j
  *   out = num / den      (a common maximum is subtracted from every exponent; fp32 accumulation)
  *   Q_t   device, [streams, g, d] contiguous, context dtype
- *   out   device, [streams, g, d] contiguous, fp32, fully overwritten
+ *   out   device, [streams, g, d] contiguous, fp32 (or bf16 with opts.out_dtype), fully overwritten
  * Returns SUBGEN_EEMPTY if no token has been given yet.
  */
 int subgen_attend(subgen_ctx *ctx, const void *Q_t, void *out);
@@ -133,7 +138,7 @@ int subgen_attend(subgen_ctx *ctx, const void *Q_t, void *out);
  * speculative draft, or of a wide grouped-query head group.  Every query gets exactly what subgen_attend
  * would give it; n_queries is independent of the context's q_per_stream.  The state is not changed.
  *   Q     device, [streams, n_queries, d] contiguous, context dtype
- *   out   device, [streams, n_queries, d] contiguous, fp32, fully overwritten
+ *   out   device, [streams, n_queries, d] contiguous, fp32 (or bf16 with opts.out_dtype), fully overwritten
  * bf16 contexts with d = 64 or 128 in representative mode run both contractions (scores, weights x values)
  * on the matrix cores and read the state once per 64 queries; other contexts answer the queries in groups of
  * at most four with the decode kernels.

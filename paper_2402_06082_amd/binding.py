@@ -42,7 +42,7 @@ class subgen_opts(C.Structure):
                 ("max_centers", C.c_int32), ("assign_log_tokens", C.c_int64), ("seed", C.c_uint64),
                 ("hip_stream", C.c_void_p), ("device", C.c_int32), ("device_set", C.c_int32),
                 ("kernel_path", C.c_int32), ("t_per_cluster", C.c_int32), ("device_counter", C.c_int32),
-                ("reserved_", C.c_int32)]
+                ("out_dtype", C.c_int32)]
 
 
 class subgen_stats_t(C.Structure):
@@ -161,7 +161,8 @@ class SubGen:
     def __init__(self, streams: int, d: int, delta: float, sample_budget: int, window: int, *,
                  dtype: torch.dtype = torch.float32, q_per_stream: int = 1, max_centers: int = 0,
                  assign_log_tokens: int = 0, seed: int = 0, device: Optional[torch.device] = None,
-                 kernel_path: int = 0, t_per_cluster: int = 0, device_counter: bool = False):
+                 kernel_path: int = 0, t_per_cluster: int = 0, device_counter: bool = False,
+                 out_dtype: torch.dtype = torch.float32):
         self._L = load()
         self._h = C.c_void_p()
         if not torch.cuda.is_available():
@@ -171,6 +172,7 @@ class SubGen:
         self.g = int(q_per_stream)
         self.dtype = dtype
         self.dtype_code = _dtype_code(dtype)
+        self.out_dtype = out_dtype
         self.max_centers = int(max_centers) if max_centers else 4096
         self.assign_log_tokens = int(assign_log_tokens)
         self.delta = float(np.float32(delta))
@@ -187,6 +189,7 @@ class SubGen:
         o.kernel_path = int(kernel_path)
         o.device_counter = 1 if device_counter else 0
         o.t_per_cluster = self.t = int(t_per_cluster)
+        o.out_dtype = _dtype_code(out_dtype)
         _check(self._L.subgen_create(C.byref(self._h), self.streams, self.d, C.c_float(self.delta), self.s, self.w,
                                      C.byref(o)), "subgen_create")
 
@@ -214,9 +217,9 @@ class SubGen:
 
     def attend(self, Q_t: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         if out is None:
-            out = torch.empty(self.streams, self.g, self.d, dtype=torch.float32, device=self.device)
+            out = torch.empty(self.streams, self.g, self.d, dtype=self.out_dtype, device=self.device)
         q = self._rows(Q_t, (self.streams, self.g, self.d), "Q_t")
-        o = self._rows(out, (self.streams, self.g, self.d), "out", torch.float32)
+        o = self._rows(out, (self.streams, self.g, self.d), "out", self.out_dtype)
         _check(self._L.subgen_attend(self._h, q, o), "subgen_attend")
         return out
 
@@ -226,20 +229,20 @@ class SubGen:
             raise ValueError("Q must be [streams, n_queries, d]")
         nq = int(Q.shape[1])
         if out is None:
-            out = torch.empty(self.streams, nq, self.d, dtype=torch.float32, device=self.device)
+            out = torch.empty(self.streams, nq, self.d, dtype=self.out_dtype, device=self.device)
         q = self._rows(Q, (self.streams, nq, self.d), "Q")
-        o = self._rows(out, (self.streams, nq, self.d), "out", torch.float32)
+        o = self._rows(out, (self.streams, nq, self.d), "out", self.out_dtype)
         _check(self._L.subgen_attend_many(self._h, q, nq, o), "subgen_attend_many")
         return out
 
     def step(self, K_t: torch.Tensor, V_t: torch.Tensor, Q_t: torch.Tensor,
              out: Optional[torch.Tensor] = None) -> torch.Tensor:
         if out is None:
-            out = torch.empty(self.streams, self.g, self.d, dtype=torch.float32, device=self.device)
+            out = torch.empty(self.streams, self.g, self.d, dtype=self.out_dtype, device=self.device)
         k = self._rows(K_t, (self.streams, self.d), "K_t")
         v = self._rows(V_t, (self.streams, self.d), "V_t")
         q = self._rows(Q_t, (self.streams, self.g, self.d), "Q_t")
-        o = self._rows(out, (self.streams, self.g, self.d), "out", torch.float32)
+        o = self._rows(out, (self.streams, self.g, self.d), "out", self.out_dtype)
         _check(self._L.subgen_step(self._h, k, v, q, o), "subgen_step")
         return out
 

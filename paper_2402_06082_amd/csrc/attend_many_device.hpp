@@ -249,7 +249,7 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
             dn = fmaf(sm.wden[wv][qn], sc, dn);
             num = fmaf(accbuf[((size_t)wv * 16 + qn) * D + c], sc, num);
         }
-        call.out[(sid * (size_t)call.Gm + q) * D + c] = num / dn;
+        put_out(st, call.out, (sid * (size_t)call.Gm + q) * D + c, num / dn);
     }
 }
 

@@ -72,7 +72,12 @@ int dev_alloc(subgen_ctx *c, T **p, size_t count, int fill_byte)
     const size_t bytes = (count ? count : 1) * sizeof(T);
     hipError_t e = hipMalloc(&q, bytes);
     if (e != hipSuccess) return fail_hip(c, e);
-    c->allocs.push_back(q);
+    try {
+        c->allocs.push_back(q);
+    } catch (const std::bad_alloc &) {   // nothing may throw across the C ABI
+        (void)hipFree(q);
+        return SUBGEN_ENOMEM;
+    }
     e = hipMemsetAsync(q, fill_byte, bytes, c->stream);
     if (e != hipSuccess) return fail_hip(c, e);
     *p = reinterpret_cast<T *>(q);
@@ -349,6 +354,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     if (o.kernel_path < 0 || o.kernel_path > 2) return SUBGEN_EINVAL;
     if (o.t_per_cluster < 0 || o.t_per_cluster > 64) return SUBGEN_EINVAL;
     if (o.device_counter != 0 && o.device_counter != 1) return SUBGEN_EINVAL;
+    if (o.out_dtype != SUBGEN_F32 && o.out_dtype != SUBGEN_BF16) return SUBGEN_EINVAL;
 
     subgen_ctx *c = new (std::nothrow) subgen_ctx();
     if (!c) return SUBGEN_ENOMEM;
@@ -371,6 +377,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     State &st = c->st;
     st.Mcap = Mcap; st.s = sample_budget; st.w = window; st.d = d;
     st.t = o.t_per_cluster;
+    st.out_bf16 = o.out_dtype == SUBGEN_BF16 ? 1 : 0;
     st.McapS = (Mcap + 15) / 16 * 16; st.sS = (sample_budget + 15) / 16 * 16;
     st.delta2 = (double)delta * (double)delta;
     st.seed_lo = (uint32_t)o.seed; st.seed_hi = (uint32_t)(o.seed >> 32);
@@ -471,7 +478,7 @@ int subgen_attend_many(subgen_ctx *c, const void *Q, int32_t n_queries, void *ou
     for (int32_t q0 = 0; q0 < n_queries;) {
         const int g = n_queries - q0 >= 4 ? 4 : (n_queries - q0 >= 2 ? 2 : 1);
         Call call{};
-        call.Q = (const char *)Q + q0 * rowb; call.out = (float *)out + (int64_t)q0 * c->d; call.n_seen = c->n_seen;
+        call.Q = (const char *)Q + q0 * rowb; call.out = (float *)((char *)out + (int64_t)q0 * c->d * (c->st.out_bf16 ? 2 : 4)); call.n_seen = c->n_seen;
         call.q_stride = n_queries * rowb; call.out_stride = (int64_t)n_queries * c->d;
         const int rc = launch_decode(c, MODE_ATTEND, call, g);
         if (rc != SUBGEN_OK) return rc;
@@ -685,8 +692,14 @@ int subgen_center_counts(subgen_ctx *c, int32_t *host_m)
 int subgen_stats(subgen_ctx *c, subgen_stats_t *o)
 {
     if (!c || !o) return SUBGEN_EINVAL;
-    std::vector<int32_t> m((size_t)c->S);
-    std::vector<uint32_t> fl((size_t)c->S);
+    std::vector<int32_t> m;
+    std::vector<uint32_t> fl;
+    try {
+        m.resize((size_t)c->S);
+        fl.resize((size_t)c->S);
+    } catch (const std::bad_alloc &) {   // nothing may throw across the C ABI
+        return SUBGEN_ENOMEM;
+    }
     int rc = subgen_center_counts(c, m.data());
     if (rc != SUBGEN_OK) return rc;
     DeviceGuard guard(c->device);

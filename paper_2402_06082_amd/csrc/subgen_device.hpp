@@ -51,6 +51,7 @@ struct State {
     double delta2;      // delta^2
     uint32_t seed_lo, seed_hi;
     int64_t *seen;      // [1] tokens seen by every stream, kept on the device (contexts made for graph capture), or null
+    int32_t out_bf16;   // outputs are written as bf16 (round to nearest even) instead of fp32
 };
 
 // Tokens seen before this launch: the host's count (a kernel argument), or, in contexts that keep the count on the
@@ -159,6 +160,24 @@ __device__ __forceinline__ float row_sum16(float v)
     v += row_ror<2>(v);
     v += row_ror<1>(v);
     return v;
+}
+
+// Attention outputs are fp32 or bf16 (a context option).  `rows` is the base of one stream's outputs, found by
+// out_rows() below; element i is stored in the context's output type.
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN (quiet)
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ float *out_rows(const State &st, float *out, size_t elems)
+{
+    return reinterpret_cast<float *>(reinterpret_cast<char *>(out) + elems * (st.out_bf16 ? 2 : 4));
+}
+__device__ __forceinline__ void put_out(const State &st, float *rows, size_t i, float v)
+{
+    if (st.out_bf16) reinterpret_cast<uint16_t *>(rows)[i] = (uint16_t)f32_to_bf16_rne(v);
+    else rows[i] = v;
 }
 
 // online-softmax partial of one row group for one query
@@ -588,7 +607,7 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
                 den = fmaf(sm.wden[wv][g], sc, den);
                 num = fmaf(sm.wacc[wv][g][c], sc, num);
             }
-            outrows[(size_t)g * d + c] = num / den;
+            put_out(st, outrows, (size_t)g * d + c, num / den);
         }
     }
     __syncthreads();  // LDS and state are reusable by the next token
@@ -608,7 +627,7 @@ __global__ __launch_bounds__(kWG) void decode_kernel(const State st, const Call 
     const char *krow = UPD ? call.K + sid * call.stream_stride : nullptr;
     const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
     const char *qrows = ATT ? call.Q + sid * call.q_stride : nullptr;
-    float *outrows = ATT ? call.out + sid * call.out_stride : nullptr;
+    float *outrows = ATT ? out_rows(st, call.out, sid * call.out_stride) : nullptr;
     token_step<BF16, LPR, G, UPD, ATT>(st, sid, krow, vrow, qrows, outrows, tokens_seen(st, call.n_seen), m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {

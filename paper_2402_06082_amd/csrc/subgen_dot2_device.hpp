@@ -444,7 +444,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                 dn = fmaf(sm.wden[wv], sc, dn);
                 num = fmaf(sm.wacc[wv][tid], sc, num);
             }
-            outrow[tid] = num / dn;
+            put_out(st, outrow, tid, num / dn);
         }
     }
     // ---- the update's writes to the ring and to the cluster table (see above)
@@ -482,7 +482,7 @@ __global__ __launch_bounds__(NW * 64) void decode_dot2_kernel(const State st, co
     const char *krow = UPD ? call.K + sid * call.stream_stride : nullptr;
     const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
     const char *qrow = ATT ? call.Q + sid * call.q_stride : nullptr;
-    float *outrow = ATT ? call.out + sid * call.out_stride : nullptr;
+    float *outrow = ATT ? out_rows(st, call.out, sid * call.out_stride) : nullptr;
     token_step_dot2<UPD, ATT, NW>(st, sid, krow, vrow, qrow, outrow, tokens_seen(st, call.n_seen), m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {

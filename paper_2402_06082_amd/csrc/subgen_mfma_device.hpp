@@ -626,7 +626,7 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
                 dn = fmaf(sm.wden[wv][g], sc, dn);
                 num = fmaf(sm.wacc[wv][g][c], sc, num);
             }
-            outrows[(size_t)g * D + c] = num / dn;
+            put_out(st, outrows, (size_t)g * D + c, num / dn);
         }
     }
     __syncthreads();  // LDS and state are reusable by the next token
@@ -643,7 +643,7 @@ __global__ __launch_bounds__(kWG, 3) void decode_mfma_kernel(const State st, con
     const char *krow = UPD ? call.K + sid * call.stream_stride : nullptr;
     const char *vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
     const char *qrows = ATT ? call.Q + sid * call.q_stride : nullptr;
-    float *outrows = ATT ? call.out + sid * call.out_stride : nullptr;
+    float *outrows = ATT ? out_rows(st, call.out, sid * call.out_stride) : nullptr;
     token_step_mfma<NK, G, UPD, ATT>(st, sid, krow, vrow, qrows, outrows, tokens_seen(st, call.n_seen), m, mu, sm);
     if constexpr (UPD) {
         if (threadIdx.x == 0) {

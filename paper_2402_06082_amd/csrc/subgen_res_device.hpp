@@ -338,7 +338,7 @@ __device__ __forceinline__ void token_step_res(const State &st, const size_t sid
                 den = fmaf(sm.wden[wv][g], sc, den);
                 num = fmaf(sm.wacc[wv][g][c], sc, num);
             }
-            outrows[(size_t)g * d + c] = num / den;
+            put_out(st, outrows, (size_t)g * d + c, num / den);
         }
     }
     __syncthreads();  // LDS and state are reusable by the next token
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(kWG) void decode_res_kernel(const State st, const C
     const char *kbase = UPD ? call.K + sid * call.stream_stride : nullptr;
     const char *vbase = UPD ? call.V + sid * call.stream_stride : nullptr;
     const char *qrows = ATT ? call.Q + sid * call.q_stride : nullptr;
-    float *outrows = ATT ? call.out + sid * call.out_stride : nullptr;
+    float *outrows = ATT ? out_rows(st, call.out, sid * call.out_stride) : nullptr;
     const int64_t nt = UPD ? call.n_tokens : 1;
     const int64_t n0 = tokens_seen(st, call.n_seen);
     for (int64_t t = 0; t < nt; ++t)

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
     const char *const krow = UPD ? call.K + sid * call.stream_stride : nullptr;
     const char *const vrow = UPD ? call.V + sid * call.stream_stride : nullptr;
     const char *const qrows = call.Q + sid * call.q_stride;
-    float *const outrows = call.out + sid * call.out_stride;
+    float *const outrows = out_rows(st, call.out, sid * call.out_stride);
     const int64_t n_seen = tokens_seen(st, call.n_seen);
     int m = st.m[sid];
     double mu = st.mu[sid];
@@ -539,7 +539,7 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
                 num = fmaf(accbuf[((size_t)wv * 16 + g) * D + c], sc, num);
             }
         }
-        outrows[(size_t)g * D + c] = num / dn;
+        put_out(st, outrows, (size_t)g * D + c, num / dn);
     }
 
     // ---- the update's writes to the cluster table (see the decision above)

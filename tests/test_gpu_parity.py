@@ -673,3 +673,62 @@ def test_ingest_window_sizes_and_long_calls(w, s, kernel_path):
     parts.ingest_prefix(K2, V2)
     for sid in range(wl.S):
         assert state_tuple(one, sid) == state_tuple(parts, sid)
+
+
+@pytest.mark.parametrize("dtype,d,g,kernel_path,t", [(torch.bfloat16, 128, 1, 0, 0), (torch.bfloat16, 128, 1, 2, 0),
+                                                     (torch.bfloat16, 128, 4, 0, 0), (torch.bfloat16, 64, 2, 0, 0),
+                                                     (torch.bfloat16, 256, 1, 0, 0), (torch.bfloat16, 128, 2, 1, 0),
+                                                     (torch.float32, 64, 1, 0, 0), (torch.bfloat16, 128, 1, 0, 2)])
+def test_bf16_outputs_are_the_fp32_outputs_rounded_once(dtype, d, g, kernel_path, t):
+    """opts.out_dtype = bf16 in every kernel family (step, attend, attend_many): the stored value is the fp32
+    result rounded to nearest even, so it equals the rounded output of an fp32-output twin bit for bit and stays
+    within the 2e-3 bar plus one bf16 rounding (2^-9 relative) of the oracle."""
+    b = binding()
+    gen = torch.Generator(device="cpu").manual_seed(d + 7 * g + t)
+    S, n, s, w = 5, 200, 24, 6
+    cent = torch.randn(S, 9, d, generator=gen) * 2.0
+    comp = torch.randint(0, 9, (S, n), generator=gen)
+    K = torch.gather(cent, 1, comp[..., None].expand(S, n, d)) + 0.2 * torch.randn(S, n, d, generator=gen)
+    V = torch.randn(S, n, d, generator=gen)
+    Q = torch.randn(S, n, g, d, generator=gen) / d ** 0.5
+    K, V, Q = (x.to(dtype).to(DEV) for x in (K, V, Q))
+    delta = 0.2 * (2 * d) ** 0.5 * 1.05
+    mk = lambda od: b.SubGen(S, d, delta, s, w, dtype=dtype, q_per_stream=g, seed=3, device=DEV,
+                             kernel_path=kernel_path, t_per_cluster=t, out_dtype=od)
+    lo, hi = mk(torch.bfloat16), mk(torch.float32)
+    oracles = make_oracles(S, d, delta, s, w, seed=3, t=t)
+    Kc, Vc, Qc = to_f32_np(K), to_f32_np(V), to_f32_np(Q)
+    for sg in (lo, hi):
+        sg.ingest_prefix(K[:, :150].contiguous(), V[:, :150].contiguous())
+    for i, o in enumerate(oracles):
+        o.ingest(Kc[i, :150], Vc[i, :150])
+    tol = REL_L2_TOL + 2.0 ** -9
+    for tt in range(150, n):
+        kt, vt, qt = K[:, tt].contiguous(), V[:, tt].contiguous(), Q[:, tt].contiguous()
+        a, c = lo.step(kt, vt, qt), hi.step(kt, vt, qt)
+        assert a.dtype == torch.bfloat16 and c.dtype == torch.float32
+        assert torch.equal(a, c.to(torch.bfloat16)), tt
+        ref = np.stack([o.decode(Kc[i, tt:tt + 1], Vc[i, tt:tt + 1], Qc[i, tt:tt + 1])[0] for i, o in enumerate(oracles)])
+        assert rel_l2(to_f32_np(c), ref).max() <= REL_L2_TOL and rel_l2(to_f32_np(a), ref).max() <= tol, tt
+    qt = Q[:, n - 1].contiguous()
+    assert torch.equal(lo.attend(qt), hi.attend(qt).to(torch.bfloat16))
+    for nq in (3, 21):                                  # grouped decode kernels and the matrix-core block kernel
+        Qm = (torch.randn(S, nq, d, generator=gen) / d ** 0.5).to(dtype).to(DEV)
+        am = lo.attend_many(Qm)
+        assert am.dtype == torch.bfloat16 and torch.equal(am, hi.attend_many(Qm).to(torch.bfloat16)), nq
+    with pytest.raises(ValueError):                     # an fp32 buffer is refused by a bf16-output context
+        lo.attend(qt, torch.empty(S, g, d, dtype=torch.float32, device=DEV))
+    assert compare_state(lo, oracles) == 0 and compare_state(hi, oracles) == 0
+
+
+def test_exact_attend_takes_more_streams_than_one_grid_axis_of_65535():
+    b = binding()
+    gen = torch.Generator(device="cpu").manual_seed(9)
+    S, n, d = 70001, 6, 64
+    K = torch.randn(S, n, d, generator=gen).to(torch.bfloat16).to(DEV)
+    V = torch.randn(S, n, d, generator=gen).to(torch.bfloat16).to(DEV)
+    Q = (torch.randn(S, 1, d, generator=gen) / 4).to(torch.bfloat16).to(DEV)
+    out = b.exact_attend(K, V, Q).cpu().numpy()
+    for i in (0, 1, 65534, 65535, 65536, S - 1):
+        ref = exact_attention(to_f32_np(K[i]), to_f32_np(V[i]), to_f32_np(Q[i, 0]))
+        assert rel_l2(out[i, 0], ref) <= 1e-4, i
