@@ -164,6 +164,8 @@ def main():
                     help="comma-separated query counts: also time subgen_attend_many on the final state")
     ap.add_argument("--t", type=int, default=0, help="per-cluster reservoir slots (0 = representative mode)")
     ap.add_argument("--generic", action="store_true", help="force the generic vector-ALU kernels (kernel_path = 1)")
+    ap.add_argument("--split-workgroups", type=int, default=0,
+                    help="workgroups per stream (0 = the library's choice, 1 = never split, 2..64)")
     ap.add_argument("--no-exact", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=1024)
@@ -213,7 +215,7 @@ def main():
     cpu_idx = torch.tensor(cpu_ids, device=dev, dtype=torch.long)
     mk = lambda log: binding.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=cfg.g,
                                     max_centers=max_centers, seed=0, device=dev, kernel_path=1 if a.generic else 0,
-                                    t_per_cluster=a.t, assign_log_tokens=log)
+                                    t_per_cluster=a.t, assign_log_tokens=log, split_workgroups=a.split_workgroups)
     sg = mk(0)                   # the context that is timed
     # a twin of it that keeps the decision log the parity report needs: same launch shape, same inputs, untimed
     # (the log's scattered stores cost the prefix ingest about 13 %, so the timed context runs without it)

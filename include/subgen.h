@@ -95,6 +95,13 @@ typedef struct subgen_opts {
                                subgen_sync after replaying graphs.  0 (default) = the count is a kernel argument */
     int32_t out_dtype;      /* element type of the attention outputs: SUBGEN_F32 (default; what the 2e-3 parity bar is
                                stated on) or SUBGEN_BF16 (the fp32 result rounded to nearest even at the store)  */
+    int32_t split_workgroups; /* workgroups that share one stream in update / attend / step.  0 = automatic: one per
+                               stream, except in contexts of at most 32 streams (kernel_path 0, representative mode),
+                               where 8 to 32 of them bring the launch to about 256 workgroups: a context of a few
+                               streams would otherwise leave most of the chip idle.  1 = always one per
+                               stream.  2 .. 64 = that many.  State and decisions do not depend on this; outputs
+                               agree to fp32 rounding                                                          */
+    int32_t reserved_;      /* padding: zero */
 } subgen_opts;
 
 /*

@@ -42,7 +42,7 @@ class subgen_opts(C.Structure):
                 ("max_centers", C.c_int32), ("assign_log_tokens", C.c_int64), ("seed", C.c_uint64),
                 ("hip_stream", C.c_void_p), ("device", C.c_int32), ("device_set", C.c_int32),
                 ("kernel_path", C.c_int32), ("t_per_cluster", C.c_int32), ("device_counter", C.c_int32),
-                ("out_dtype", C.c_int32)]
+                ("out_dtype", C.c_int32), ("split_workgroups", C.c_int32), ("reserved_", C.c_int32)]
 
 
 class subgen_stats_t(C.Structure):
@@ -162,7 +162,7 @@ class SubGen:
                  dtype: torch.dtype = torch.float32, q_per_stream: int = 1, max_centers: int = 0,
                  assign_log_tokens: int = 0, seed: int = 0, device: Optional[torch.device] = None,
                  kernel_path: int = 0, t_per_cluster: int = 0, device_counter: bool = False,
-                 out_dtype: torch.dtype = torch.float32):
+                 out_dtype: torch.dtype = torch.float32, split_workgroups: int = 0):
         self._L = load()
         self._h = C.c_void_p()
         if not torch.cuda.is_available():
@@ -190,6 +190,7 @@ class SubGen:
         o.device_counter = 1 if device_counter else 0
         o.t_per_cluster = self.t = int(t_per_cluster)
         o.out_dtype = _dtype_code(out_dtype)
+        o.split_workgroups = int(split_workgroups)
         _check(self._L.subgen_create(C.byref(self._h), self.streams, self.d, C.c_float(self.delta), self.s, self.w,
                                      C.byref(o)), "subgen_create")
 

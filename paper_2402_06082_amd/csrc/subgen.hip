@@ -20,6 +20,7 @@
 #include "subgen_res_device.hpp"
 #include "kcenter_device.hpp"
 #include "attend_many_device.hpp"
+#include "subgen_split_device.hpp"
 
 using sg::Call;
 using sg::State;
@@ -229,10 +230,54 @@ void launch_dot2(Mode mode, dim3 grid, hipStream_t s, const State &st, const Cal
     }
 }
 
+template <bool BF16, int LPR, int G>
+void launch_split_mode(Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    switch (mode) {
+        case MODE_UPDATE:
+            hipLaunchKernelGGL((sg::decode_split_kernel<BF16, LPR, 1, true, false>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+        case MODE_ATTEND:
+            hipLaunchKernelGGL((sg::decode_split_kernel<BF16, LPR, G, false, true>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+        case MODE_STEP:
+            hipLaunchKernelGGL((sg::decode_split_kernel<BF16, LPR, G, true, true>), grid, dim3(sg::kWG), 0, s, st, call);
+            break;
+    }
+}
+
+template <bool BF16, int LPR>
+void launch_split_g(int G, Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
+{
+    if (G == 1) launch_split_mode<BF16, LPR, 1>(mode, grid, s, st, call);
+    else if (G == 2) launch_split_mode<BF16, LPR, 2>(mode, grid, s, st, call);
+    else launch_split_mode<BF16, LPR, 4>(mode, grid, s, st, call);
+}
+
+// contexts of a few streams: split_P workgroups per stream
+void launch_split(subgen_ctx *c, Mode mode, const Call &call, int G)
+{
+    const dim3 grid((unsigned)(c->S * c->st.split_P));
+    if (c->dtype == SUBGEN_BF16) {
+        if (c->LPR == 8) launch_split_g<true, 8>(G, mode, grid, c->stream, c->st, call);
+        else if (c->LPR == 16) launch_split_g<true, 16>(G, mode, grid, c->stream, c->st, call);
+        else launch_split_g<true, 32>(G, mode, grid, c->stream, c->st, call);
+    } else {
+        if (c->LPR == 8) launch_split_g<false, 8>(G, mode, grid, c->stream, c->st, call);
+        else if (c->LPR == 16) launch_split_g<false, 16>(G, mode, grid, c->stream, c->st, call);
+        else launch_split_g<false, 32>(G, mode, grid, c->stream, c->st, call);
+    }
+}
+
 // G = queries per stream of this launch (the context's own, or a group of a many-query call)
 int launch_decode(subgen_ctx *c, Mode mode, const Call &call, int G)
 {
     const dim3 grid((unsigned)c->S);
+    if (c->st.split_P > 1) {
+        launch_split(c, mode, call, G);
+        const hipError_t e = hipGetLastError();
+        return e == hipSuccess ? SUBGEN_OK : fail_hip(c, e);
+    }
     const bool mfma = c->mfma && mfma_supported(c->dtype, c->LPR, G);
     if (c->st.t > 0) {
         launch_res(c, mode, call, G);
@@ -355,6 +400,7 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     if (o.t_per_cluster < 0 || o.t_per_cluster > 64) return SUBGEN_EINVAL;
     if (o.device_counter != 0 && o.device_counter != 1) return SUBGEN_EINVAL;
     if (o.out_dtype != SUBGEN_F32 && o.out_dtype != SUBGEN_BF16) return SUBGEN_EINVAL;
+    if (o.split_workgroups < 0 || o.split_workgroups > 64) return SUBGEN_EINVAL;
 
     subgen_ctx *c = new (std::nothrow) subgen_ctx();
     if (!c) return SUBGEN_ENOMEM;
@@ -373,11 +419,23 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     c->ingest_mfma = o.kernel_path != 1 && o.dtype == SUBGEN_BF16 && (c->LPR == 8 || c->LPR == 16);
     c->wide = o.kernel_path == 0 && streams <= 256;   // measured crossover between 256 and 512 streams
     c->dev_seen = o.device_counter != 0;
+    // a few streams (far fewer than the chip has compute units): several workgroups per stream.  Automatic
+    // choice: up to 32 streams, the power of two that brings the launch to at most 256 workgroups, at most 32 per
+    // stream (measured: 1 stream 38 -> 15 us with 32, 32 streams 17.1 -> 14.8 us with 8; at 4 per stream the
+    // combine costs what the shorter scan saves, so larger contexts keep one workgroup per stream)
+    int32_t split = o.split_workgroups;
+    if (split == 0) {
+        split = 1;
+        if (o.kernel_path == 0 && o.t_per_cluster == 0 && streams <= 32)
+            for (split = 32; split > 8 && split * streams > 256; split /= 2) {}
+    }
+    if (o.t_per_cluster > 0) split = 1;   // per-cluster reservoirs keep one workgroup per stream
 
     State &st = c->st;
     st.Mcap = Mcap; st.s = sample_budget; st.w = window; st.d = d;
     st.t = o.t_per_cluster;
     st.out_bf16 = o.out_dtype == SUBGEN_BF16 ? 1 : 0;
+    st.split_P = split > 1 ? split : 0;
     st.McapS = (Mcap + 15) / 16 * 16; st.sS = (sample_budget + 15) / 16 * 16;
     st.delta2 = (double)delta * (double)delta;
     st.seed_lo = (uint32_t)o.seed; st.seed_hi = (uint32_t)(o.seed >> 32);
@@ -398,6 +456,9 @@ int subgen_create(subgen_ctx **out, int64_t streams, int32_t d, float delta, int
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.mu, S, 0);
     if (rc == SUBGEN_OK) rc = dev_alloc(c, &st.flags, S, 0);
     if (rc == SUBGEN_OK && o.device_counter) rc = dev_alloc(c, &st.seen, 1, 0);
+    if (rc == SUBGEN_OK && st.split_P > 1) rc = dev_alloc(c, &st.split_cnt, S, 0);
+    if (rc == SUBGEN_OK && st.split_P > 1)
+        rc = dev_alloc(c, &st.split_part, S * st.split_P * (size_t)sg::split_partial_floats(4, d), 0);
     if (rc == SUBGEN_OK && st.assign_cap > 0) rc = dev_alloc(c, &st.assign, S * (size_t)st.assign_cap, 0xFF);
     if (rc != SUBGEN_OK) {
         subgen_destroy(c);

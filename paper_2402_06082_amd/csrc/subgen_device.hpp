@@ -52,6 +52,10 @@ struct State {
     uint32_t seed_lo, seed_hi;
     int64_t *seen;      // [1] tokens seen by every stream, kept on the device (contexts made for graph capture), or null
     int32_t out_bf16;   // outputs are written as bf16 (round to nearest even) instead of fp32
+    // contexts of a few streams: split_P workgroups share a stream (0 = one workgroup per stream)
+    int32_t split_P;
+    uint32_t *split_cnt;   // [S]        workgroups of the stream that have arrived in the current launch
+    float *split_part;     // [S][P][.]  their partial results
 };
 
 // Tokens seen before this launch: the host's count (a kernel argument), or, in contexts that keep the count on the

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
 def test_binding_struct_sizes_match_the_header_layout():
     # natural C layout of the three structs in the header (x86-64)
     from paper_2402_06082_amd import binding
-    assert ctypes.sizeof(binding.subgen_opts) == 64
+    assert ctypes.sizeof(binding.subgen_opts) == 72
     assert ctypes.sizeof(binding.subgen_stats_t) == 56
     assert ctypes.sizeof(binding.subgen_state_view) == 144
 
@@ -59,11 +59,15 @@ def test_host_side_argument_checks_need_no_gpu():
     bad = [dict(streams=0), dict(d=100), dict(d=0), dict(delta=-1.0), dict(delta=float("nan")), dict(delta=float("inf")),
            dict(s=0), dict(w=-1), dict(q_per_stream=3), dict(dtype=7), dict(kernel_path=3), dict(t_per_cluster=65),
            dict(t_per_cluster=-1), dict(max_centers=-5), dict(assign_log_tokens=-1), dict(device_counter=2),
-           dict(struct_size=2), dict(struct_size=1000)]
+           dict(struct_size=2), dict(struct_size=1000), dict(out_dtype=2), dict(split_workgroups=65),
+           dict(split_workgroups=-1)]
     for kw in bad:
         assert create(**kw) == -1, kw
         assert not h.value
     assert L.subgen_create(None, 2, 128, C.c_float(1.0), 4, 2, None) == -1
+    # a caller compiled against the 64-byte options struct of an earlier header is still understood
+    if not torch.cuda.is_available():
+        assert create(struct_size=64) in (-2, -3)
     if not torch.cuda.is_available():
         assert create() in (-2, -3)          # valid arguments, no device: an error code, not a crash
         assert not h.value

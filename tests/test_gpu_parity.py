@@ -22,7 +22,7 @@ def binding():
 
 
 def run_config(cfg, streams, delta, prefix, steps, *, fused=True, ingest_chunk=None, oracle_ids=None, seed=0,
-               max_centers=0, kernel_path=0):
+               max_centers=0, kernel_path=0, split=0):
     """Prefix ingest + decode steps on the GPU and in the oracle; returns (gpu outs of the oracle's streams, sg,
     the oracle set).  The caller reconciles (near-tie protocol) and then reads the oracle's outputs."""
     b = binding()
@@ -31,7 +31,7 @@ def run_config(cfg, streams, delta, prefix, steps, *, fused=True, ingest_chunk=N
     ids = list(range(S)) if oracle_ids is None else list(oracle_ids)
     sg = b.SubGen(S, cfg.d, delta, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=cfg.g,
                   max_centers=max_centers, assign_log_tokens=prefix + steps, seed=seed, device=DEV,
-                  kernel_path=kernel_path)
+                  kernel_path=kernel_path, split_workgroups=split)
     oset = OracleSet(ids, cfg.d, delta, cfg.s, cfg.w, seed=seed, max_centers=max_centers)
     chunk = ingest_chunk or 2048
     for t0 in range(0, prefix, chunk):
@@ -77,12 +77,14 @@ def test_cfg1_single_head_fp32(name, fused):
         assert 20 <= m[0] <= 300
 
 
-@pytest.mark.parametrize("kernel_path", [0, 1, 2])
-def test_cfg2_llama_layer_bf16_all_streams(kernel_path):
+@pytest.mark.parametrize("kernel_path,split", [(0, 0), (1, 0), (2, 0), (0, 1)])
+def test_cfg2_llama_layer_bf16_all_streams(kernel_path, split):
+    """32 streams: several workgroups per stream (the automatic choice), the generic kernels, the four-wavefront
+    row kernels, and the wide-workgroup row kernels (automatic path with one workgroup per stream)."""
     from paper_2402_06082_amd.tuning import tune_delta
     cfg = CONFIGS["cfg2"]
     delta, m_probe = tune_delta(cfg, DEV)
-    got, sg, oset = run_config(cfg, None, delta, cfg.prefix, cfg.decode_steps, kernel_path=kernel_path)
+    got, sg, oset = run_config(cfg, None, delta, cfg.prefix, cfg.decode_steps, kernel_path=kernel_path, split=split)
     ties = oset.reconcile(sg)            # near-ties are forced and replayed: every stream is compared to the end
     worst = check_outputs(got, oset.reference())
     st = sg.stats()
@@ -117,11 +119,13 @@ def test_cfg5_shape_gqa_four_queries(kernel_path):
     check_outputs(got2, oset2.reference())
 
 
-def test_cfg4_shape_drift_small():
-    """A few streams of the long-context shape: contexts this small take the wide-workgroup kernels (the
-    four-wavefront ones meet the oracle at the workload's full size in test_gpu_fullsize.py)."""
+@pytest.mark.parametrize("split", [0, 1])
+def test_cfg4_shape_drift_small(split):
+    """A few streams of the long-context shape: contexts this small run several workgroups per stream or, with
+    one workgroup per stream, the wide-workgroup kernels (the four-wavefront ones meet the oracle at the
+    workload's full size in test_gpu_fullsize.py)."""
     cfg = CONFIGS["cfg4"]
-    got, sg, oset = run_config(cfg, 4, 8.3, 4096, 16)
+    got, sg, oset = run_config(cfg, 4, 8.3, 4096, 16, split=split)
     assert oset.reconcile(sg) == 0
     check_outputs(got, oset.reference())
 
@@ -171,7 +175,7 @@ def test_step_equals_update_then_attend(kernel_path):
     K, V = wl.tokens(0, 120)
     Q = wl.queries(0, 120)
     mk = lambda: b.SubGen(wl.S, cfg.d, 8.0, cfg.s, cfg.w, dtype=cfg.torch_dtype, q_per_stream=2, device=DEV,
-                          kernel_path=kernel_path)
+                          kernel_path=kernel_path, split_workgroups=1)
     a, c = mk(), mk()
     for t in range(120):
         kt, vt, qt = K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()
@@ -204,7 +208,8 @@ def test_shapes_and_edge_parameters(dtype, d, s, w, kernel_path):
         pytest.skip("fp32 rows always take the generic kernels")
     if kernel_path == 2 and d != 128:
         pytest.skip("only the row path (bf16, d = 128, one query) has a wide-workgroup variant")
-    sg = b.SubGen(S, d, delta, s, w, dtype=dtype, assign_log_tokens=n, seed=11, device=DEV, kernel_path=kernel_path)
+    sg = b.SubGen(S, d, delta, s, w, dtype=dtype, assign_log_tokens=n, seed=11, device=DEV, kernel_path=kernel_path,
+                  split_workgroups=1)
     oracles = make_oracles(S, d, delta, s, w, seed=11)
     for t in range(n):
         out = sg.step(K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous())
@@ -232,7 +237,7 @@ def test_delta_zero_duplicates_and_center_overflow(dtype, d, g, kernel_path):
 
     def run(max_centers):
         sg = b.SubGen(S, d, 0.0, 8, 0, dtype=dtype, q_per_stream=g, max_centers=max_centers, assign_log_tokens=n,
-                      device=DEV, kernel_path=kernel_path)
+                      device=DEV, kernel_path=kernel_path, split_workgroups=1)
         oracles = make_oracles(S, d, 0.0, 8, 0, max_centers=max_centers)
         sg.ingest_prefix(K[:, :n_ing].contiguous(), V[:, :n_ing].contiguous())
         for i, o in enumerate(oracles):
@@ -282,7 +287,7 @@ def test_nonfinite_tokens_are_dropped_and_flagged(dtype, d, g, kernel_path, t, i
     K, V, Q = (x.to(dtype).to(DEV) for x in (K, V, Q))
     delta = 0.2 * (2 * d) ** 0.5 * 1.05
     sg = b.SubGen(S, d, delta, s, w, dtype=dtype, q_per_stream=g, assign_log_tokens=n, seed=4, device=DEV,
-                  kernel_path=kernel_path, t_per_cluster=t)
+                  kernel_path=kernel_path, t_per_cluster=t, split_workgroups=1)
     oracles = make_oracles(S, d, delta, s, w, seed=4, t=t)
     Kc, Vc, Qc = to_f32_np(K), to_f32_np(V), to_f32_np(Q)
     t0 = 0
@@ -485,7 +490,7 @@ def test_matrix_core_path_exact_decisions_on_lattice_keys(g, d, kernel_path):
     K, V, Q = (t.to(torch.bfloat16).to(DEV) for t in (K, V, Q))
     delta = 1.0                                                            # distances are sqrt(j)/2: 1.0 is hit exactly
     sg = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, q_per_stream=g, assign_log_tokens=n, seed=2, device=DEV,
-                  kernel_path=kernel_path)
+                  kernel_path=kernel_path, split_workgroups=1)     # one workgroup per stream: the families under test
     oracles = make_oracles(S, d, delta, s, w, seed=2)
     outs = torch.stack([sg.step(K[:, t].contiguous(), V[:, t].contiguous(), Q[:, t].contiguous()) for t in range(n)])
     ref = np.stack([o.decode(to_f32_np(K[i]), to_f32_np(V[i]), to_f32_np(Q[i])) for i, o in enumerate(oracles)], 1)
@@ -679,7 +684,8 @@ def test_ingest_window_sizes_and_long_calls(w, s, kernel_path):
                                                      (torch.bfloat16, 128, 4, 0, 0), (torch.bfloat16, 64, 2, 0, 0),
                                                      (torch.bfloat16, 256, 1, 0, 0), (torch.bfloat16, 128, 2, 1, 0),
                                                      (torch.float32, 64, 1, 0, 0), (torch.bfloat16, 128, 1, 0, 2)])
-def test_bf16_outputs_are_the_fp32_outputs_rounded_once(dtype, d, g, kernel_path, t):
+@pytest.mark.parametrize("split", [1, 8])
+def test_bf16_outputs_are_the_fp32_outputs_rounded_once(dtype, d, g, kernel_path, t, split):
     """opts.out_dtype = bf16 in every kernel family (step, attend, attend_many): the stored value is the fp32
     result rounded to nearest even, so it equals the rounded output of an fp32-output twin bit for bit and stays
     within the 2e-3 bar plus one bf16 rounding (2^-9 relative) of the oracle."""
@@ -694,7 +700,7 @@ def test_bf16_outputs_are_the_fp32_outputs_rounded_once(dtype, d, g, kernel_path
     K, V, Q = (x.to(dtype).to(DEV) for x in (K, V, Q))
     delta = 0.2 * (2 * d) ** 0.5 * 1.05
     mk = lambda od: b.SubGen(S, d, delta, s, w, dtype=dtype, q_per_stream=g, seed=3, device=DEV,
-                             kernel_path=kernel_path, t_per_cluster=t, out_dtype=od)
+                             kernel_path=kernel_path, t_per_cluster=t, out_dtype=od, split_workgroups=split)
     lo, hi = mk(torch.bfloat16), mk(torch.float32)
     oracles = make_oracles(S, d, delta, s, w, seed=3, t=t)
     Kc, Vc, Qc = to_f32_np(K), to_f32_np(V), to_f32_np(Q)
