@@ -22,8 +22,10 @@
 // The softmax reference mx is per query and shared by the three kinds of rows; it is raised lazily (only when
 // a score exceeds it by kLazy), and then the accumulators are rescaled.
 //
-// Workgroup = one stream x 16*QT queries; the four wavefronts are QT query tiles x 4/QT row splits.  Every
-// iteration stages 128 rows (four tiles); a wavefront takes the tiles of its row split.
+// Workgroup = one stream x 16*QT*QW queries; the four wavefronts are QT query groups x 4/QT row splits, and a
+// wavefront answers QW tiles of 16 queries with every operand it reads from LDS (QW = 2 for large blocks: the
+// key and value tiles are then read once per 32 queries, which moves the bound from LDS reads to the matrix
+// cores).  Every iteration stages 128 rows (four tiles); a wavefront takes the tiles of its row split.
 #pragma once
 #include <type_traits>
 
@@ -35,7 +37,7 @@ struct ManyCall {
     const char *Q;   // [S][Gm][d] bf16
     float *out;      // [S][Gm][d] fp32
     int32_t Gm;      // queries per stream
-    int32_t tiles;   // workgroups per stream = ceil(Gm / (16 QT))
+    int32_t tiles;   // workgroups per stream = ceil(Gm / (16 QT QW))
     int64_t n_seen;  // tokens seen by every stream
     int64_t streams;
 };
@@ -50,7 +52,7 @@ struct SmemMany {
     float wmx[kWaves][16], wden[kWaves][16];
 };
 
-template <int NK, int QT, bool NT>
+template <int NK, int QT, bool NT, int QW = 1>
 __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, const ManyCall call)
 {
     static_assert(kWaves == 4, "four wavefronts: QT query tiles x 4/QT row splits");
@@ -88,20 +90,26 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
     const int64_t n_evicted = st.w == 0 ? n_seen : (n_seen > st.w ? n_seen - st.w : 0);
     const int fill = (int)(n_seen < st.w ? n_seen : st.w);
 
-    // the wavefront's 16 queries as the B operand of the score contraction
-    const int q0 = (tile * QT + qt) * 16;
-    uint4 Bq[NK];
-    {
-        const int q = q0 + n16 < call.Gm ? q0 + n16 : call.Gm - 1;
+    // the wavefront's QW tiles of 16 queries as the B operands of the score contraction
+    const int q0 = (tile * QT + qt) * QW * 16;
+    uint4 Bq[QW][NK];
+#pragma unroll
+    for (int w2 = 0; w2 < QW; ++w2) {
+        const int q = q0 + w2 * 16 + n16 < call.Gm ? q0 + w2 * 16 + n16 : call.Gm - 1;
         const char *qp = call.Q + (sid * (size_t)call.Gm + q) * ROWB;
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk) Bq[kk] = ld16(qp + (L + 4 * kk) * 16);
+        for (int kk = 0; kk < NK; ++kk) Bq[w2][kk] = ld16(qp + (L + 4 * kk) * 16);
     }
 
-    float mx = -INFINITY, den = 0.f;   // per query n16; mx is the same in the four lanes of a query
-    floatx4_t acc[NCB];                // O[query 4L + r][column 16 cb + n16]
+    float mx[QW], den[QW];             // per query n16 of tile w2; mx is the same in the four lanes of a query
+    floatx4_t acc[QW][NCB];            // O[query 4L + r][column 16 cb + n16]
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) acc[cb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int w2 = 0; w2 < QW; ++w2) {
+        mx[w2] = -INFINITY;
+        den[w2] = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) acc[w2][cb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    }
 
     // kind: 0 = representatives (weight n_i, normaliser only), 1 = sampled pairs (weight mu/(s ||v||^2),
     // numerator only), 2 = window (weight 1, both)
@@ -153,61 +161,76 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
             for (int tt = 0; tt < kTiles / RS; ++tt) {
                 const int t = rs + RS * tt;
                 if (r0 + t * kTileRows >= nrows) break;
-                // ---- scores of the tile's 32 rows against the 16 queries
-                floatx4_t c0 = {0.f, 0.f, 0.f, 0.f}, c1 = {0.f, 0.f, 0.f, 0.f};
+                // ---- scores of the tile's 32 rows against the wavefront's queries (every A operand read from LDS
+                //      serves all QW query tiles)
+                floatx4_t c0[QW], c1[QW];
+#pragma unroll
+                for (int w2 = 0; w2 < QW; ++w2) c0[w2] = c1[w2] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < NK; ++kk) {
                     const uint4 a0 = *reinterpret_cast<const uint4 *>(&sm.kt[t][n16 * KS + (L + 4 * kk) * 16]);
                     const uint4 a1 = *reinterpret_cast<const uint4 *>(&sm.kt[t][(16 + n16) * KS + (L + 4 * kk) * 16]);
-                    c0 = mfma_bf16(a0, Bq[kk], c0);
-                    c1 = mfma_bf16(a1, Bq[kk], c1);
+#pragma unroll
+                    for (int w2 = 0; w2 < QW; ++w2) {
+                        c0[w2] = mfma_bf16(a0, Bq[w2][kk], c0[w2]);
+                        c1[w2] = mfma_bf16(a1, Bq[w2][kk], c1[w2]);
+                    }
                 }
                 const float4 w0 = *reinterpret_cast<const float4 *>(&sm.wrow[t * kTileRows + 4 * L]);
                 const float4 w1 = *reinterpret_cast<const float4 *>(&sm.wrow[t * kTileRows + 16 + 4 * L]);
-                // ---- lazy softmax reference (rows beyond nrows repeat the last row, so every score is a real one)
-                float lm = fmaxf(fmaxf(fmaxf(c0[0], c0[1]), fmaxf(c0[2], c0[3])),
-                                 fmaxf(fmaxf(c1[0], c1[1]), fmaxf(c1[2], c1[3])));
-                if (__any(lm > mx + kLazy || mx == -INFINITY)) {
-                    lm = fmaxf(lm, __shfl_xor(lm, 16));
-                    lm = fmaxf(lm, __shfl_xor(lm, 32));
-                    float scale = 1.f;
-                    if (lm > mx + kLazy || mx == -INFINITY) {
-                        scale = __expf(mx - lm);   // mx = -inf gives 0
-                        den *= scale;
-                        mx = lm;
+                uint4 ah[QW], al[QW];
+#pragma unroll
+                for (int w2 = 0; w2 < QW; ++w2) {
+                    // ---- lazy softmax reference (rows beyond nrows repeat the last row, so every score is a real one)
+                    float lm = fmaxf(fmaxf(fmaxf(c0[w2][0], c0[w2][1]), fmaxf(c0[w2][2], c0[w2][3])),
+                                     fmaxf(fmaxf(c1[w2][0], c1[w2][1]), fmaxf(c1[w2][2], c1[w2][3])));
+                    if (__any(lm > mx[w2] + kLazy || mx[w2] == -INFINITY)) {
+                        lm = fmaxf(lm, __shfl_xor(lm, 16));
+                        lm = fmaxf(lm, __shfl_xor(lm, 32));
+                        float scale = 1.f;
+                        if (lm > mx[w2] + kLazy || mx[w2] == -INFINITY) {
+                            scale = __expf(mx[w2] - lm);   // mx = -inf gives 0
+                            den[w2] *= scale;
+                            mx[w2] = lm;
+                        }
+                        // the accumulators hold queries 4L + r: fetch their factors from the lanes of those queries
+                        float sr[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) sr[r] = __shfl(scale, 4 * L + r);
+#pragma unroll
+                        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) acc[w2][cb][r] *= sr[r];
                     }
-                    // the accumulators hold queries 4L + r: fetch their factors from the lanes of those queries
-                    float sr[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) sr[r] = __shfl(scale, 4 * L + r);
-#pragma unroll
-                    for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[cb][r] *= sr[r];
+                    float e[8];
+                    e[0] = w0.x * __expf(c0[w2][0] - mx[w2]); e[1] = w0.y * __expf(c0[w2][1] - mx[w2]);
+                    e[2] = w0.z * __expf(c0[w2][2] - mx[w2]); e[3] = w0.w * __expf(c0[w2][3] - mx[w2]);
+                    e[4] = w1.x * __expf(c1[w2][0] - mx[w2]); e[5] = w1.y * __expf(c1[w2][1] - mx[w2]);
+                    e[6] = w1.z * __expf(c1[w2][2] - mx[w2]); e[7] = w1.w * __expf(c1[w2][3] - mx[w2]);
+                    if constexpr (TODEN) den[w2] += ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+                    if constexpr (HASV) {
+                        // ---- weights as bf16 hi + lo, in contraction-slot order (slot j <-> e[j])
+                        ah[w2].x = pack_bf16(e[0], e[1]); ah[w2].y = pack_bf16(e[2], e[3]);
+                        ah[w2].z = pack_bf16(e[4], e[5]); ah[w2].w = pack_bf16(e[6], e[7]);
+                        al[w2].x = pack_bf16(e[0] - bf16_lo(ah[w2].x), e[1] - bf16_hi(ah[w2].x));
+                        al[w2].y = pack_bf16(e[2] - bf16_lo(ah[w2].y), e[3] - bf16_hi(ah[w2].y));
+                        al[w2].z = pack_bf16(e[4] - bf16_lo(ah[w2].z), e[5] - bf16_hi(ah[w2].z));
+                        al[w2].w = pack_bf16(e[6] - bf16_lo(ah[w2].w), e[7] - bf16_hi(ah[w2].w));
+                    }
                 }
-                float e[8];
-                e[0] = w0.x * __expf(c0[0] - mx); e[1] = w0.y * __expf(c0[1] - mx);
-                e[2] = w0.z * __expf(c0[2] - mx); e[3] = w0.w * __expf(c0[3] - mx);
-                e[4] = w1.x * __expf(c1[0] - mx); e[5] = w1.y * __expf(c1[1] - mx);
-                e[6] = w1.z * __expf(c1[2] - mx); e[7] = w1.w * __expf(c1[3] - mx);
-                if constexpr (TODEN) den += ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
                 if constexpr (HASV) {
-                    // ---- weights as bf16 hi + lo, in contraction-slot order (slot j <-> e[j])
-                    uint4 ah, al;
-                    ah.x = pack_bf16(e[0], e[1]); ah.y = pack_bf16(e[2], e[3]);
-                    ah.z = pack_bf16(e[4], e[5]); ah.w = pack_bf16(e[6], e[7]);
-                    al.x = pack_bf16(e[0] - bf16_lo(ah.x), e[1] - bf16_hi(ah.x));
-                    al.y = pack_bf16(e[2] - bf16_lo(ah.y), e[3] - bf16_hi(ah.y));
-                    al.z = pack_bf16(e[4] - bf16_lo(ah.z), e[5] - bf16_hi(ah.z));
-                    al.w = pack_bf16(e[6] - bf16_lo(ah.w), e[7] - bf16_hi(ah.w));
+                    // every transposed value operand read from LDS serves all QW query tiles
                     const char *v0 = &sm.vt[t][(4 * L + (n16 >> 2)) * VS + (n16 & 3) * 8];
                     const char *v1 = v0 + 16 * VS;
 #pragma unroll
                     for (int cb = 0; cb < NCB; ++cb) {
                         const u32x2_t b0 = lds_read_tr16(v0 + cb * 32), b1 = lds_read_tr16(v1 + cb * 32);
                         const uint4 b = make_uint4(b0[0], b0[1], b1[0], b1[1]);
-                        acc[cb] = mfma_bf16(ah, b, acc[cb]);
-                        acc[cb] = mfma_bf16(al, b, acc[cb]);
+#pragma unroll
+                        for (int w2 = 0; w2 < QW; ++w2) {
+                            acc[w2][cb] = mfma_bf16(ah[w2], b, acc[w2][cb]);
+                            acc[w2][cb] = mfma_bf16(al[w2], b, acc[w2][cb]);
+                        }
                     }
                 }
             }
@@ -217,39 +240,44 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
     if (n_evicted > 0) scan(std::integral_constant<int, 1>{}, Ks, Vs, st.s);
     if (fill > 0) scan(std::integral_constant<int, 2>{}, Kw, Vw, fill);
 
-    // ---- totals per wavefront, then the row splits of a query tile are merged through LDS
-    den += __shfl_xor(den, 16);
-    den += __shfl_xor(den, 32);
-    __syncthreads();   // the tiles are dead: their memory carries the accumulators
+    // ---- totals per wavefront, then the row splits of a query group are merged through LDS, one query tile of
+    //      the wavefronts at a time (the key tiles' memory carries the accumulators)
     float *const accbuf = reinterpret_cast<float *>(&sm.kt[0][0]);   // [wave][16 queries][D]
     static_assert(sizeof(sm.kt) >= (size_t)kWaves * 16 * D * sizeof(float), "accumulators fit in the key tiles");
-    if (L == 0) {
-        sm.wmx[wave][n16] = mx;
-        sm.wden[wave][n16] = den;
-    }
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) accbuf[((size_t)wave * 16 + 4 * L + r) * D + cb * 16 + n16] = acc[cb][r];
-    __syncthreads();
-    for (int i = tid; i < QT * 16 * D; i += kWG) {
-        const int ql = i / D, c = i % D;       // query of this workgroup, output column
-        const int qtile = ql / 16, qn = ql % 16;
-        const int q = (tile * QT + qtile) * 16 + qn;
-        if (q >= call.Gm) continue;
-        float M = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < RS; ++r) M = fmaxf(M, sm.wmx[qtile + QT * r][qn]);
-        float dn = 0.f, num = 0.f;
-#pragma unroll
-        for (int r = 0; r < RS; ++r) {
-            const int wv = qtile + QT * r;
-            const float wm = sm.wmx[wv][qn];
-            const float sc = (wm == -INFINITY) ? 0.f : __expf(wm - M);
-            dn = fmaf(sm.wden[wv][qn], sc, dn);
-            num = fmaf(accbuf[((size_t)wv * 16 + qn) * D + c], sc, num);
+    for (int w2 = 0; w2 < QW; ++w2) {
+        float dsum = den[w2];
+        dsum += __shfl_xor(dsum, 16);
+        dsum += __shfl_xor(dsum, 32);
+        __syncthreads();   // the tiles (or the previous query tile's accumulators) are dead
+        if (L == 0) {
+            sm.wmx[wave][n16] = mx[w2];
+            sm.wden[wave][n16] = dsum;
         }
-        put_out(st, call.out, (sid * (size_t)call.Gm + q) * D + c, num / dn);
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) accbuf[((size_t)wave * 16 + 4 * L + r) * D + cb * 16 + n16] = acc[w2][cb][r];
+        __syncthreads();
+        for (int i = tid; i < QT * 16 * D; i += kWG) {
+            const int ql = i / D, c = i % D;       // query of this workgroup, output column
+            const int qgrp = ql / 16, qn = ql % 16;
+            const int q = ((tile * QT + qgrp) * QW + w2) * 16 + qn;
+            if (q >= call.Gm) continue;
+            float M = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < RS; ++r) M = fmaxf(M, sm.wmx[qgrp + QT * r][qn]);
+            float dn = 0.f, num = 0.f;
+#pragma unroll
+            for (int r = 0; r < RS; ++r) {
+                const int wv = qgrp + QT * r;
+                const float wm = sm.wmx[wv][qn];
+                const float sc = (wm == -INFINITY) ? 0.f : __expf(wm - M);
+                dn = fmaf(sm.wden[wv][qn], sc, dn);
+                num = fmaf(accbuf[((size_t)wv * 16 + qn) * D + c], sc, num);
+            }
+            put_out(st, call.out, (sid * (size_t)call.Gm + q) * D + c, num / dn);
+        }
     }
 }
 

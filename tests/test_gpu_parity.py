@@ -337,7 +337,7 @@ def test_attend_many_matches_the_oracle_query_by_query(dtype, d, kernel_path, t,
     for i, o in enumerate(oracles):
         o.ingest(Kc[i], Vc[i])
     assert compare_state(sg, oracles) == 0
-    for nq in ([1, 5, 16, 17, 33, 64, 100, 130] if (s, w, n) == (130, 17, 700) else [7, 48]):
+    for nq in ([1, 5, 16, 17, 33, 64, 65, 100, 128, 130, 200, 257, 300] if (s, w, n) == (130, 17, 700) else [7, 48, 97]):
         Q = (torch.randn(S, nq, d, generator=gen) / d ** 0.5 * 2.0).to(dtype).to(DEV)
         out = sg.attend_many(Q).cpu().numpy()
         Qc = to_f32_np(Q)
