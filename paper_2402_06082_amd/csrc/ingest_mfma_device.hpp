@@ -37,10 +37,8 @@ template <int NK>
 struct SmemIngest {
     alignas(16) float nk[kChunkT];
     float vn[kChunkT];
-    // coin threshold and ||v||^2 of the evicted tokens whose coins are still to be drawn (up to kCoinSpan).
-    // The coin u = (r >> 8) 2^-24 of a 32-bit word r is accepted iff u < p; p 2^24 is exact in fp32, so this is
-    // (r >> 8) < ceil(p 2^24), i.e. r <= 256 ceil(p 2^24) - 1 in 32-bit arithmetic (p = 1 wraps to 0xffffffff:
-    // always).  plim holds that bound; 0 stands for p = 0 (never; a bound of a positive p is at least 255).
+    // coin bound (coin_limit: a word r is accepted iff r <= bound; 0 = never) and ||v||^2 of the evicted tokens
+    // whose coins are still to be drawn (up to kCoinSpan)
     uint32_t plim[kCoinSpan];
     float vnall[kCoinSpan];
     float wb1[kWaves][kChunkT], wb2[kWaves][kChunkT];
@@ -139,8 +137,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                     if (lim != 0u) {
                         const uint64_t ge = (uint64_t)(g0 + jj);
                         uint32_t r[4];
-                        philox4x32_10((uint32_t)blk, (uint32_t)ge, (uint32_t)(ge >> 32), (uint32_t)sid, st.seed_lo,
-                                      st.seed_hi, r);
+                        coin_block(st, sid, (int64_t)ge, (uint32_t)blk, false, r);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) last[i] = r[i] <= lim ? jj : last[i];
                     }
@@ -219,7 +216,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 b = group_sum<LPR>(b);
                 // a token with NaN or Inf in it (or a norm beyond fp32) is dropped: it joins nothing, opens
                 // nothing and is never sampled; it is marked by ||k||^2 = +inf, ||v||^2 = 0
-                const bool bad = !((float)a < INFINITY) || !((float)b < INFINITY);
+                const bool bad = !token_is_finite((float)a, (float)b);
                 if (col == 0) {
                     sm.nk[grp + it * RPB] = bad ? INFINITY : (float)a;
                     sm.vn[grp + it * RPB] = bad ? 0.f : (float)b;
@@ -378,9 +375,9 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             const int mcur = m0 + __builtin_popcountll(cmask & below);   // clusters that exist when token j arrives
             const float emax = kDistEps * (nxl + nkj);
             const bool live = valid && j >= done;
-            const bool amb = mcur > 0 && (!(c2 - c1 > 2.f * emax) || !(fabsf(c1 - thr) > emax + 1e-6f * thr));
+            const bool amb = distances_ambiguous(c1, c2, thr, emax, mcur);
             const bool join = mcur > 0 && c1 <= thr;
-            const bool forced = !join && mcur > 0 && mcur >= st.Mcap;
+            const bool forced = decide_cluster(join, ci, mcur, st.Mcap).forced;
             const bool event = live && (amb || (!join && !forced));
             const uint64_t evmask = __ballot(event);
             const int e = evmask ? __builtin_ctzll(evmask) : nt;   // first creation / ambiguous token
@@ -404,10 +401,11 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 exact_nearest<LPR>(X, me, *reinterpret_cast<const uint4 *>(&sm.kt[e * KS + col * 16]), sm.wbest, sm.widx, best,
                               bidx);
                 const bool ejoin = bidx >= 0 && best <= st.delta2;
-                const bool eforced = !ejoin && me > 0 && me >= st.Mcap;
-                if (eforced && bidx < 0) bidx = 0;
-                create = !ejoin && !eforced;
+                const Decision dec = decide_cluster(ejoin, bidx, me, st.Mcap);
+                const bool eforced = dec.forced;
+                create = dec.created;
                 if (!create) {
+                    bidx = dec.target;
                     target = bidx;
                     if (tid == 0) {
                         atomicAdd(&cnt[bidx], 1);
@@ -459,11 +457,10 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 if (prj > 0.f) {
                     const uint64_t ge = (uint64_t)(c0 + jj);
                     uint32_t r[4];
-                    philox4x32_10((uint32_t)b, (uint32_t)ge, (uint32_t)(ge >> 32) | 0x80000000u, (uint32_t)sid,
-                                  st.seed_lo, st.seed_hi, r);
+                    coin_block(st, sid, (int64_t)ge, (uint32_t)b, true, r);
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        if (4 * b + i < TT && (float)(r[i] >> 8) * (1.0f / 16777216.0f) < prj) wbits |= 1u << i;
+                        if (4 * b + i < TT && coin_accepts(r[i], prj)) wbits |= 1u << i;
                 }
                 sm.win[jj][b] = (uint8_t)wbits;
             }
@@ -497,11 +494,8 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                                       ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(vhi, l) << 32);
                 if (l < j) muj += __builtin_bit_cast(double, bits);
             }
-            float pj;
-            if (muj == 0.0) pj = 1.f;
-            else if (vnj == 0.f) pj = 0.f;
-            else pj = (float)((double)vnj / (muj + (double)vnj));
-            sm.plim[span_fill + j] = valid && pj > 0.f ? (uint32_t)ceilf(pj * 16777216.0f) * 256u - 1u : 0u;
+            const float pj = coin_probability(muj, vnj);
+            sm.plim[span_fill + j] = valid ? coin_limit(pj) : 0u;
             sm.vnall[span_fill + j] = vnj;
             const double mend = muj + (double)vnj;
             mu = __shfl(mend, nt - 1);

@@ -102,6 +102,83 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 }
 
 // ---------------------------------------------------------------------------
+// The readings of Algorithm 1 that every kernel family shares, each in one place.
+// ---------------------------------------------------------------------------
+
+// Sliding window (Section 3.2) by deferred insertion: token n goes into ring slot n mod w and the token that was
+// there, n - w, is the one that is clustered and offered to the sampler; with w = 0 the new token itself is
+// (plain Algorithm 1).  slot is -1 when there is no ring.
+struct Eviction {
+    bool evict;       // a token leaves the window in this step
+    int64_t token;    // its index
+    int slot;         // ring slot of the new token (which still holds the leaving token's rows)
+};
+__device__ __forceinline__ Eviction window_push(const int64_t n_seen, const int w)
+{
+    if (w == 0) return Eviction{true, n_seen, -1};
+    return Eviction{n_seen >= w, n_seen - w, (int)(n_seen % w)};
+}
+
+// A token whose ||k||^2 or ||v||^2 (double sums rounded to fp32) is not finite is dropped when it leaves the
+// window: not clustered, not sampled, flag bit 2.
+__device__ __forceinline__ bool token_is_finite(const float kk, const float vn) { return kk < INFINITY && vn < INFINITY; }
+
+// UpdateSoftmaxNormalizer, the decision once the nearest representative is known: `join` says that there is one
+// within delta (||k - x|| <= delta, tested on squared values; lowest index on ties is the caller's argmin rule).
+// Otherwise a new cluster is opened, unless the table is full: then the token joins its nearest cluster
+// regardless of delta (flag bit 1).  bidx < 0 with a full table only happens with non-finite representatives
+// (imported state): cluster 0 takes the token.
+struct Decision {
+    bool created, forced;
+    int target;       // cluster that gains the token (m for a new one)
+};
+__device__ __forceinline__ Decision decide_cluster(const bool join, int bidx, const int m, const int Mcap)
+{
+    if (!join && bidx < 0 && m >= Mcap) bidx = 0;
+    const bool forced = !join && m > 0 && m >= Mcap;
+    const bool created = !join && !forced;
+    return Decision{created, forced, created ? m : bidx};
+}
+
+// Approximate squared distances D~ (error at most emax each) decide only when both the best / runner-up gap and
+// the distance to the threshold exceed their error; otherwise the caller re-evaluates exactly in double.
+__device__ __forceinline__ bool distances_ambiguous(const float b1, const float b2, const float thr, const float emax,
+                                                    const int m)
+{
+    return m > 0 && (!(b2 - b1 > 2.f * emax) || !(fabsf(b1 - thr) > emax + 1e-6f * thr));
+}
+
+// UpdateMatrixProduct: probability of the coin of every slot, p = ||v||^2 / (mu + ||v||^2) with the mu from
+// before this token, rounded to fp32; mu = 0 gives 1 (the first token fills all slots), a zero-norm value 0.
+__device__ __forceinline__ float coin_probability(const double mu, const float vn)
+{
+    if (mu == 0.0) return 1.f;
+    if (vn == 0.f) return 0.f;
+    return (float)((double)vn / (mu + (double)vn));
+}
+
+// The coins: slot j of token t of stream sid takes word j mod 4 of the Philox block with counter
+// (j div 4, t lo, t hi, sid) and the seed as key; the reservoir coins of a cluster (t >= 1 slots per cluster) use
+// the same generator with the top bit of the third counter word set.  u = (word >> 8) 2^-24; accepted iff u < p.
+__device__ __forceinline__ void coin_block(const State &st, const size_t sid, const int64_t token, const uint32_t block,
+                                           const bool reservoir, uint32_t (&r)[4])
+{
+    philox4x32_10(block, (uint32_t)token, (uint32_t)((uint64_t)token >> 32) | (reservoir ? 0x80000000u : 0u),
+                  (uint32_t)sid, st.seed_lo, st.seed_hi, r);
+}
+__device__ __forceinline__ bool coin_accepts(const uint32_t word, const float p)
+{
+    return (float)(word >> 8) * (1.0f / 16777216.0f) < p;
+}
+// The same test in integer form, for loops that draw many coins against one p: p 2^24 is exact in fp32, so
+// u < p  <=>  (word >> 8) < ceil(p 2^24)  <=>  word <= 256 ceil(p 2^24) - 1 in 32-bit arithmetic (p = 1 wraps to
+// 0xffffffff: always).  0 stands for p = 0 (never; the bound of a positive p is at least 255).
+__device__ __forceinline__ uint32_t coin_limit(const float p)
+{
+    return p > 0.f ? (uint32_t)ceilf(p * 16777216.0f) * 256u - 1u : 0u;
+}
+
+// ---------------------------------------------------------------------------
 // 16-byte row chunks
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ uint4 ld16(const char *p) { return *reinterpret_cast<const uint4 *>(p); }
@@ -261,17 +338,16 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
     int64_t etoken = 0;
     uint4 ek = make_uint4(0, 0, 0, 0), ev = make_uint4(0, 0, 0, 0);
     if constexpr (UPD) {
-        if (st.w == 0) {
-            evict = true;
-            etoken = n_seen;
+        const Eviction wp = window_push(n_seen, st.w);
+        evict = wp.evict;
+        etoken = wp.token;
+        if (wp.slot < 0) {
             ek = ld16(krow + col * 16);
             ev = ld16(vrow + col * 16);
         } else {
-            const int slot = (int)(n_seen % st.w);
+            const int slot = wp.slot;
             char *kw = Kw + (size_t)slot * ROWB, *vw = Vw + (size_t)slot * ROWB;
-            if (n_seen >= st.w) {
-                evict = true;
-                etoken = n_seen - st.w;
+            if (evict) {
                 ek = ld16(kw + col * 16);
                 ev = ld16(vw + col * 16);
             }
@@ -311,7 +387,7 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
             }
             kk2 = group_sum<LPR>(kk2);
             vn = (float)group_sum<LPR>(vv2);
-            if (evict && (!((float)kk2 < INFINITY) || !(vn < INFINITY))) {
+            if (evict && !token_is_finite((float)kk2, vn)) {
                 evict = false;
                 if (tid == 0) st.flags[sid] |= 2u;
             }
@@ -435,10 +511,9 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
             }
             // ---- join iff ||k - x_i*||^2 <= delta^2, else open a cluster (or force-join when full)
             const bool join = bidx >= 0 && best <= st.delta2;
-            if (!join && bidx < 0 && m >= st.Mcap) bidx = 0;   // only with non-finite representatives (imported state)
-            const bool forced = !join && bidx >= 0 && m >= st.Mcap;
-            const bool created = !join && !forced;
-            const int target = created ? m : bidx;
+            const Decision dec = decide_cluster(join, bidx, m, st.Mcap);
+            const bool forced = dec.forced, created = dec.created;
+            const int target = dec.target;
             if (created) {
                 if (tid < LPR) st16(X + (size_t)m * ROWB + tid * 16, ek);
                 if (tid == 0) {
@@ -466,10 +541,7 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
             if (created) m += 1;
 
             // ---- sampling update: p from the old mu, one coin per slot, then mu += ||v||^2
-            float p;
-            if (mu == 0.0) p = 1.f;
-            else if (vn == 0.f) p = 0.f;
-            else p = (float)((double)vn / (mu + (double)vn));
+            const float p = coin_probability(mu, vn);
 
             for (int base = 0; base < st.s; base += kQueue) {
                 if (tid == 0) sm.qn = 0;
@@ -477,12 +549,10 @@ __device__ __forceinline__ void token_step(const State &st, const size_t sid, co
                 const int j0 = base + tid * 4;
                 if (j0 < st.s && p > 0.f) {
                     uint32_t r[4];
-                    philox4x32_10((uint32_t)(j0 >> 2), (uint32_t)etoken, (uint32_t)((uint64_t)etoken >> 32),
-                                  (uint32_t)sid, st.seed_lo, st.seed_hi, r);
+                    coin_block(st, sid, etoken, (uint32_t)(j0 >> 2), false, r);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float u = (float)(r[i] >> 8) * (1.0f / 16777216.0f);
-                        if (j0 + i < st.s && u < p) sm.queue[atomicAdd(&sm.qn, 1)] = j0 + i;
+                        if (j0 + i < st.s && coin_accepts(r[i], p)) sm.queue[atomicAdd(&sm.qn, 1)] = j0 + i;
                     }
                 }
                 __syncthreads();

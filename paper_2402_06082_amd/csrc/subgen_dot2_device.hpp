@@ -82,17 +82,13 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
     float nk = 0.f, vn = 0.f;
     if constexpr (UPD) {
         const char *esk = krow, *esv = vrow;
-        if (st.w == 0) {
-            evict = true;
-            etoken = n_seen;
-        } else {
-            wslot = (int)(n_seen % st.w);
+        const Eviction wp = window_push(n_seen, st.w);
+        evict = wp.evict;
+        etoken = wp.token;
+        wslot = wp.slot;
+        if (wslot >= 0) {
             esk = Kw + (size_t)wslot * ROWB;
             esv = Vw + (size_t)wslot * ROWB;
-            if (n_seen >= st.w) {
-                evict = true;
-                etoken = n_seen - st.w;
-            }
         }
         if (evict) {
             ek = ld16(esk + col * 16);
@@ -123,7 +119,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             }
             nk = (float)group_sum<LPR>(a);
             vn = (float)group_sum<LPR>(b);
-            if (!(nk < INFINITY) || !(vn < INFINITY)) {   // NaN or Inf in the token: it is dropped and flagged
+            if (!token_is_finite(nk, vn)) {   // NaN or Inf in the token: it is dropped and flagged
                 evict = false;
                 if (tid == 0) st.flags[sid] |= 2u;
             }
@@ -264,7 +260,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             const float emax = kDistEps * (nxmax + nk);
             bool join;
             int bidx = i1;
-            const bool ambiguous = m > 0 && (!(b2 - b1 > 2.f * emax) || !(fabsf(b1 - thr) > emax + 1e-6f * thr));
+            const bool ambiguous = distances_ambiguous(b1, b2, thr, emax, m);
             if (ambiguous) {
                 double best;
                 exact_nearest<LPR, NW>(X, m, ek, sm.wbest, sm.widx, best, bidx);
@@ -272,10 +268,9 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
             } else {
                 join = m > 0 && b1 <= thr;
             }
-            if (!join && bidx < 0 && m >= st.Mcap) bidx = 0;   // only with non-finite representatives (imported state)
-            const bool forced = !join && m > 0 && m >= st.Mcap;
-            const bool created = !join && !forced;
-            const int target = created ? m : bidx;
+            const Decision dec = decide_cluster(join, bidx, m, st.Mcap);
+            const bool forced = dec.forced, created = dec.created;
+            const int target = dec.target;
             if constexpr (ATT) {
                 // the cluster that gained this token adds one more term to the normaliser: its row is only
                 // requested here, the product waits until the row has landed (before the final merge)
@@ -295,20 +290,15 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
 
             // ---- sampling update: p from the old mu, one coin per slot, then mu += ||v||^2.  Accepts are rare
             //      (about s/n per token), so the lane that draws one copies the two rows itself.
-            float p;
-            if (mu == 0.0) p = 1.f;
-            else if (vn == 0.f) p = 0.f;
-            else p = (float)((double)vn / (mu + (double)vn));
+            const float p = coin_probability(mu, vn);
             if (p > 0.f) {
                 for (int j0 = tid * 4; j0 < st.s; j0 += WG * 4) {
                     uint32_t r[4];
-                    philox4x32_10((uint32_t)(j0 >> 2), (uint32_t)etoken, (uint32_t)((uint64_t)etoken >> 32),
-                                  (uint32_t)sid, st.seed_lo, st.seed_hi, r);
+                    coin_block(st, sid, etoken, (uint32_t)(j0 >> 2), false, r);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float u = (float)(r[i] >> 8) * (1.0f / 16777216.0f);
                         const int j = j0 + i;
-                        if (j < st.s && u < p) {
+                        if (j < st.s && coin_accepts(r[i], p)) {
                             for (int ch = 0; ch < 16; ++ch) {
                                 st16(Ks + (size_t)j * ROWB + ch * 16, sm.ekrow[ch]);
                                 st16(Vs + (size_t)j * ROWB + ch * 16, sm.evrow[ch]);

@@ -52,19 +52,14 @@ __device__ __forceinline__ void token_step_res(const State &st, const size_t sid
         uint4 ek = make_uint4(0, 0, 0, 0), ev = make_uint4(0, 0, 0, 0);
         const char *esk = krow, *esv = vrow;
         char *kw = nullptr, *vw = nullptr;
-        if (st.w == 0) {
-            evict = true;
-            etoken = n_seen;
-        } else {
-            const int slot = (int)(n_seen % st.w);
-            kw = Kw + (size_t)slot * ROWB;
-            vw = Vw + (size_t)slot * ROWB;
+        const Eviction wp = window_push(n_seen, st.w);
+        evict = wp.evict;
+        etoken = wp.token;
+        if (wp.slot >= 0) {
+            kw = Kw + (size_t)wp.slot * ROWB;
+            vw = Vw + (size_t)wp.slot * ROWB;
             esk = kw;
             esv = vw;
-            if (n_seen >= st.w) {
-                evict = true;
-                etoken = n_seen - st.w;
-            }
         }
         if (evict) {
             ek = ld16(esk + col * 16);
@@ -94,7 +89,7 @@ __device__ __forceinline__ void token_step_res(const State &st, const size_t sid
             }
             kk2 = group_sum<LPR>(kk2);
             vn = (float)group_sum<LPR>(vv2);
-            if (evict && (!((float)kk2 < INFINITY) || !(vn < INFINITY))) {   // NaN or Inf in the token: dropped and flagged
+            if (evict && !token_is_finite((float)kk2, vn)) {   // NaN or Inf in the token: dropped and flagged
                 evict = false;
                 if (tid == 0) st.flags[sid] |= 2u;
             }
@@ -155,10 +150,9 @@ __device__ __forceinline__ void token_step_res(const State &st, const size_t sid
             }
             // ---- join (count bump + reservoir coins) or open a cluster (t copies of the key)
             const bool join = bidx >= 0 && best <= st.delta2;
-            if (!join && bidx < 0 && m >= st.Mcap) bidx = 0;   // only with non-finite representatives (imported state)
-            const bool forced = !join && bidx >= 0 && m >= st.Mcap;
-            const bool created = !join && !forced;
-            const int target = created ? m : bidx;
+            const Decision dec = decide_cluster(join, bidx, m, st.Mcap);
+            const bool forced = dec.forced, created = dec.created;
+            const int target = dec.target;
             const int nnew = created ? 1 : cnt[target] + 1;   // read by every lane before lane 0 writes it
             __syncthreads();
             if (tid == 0) {
@@ -172,13 +166,11 @@ __device__ __forceinline__ void token_step_res(const State &st, const size_t sid
                 const float pr = 1.0f / (float)nnew;   // 1 for a new cluster: every slot takes the key
                 for (int j0 = tid * 4; j0 < T; j0 += kWG * 4) {
                     uint32_t r[4];
-                    philox4x32_10((uint32_t)(j0 >> 2), (uint32_t)etoken, (uint32_t)((uint64_t)etoken >> 32) | 0x80000000u,
-                                  (uint32_t)sid, st.seed_lo, st.seed_hi, r);
+                    coin_block(st, sid, etoken, (uint32_t)(j0 >> 2), true, r);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float u = (float)(r[i] >> 8) * (1.0f / 16777216.0f);
                         const int j = j0 + i;
-                        if (j < T && (created || u < pr)) {
+                        if (j < T && (created || coin_accepts(r[i], pr))) {
                             for (int ch = 0; ch < LPR; ++ch)
                                 st16(R + ((size_t)target * T + j) * ROWB + ch * 16, sm.ekrow[ch]);
                         }
@@ -188,20 +180,15 @@ __device__ __forceinline__ void token_step_res(const State &st, const size_t sid
             if (created) m += 1;
 
             // ---- sampling update: p from the old mu, one coin per slot, then mu += ||v||^2
-            float p;
-            if (mu == 0.0) p = 1.f;
-            else if (vn == 0.f) p = 0.f;
-            else p = (float)((double)vn / (mu + (double)vn));
+            const float p = coin_probability(mu, vn);
             if (p > 0.f) {
                 for (int j0 = tid * 4; j0 < st.s; j0 += kWG * 4) {
                     uint32_t r[4];
-                    philox4x32_10((uint32_t)(j0 >> 2), (uint32_t)etoken, (uint32_t)((uint64_t)etoken >> 32),
-                                  (uint32_t)sid, st.seed_lo, st.seed_hi, r);
+                    coin_block(st, sid, etoken, (uint32_t)(j0 >> 2), false, r);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float u = (float)(r[i] >> 8) * (1.0f / 16777216.0f);
                         const int j = j0 + i;
-                        if (j < st.s && u < p) {
+                        if (j < st.s && coin_accepts(r[i], p)) {
                             for (int ch = 0; ch < LPR; ++ch) {
                                 st16(Ks + (size_t)j * ROWB + ch * 16, sm.ekrow[ch]);
                                 st16(Vs + (size_t)j * ROWB + ch * 16, sm.evrow[ch]);

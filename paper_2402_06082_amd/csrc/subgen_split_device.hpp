@@ -74,19 +74,16 @@ __global__ __launch_bounds__(kWG) void decode_split_kernel(const State st, const
     if constexpr (UPD) {
         kn = ld16(call.K + sid * call.stream_stride + col * 16);
         vnw = ld16(call.V + sid * call.stream_stride + col * 16);
-        if (st.w == 0) {
-            evict = true;
-            etoken = n_seen;
+        const Eviction e = window_push(n_seen, st.w);
+        evict = e.evict;
+        etoken = e.token;
+        wslot = e.slot;
+        if (wslot < 0) {
             ek = kn;
             ev = vnw;
-        } else {
-            wslot = (int)(n_seen % st.w);
-            if (n_seen >= st.w) {
-                evict = true;
-                etoken = n_seen - st.w;
-                ek = ld16(Kw + (size_t)wslot * ROWB + col * 16);
-                ev = ld16(Vw + (size_t)wslot * ROWB + col * 16);
-            }
+        } else if (evict) {
+            ek = ld16(Kw + (size_t)wslot * ROWB + col * 16);
+            ev = ld16(Vw + (size_t)wslot * ROWB + col * 16);
         }
     }
     const int64_t n_after = UPD ? n_seen + 1 : n_seen;
@@ -158,7 +155,7 @@ __global__ __launch_bounds__(kWG) void decode_split_kernel(const State st, const
         }
         kk2 = group_sum<LPR>(kk2);
         vn = (float)group_sum<LPR>(vv2);
-        if (evict && (!((float)kk2 < INFINITY) || !(vn < INFINITY))) {   // NaN or Inf: the token is dropped
+        if (evict && !token_is_finite((float)kk2, vn)) {   // NaN or Inf: the token is dropped
             evict = false;
             dropped = true;
         }
@@ -173,12 +170,7 @@ __global__ __launch_bounds__(kWG) void decode_split_kernel(const State st, const
         }
     }
     // coin probability from the mu before this token; mu after it (the weight of the sampled pairs uses that)
-    float pcoin = 0.f;
-    if (evict) {
-        if (mu == 0.0) pcoin = 1.f;
-        else if (vn == 0.f) pcoin = 0.f;
-        else pcoin = (float)((double)vn / (mu + (double)vn));
-    }
+    const float pcoin = evict ? coin_probability(mu, vn) : 0.f;
     const double mu_after = evict ? mu + (double)vn : mu;
 
     Partial<VEC> part[G];
@@ -258,10 +250,9 @@ __global__ __launch_bounds__(kWG) void decode_split_kernel(const State st, const
                 if constexpr (UPD) {
                     if (valid && pcoin > 0.f) {
                         uint32_t rnd[4];
-                        philox4x32_10((uint32_t)(r >> 2), (uint32_t)etoken, (uint32_t)((uint64_t)etoken >> 32),
-                                      (uint32_t)sid, st.seed_lo, st.seed_hi, rnd);
+                        coin_block(st, sid, etoken, (uint32_t)(r >> 2), false, rnd);
                         const uint32_t word = (r & 3) == 0 ? rnd[0] : (r & 3) == 1 ? rnd[1] : (r & 3) == 2 ? rnd[2] : rnd[3];
-                        take = (float)(word >> 8) * (1.0f / 16777216.0f) < pcoin;
+                        take = coin_accepts(word, pcoin);
                         if (take) {
                             st16(Ks + (size_t)r * ROWB + col * 16, ek);
                             st16(Vs + (size_t)r * ROWB + col * 16, ev);
@@ -493,10 +484,10 @@ __global__ __launch_bounds__(kWG) void decode_split_kernel(const State st, const
             int gi = ci;
             // join iff ||k - x_i*||^2 <= delta^2, else open a cluster (or force-join when the table is full)
             const bool join = gi >= 0 && gb <= st.delta2;
-            if (!join && gi < 0 && m >= st.Mcap) gi = 0;   // only with non-finite representatives (imported state)
-            const bool forced = !join && gi >= 0 && m >= st.Mcap;
-            created = !join && !forced;
-            const int target = created ? m : gi;
+            const Decision dec = decide_cluster(join, gi, m, st.Mcap);
+            const bool forced = dec.forced;
+            created = dec.created;
+            const int target = dec.target;
             if (created) {
                 if (tid < LPR) st16(X + (size_t)m * ROWB + tid * 16, ek);   // lane tid < LPR holds chunk tid of the row
                 if (tid == 0) {

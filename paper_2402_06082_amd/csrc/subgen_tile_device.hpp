@@ -130,19 +130,14 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
     if constexpr (UPD) {
         const char *esk = krow, *esv = vrow;
         char *kw = nullptr, *vw = nullptr;
-        if (st.w == 0) {
-            evict = true;
-            etoken = n_seen;
-        } else {
-            const int slot = (int)(n_seen % st.w);
-            kw = Kw + (size_t)slot * ROWB;
-            vw = Vw + (size_t)slot * ROWB;
+        const Eviction wp = window_push(n_seen, st.w);
+        evict = wp.evict;
+        etoken = wp.token;
+        if (wp.slot >= 0) {
+            kw = Kw + (size_t)wp.slot * ROWB;
+            vw = Vw + (size_t)wp.slot * ROWB;
             esk = kw;
             esv = vw;
-            if (n_seen >= st.w) {
-                evict = true;
-                etoken = n_seen - st.w;
-            }
         }
         if (tid < LPR) {
             if (evict) {
@@ -178,7 +173,7 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
             }
             nk = (float)group_sum<LPR>(a);
             vn = (float)group_sum<LPR>(b);
-            if (!(nk < INFINITY) || !(vn < INFINITY)) {   // NaN or Inf in the token: dropped and flagged
+            if (!token_is_finite(nk, vn)) {   // NaN or Inf in the token: dropped and flagged
                 evict = false;
                 if (tid == 0) st.flags[sid] |= 2u;
                 return;
@@ -416,7 +411,7 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
             const float emax = kDistEps * (nxmax + nk);
             bool join;
             int bidx = i1;
-            const bool ambiguous = m > 0 && (!(b2 - b1 > 2.f * emax) || !(fabsf(b1 - thr) > emax + 1e-6f * thr));
+            const bool ambiguous = distances_ambiguous(b1, b2, thr, emax, m);
             if (ambiguous) {
                 double best;
                 exact_nearest<LPR>(X, m, ek, sm.wbest, sm.widx, best, bidx);
@@ -424,10 +419,9 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
             } else {
                 join = m > 0 && b1 <= thr;
             }
-            if (!join && bidx < 0 && m >= st.Mcap) bidx = 0;   // only with non-finite representatives (imported state)
-            const bool forced = !join && m > 0 && m >= st.Mcap;
-            const bool created = !join && !forced;
-            const int target = created ? m : bidx;
+            const Decision dec = decide_cluster(join, bidx, m, st.Mcap);
+            const bool forced = dec.forced, created = dec.created;
+            const int target = dec.target;
             // the cluster table itself is written at the very end of the kernel: nothing below reads it, and a
             // barrier in between would have to wait for those stores to be acknowledged
             decided = true;
@@ -445,21 +439,16 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
             if (created) m += 1;
 
             // ---- sampling update: p from the old mu, one coin per slot, then mu += ||v||^2
-            float p;
-            if (mu == 0.0) p = 1.f;
-            else if (vn == 0.f) p = 0.f;
-            else p = (float)((double)vn / (mu + (double)vn));
+            const float p = coin_probability(mu, vn);
             // accepts are rare (about s/n per token), so the lane that draws one copies the two rows itself
             if (p > 0.f) {
                 for (int j0 = tid * 4; j0 < st.s; j0 += kWG * 4) {
                     uint32_t r[4];
-                    philox4x32_10((uint32_t)(j0 >> 2), (uint32_t)etoken, (uint32_t)((uint64_t)etoken >> 32),
-                                  (uint32_t)sid, st.seed_lo, st.seed_hi, r);
+                    coin_block(st, sid, etoken, (uint32_t)(j0 >> 2), false, r);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float u = (float)(r[i] >> 8) * (1.0f / 16777216.0f);
                         const int j = j0 + i;
-                        if (j < st.s && u < p) {
+                        if (j < st.s && coin_accepts(r[i], p)) {
                             for (int ch = 0; ch < CPR; ++ch) {
                                 st16(Ks + (size_t)j * ROWB + ch * 16, sm.ekrow[ch]);
                                 st16(Vs + (size_t)j * ROWB + ch * 16, sm.evrow[ch]);
