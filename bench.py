@@ -162,6 +162,9 @@ def main():
     ap.add_argument("--split", action="store_true", help="time subgen_update + subgen_attend instead of subgen_step")
     ap.add_argument("--many", type=str, default="",
                     help="comma-separated query counts: also time subgen_attend_many on the final state")
+    ap.add_argument("--kcenter", type=str, default="",
+                    help="n,k,r,streams: also time the one-shot greedy k-center compression (Section 3.2 variant) of "
+                         "7B-shaped caches of n tokens to k centers + r recent tokens")
     ap.add_argument("--t", type=int, default=0, help="per-cluster reservoir slots (0 = representative mode)")
     ap.add_argument("--generic", action="store_true", help="force the generic vector-ALU kernels (kernel_path = 1)")
     ap.add_argument("--split-workgroups", type=int, default=0,
@@ -425,6 +428,20 @@ def main():
     torch.cuda.synchronize()
     ceiling = probe_bytes / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
     del pbuf
+    kcenter = None
+    if a.kcenter:
+        kn, kk_, kr, ks = [int(x) for x in a.kcenter.split(",")]
+        kwl = Workload(CONFIGS["cfg2"].scaled(kv_heads=ks), device=dev)
+        Kc, Vc = kwl.tokens(0, kn)
+        binding.kcenter_compress(Kc[:8].contiguous(), Vc[:8].contiguous(), 16, 4)      # warm-up
+        torch.cuda.synchronize()
+        tk = time.perf_counter()
+        binding.kcenter_compress(Kc, Vc, kk_, kr)
+        torch.cuda.synchronize()
+        tk = time.perf_counter() - tk
+        kcenter = {"n": kn, "k": kk_, "r": kr, "streams": ks, "d": 128, "dtype": "bf16", "seconds": tk,
+                   "token_center_pairs_per_s": ks * (kn - kr) * kk_ / tk}
+        del Kc, Vc
     setup_s = time.perf_counter() - t_setup
 
     cpu = parity = None
@@ -489,6 +506,8 @@ def main():
         result["entry_points"] = parts
     if many is not None:
         result["attend_many"] = many
+    if kcenter is not None:
+        result["kcenter_compress"] = kcenter
     print(json.dumps(result))
     return 0
 

@@ -682,7 +682,7 @@ size_t subgen_kcenter_workspace_bytes(int64_t streams, int64_t n, int32_t r)
 {
     if (streams < 1 || n < 1 || r < 0) return 0;
     const int64_t nold = n > r ? n - r : 1;
-    return (size_t)streams * (size_t)nold * (sizeof(double) + sizeof(int32_t)) + 256;
+    return (size_t)streams * (size_t)nold * (sizeof(double) + sizeof(int32_t) + sizeof(float)) + 256;
 }
 
 int subgen_kcenter_compress(const void *K, const void *V, int64_t streams, int64_t n, int32_t d, int32_t dtype, int32_t k,
@@ -704,13 +704,14 @@ int subgen_kcenter_compress(const void *K, const void *V, int64_t streams, int64
     c.out_idx = out_idx; c.out_counts = out_counts; c.n = n; c.k = k; c.r = r;
     c.mind = (double *)workspace;
     c.assign = (int32_t *)((char *)workspace + (size_t)streams * (size_t)nold * sizeof(double));
+    c.xnorm = (float *)((char *)c.assign + (size_t)streams * (size_t)nold * sizeof(int32_t));
     hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
     const dim3 grid((unsigned)streams), block(sg::kWG);
     const int LPR = d * esz / 16;
-    if (dtype == SUBGEN_BF16) {
-        if (LPR == 8) hipLaunchKernelGGL((sg::kcenter_kernel<true, 8>), grid, block, 0, s, c);
-        else if (LPR == 16) hipLaunchKernelGGL((sg::kcenter_kernel<true, 16>), grid, block, 0, s, c);
-        else hipLaunchKernelGGL((sg::kcenter_kernel<true, 32>), grid, block, 0, s, c);
+    if (dtype == SUBGEN_BF16) {   // several centers per pass over the keys, approximate distances as a filter
+        if (LPR == 8) hipLaunchKernelGGL((sg::kcenter_batched_kernel<8>), grid, block, 0, s, c);
+        else if (LPR == 16) hipLaunchKernelGGL((sg::kcenter_batched_kernel<16>), grid, block, 0, s, c);
+        else hipLaunchKernelGGL((sg::kcenter_batched_kernel<32>), grid, block, 0, s, c);
     } else {
         if (LPR == 8) hipLaunchKernelGGL((sg::kcenter_kernel<false, 8>), grid, block, 0, s, c);
         else if (LPR == 16) hipLaunchKernelGGL((sg::kcenter_kernel<false, 16>), grid, block, 0, s, c);

@@ -621,7 +621,9 @@ def test_reservoir_mode_matches_the_oracle(dtype, d, g, t):
 
 
 @pytest.mark.parametrize("dtype,d,n,k,r", [(torch.bfloat16, 128, 700, 48, 16), (torch.float32, 64, 333, 20, 0),
-                                           (torch.bfloat16, 64, 40, 64, 8), (torch.bfloat16, 256, 5, 3, 9)])
+                                           (torch.bfloat16, 64, 40, 64, 8), (torch.bfloat16, 256, 5, 3, 9),
+                                           (torch.bfloat16, 128, 3000, 1300, 100), (torch.bfloat16, 64, 1500, 1499, 0),
+                                           (torch.bfloat16, 256, 900, 333, 7)])
 def test_greedy_kcenter_compression_matches_the_oracle(dtype, d, n, k, r):
     """One-shot greedy k-center compression (Section 3.2): selected indices, cluster sizes and the compressed
     rows are bit-exact; attention over the compressed cache equals textbook attention over the same rows."""
@@ -647,6 +649,26 @@ def test_greedy_kcenter_compression_matches_the_oracle(dtype, d, n, k, r):
         out = b.exact_attend(oK, oV, Q).cpu().numpy()
         ref = np.stack([[exact_attention(to_f32_np(oK[i]), to_f32_np(oV[i]), to_f32_np(Q[i, 0]))] for i in range(wl.S)])
         assert rel_l2(out, ref).max() <= 1e-4
+
+
+def test_greedy_kcenter_with_duplicates_and_lattice_ties():
+    """Many identical keys and keys on a coarse lattice: distances tie exactly all the time (also at zero), so the
+    lowest-index rule and the several-centers-per-pass selection are exercised where they are most fragile."""
+    from oracle.subgen_oracle import kcenter_compress as oracle_compress
+    b = binding()
+    gen = torch.Generator(device="cpu").manual_seed(21)
+    S, n, d = 3, 600, 128
+    K = torch.randint(-1, 2, (S, n, d), generator=gen).float() * 0.5
+    K[:, :, 6:] = 0.0                                   # 3^6 = 729 possible keys: plenty of duplicates among 600
+    K[1, 100:400] = K[1, 7]                             # a long run of one key
+    V = torch.randn(S, n, d, generator=gen)
+    K, V = K.to(torch.bfloat16).to(DEV), V.to(torch.bfloat16).to(DEV)
+    for k, r in [(40, 10), (500, 0), (600, 3)]:
+        oK, oV, idx, counts = b.kcenter_compress(K, V, k, r)
+        for i in range(S):
+            ridx, rcounts = oracle_compress(to_f32_np(K[i]), to_f32_np(V[i]), k, r)
+            assert np.array_equal(idx[i].cpu().numpy(), ridx), (k, r, i)
+            assert np.array_equal(counts[i].cpu().numpy(), rcounts), (k, r, i)
 
 
 @pytest.mark.parametrize("w,s", [(0, 8), (100, 64), (1, 3), (300, 130)])
