@@ -236,7 +236,9 @@ def main():
         Kall = torch.empty(S, a.prefix, cfg.d, dtype=cfg.torch_dtype, device=dev)
         Vall = torch.empty_like(Kall)
     torch.cuda.synchronize()
-    ingest_s = 0.0
+    # the ingest launches are timed with HIP events on the stream they run on (the token generator's kernels run
+    # right before them on the same stream, so the GPU never idles between a chunk's generation and its ingest)
+    ing_ev = []
     chunk = 4 * BLOCK
     for t0 in range(0, a.prefix, chunk):
         t1 = min(a.prefix, t0 + chunk)
@@ -247,11 +249,11 @@ def main():
         if want_cpu:              # kept on the device until the timing is over: a host copy here would leave the
             cpuK.append(K[cpu_idx])   # GPU idle for a moment right before the timed launch
             cpuV.append(V[cpu_idx])
-        torch.cuda.synchronize()
-        ti = time.perf_counter()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         sg.ingest_prefix(K, V)
-        sg.sync()
-        ingest_s += time.perf_counter() - ti
+        e1.record()
+        ing_ev.append((e0, e1))
         if sgp is not None and not keep:      # the twin takes the same chunk (untimed); with the prefix resident it
             sgp.ingest_prefix(K, V)           # ingests after the timed loop instead
         del K, V
@@ -259,6 +261,8 @@ def main():
         for t0 in range(0, a.prefix, chunk):
             t1 = min(a.prefix, t0 + chunk)
             sgp.ingest_prefix(Kall[:, t0:t1], Vall[:, t0:t1])
+    torch.cuda.synchronize()
+    ingest_s = sum(x.elapsed_time(y) for x, y in ing_ev) * 1e-3
     cpuK = [x.cpu() for x in cpuK]
     cpuV = [x.cpu() for x in cpuV]
     st0 = sg.stats()
