@@ -747,3 +747,23 @@ def test_forced_decisions_replace_the_rule_only_at_their_token():
     assert again.assign.tolist() == plain.assign.tolist()
     with pytest.raises(ValueError):
         again.set_overrides({1: 0})
+
+
+def test_long_stream_samples_are_uniform_over_the_tokens_when_norms_are_equal():
+    """Lemma 1 at the length of the long-context workload: with equal ||v|| every slot holds a token drawn
+    uniformly from all tokens seen, also beyond token 2^16 and with coin probabilities down to 2^-17 (chi-square over
+    16 equal ranges of the token index; slots of one stream are independent, three seeds)."""
+    n, s, bins = 140000, 512, 16
+    K = np.zeros((n, 2), dtype=np.float32)
+    V = np.ones((n, 2), dtype=np.float32)
+    counts = np.zeros(bins)
+    for seed in (1, 2, 3):
+        o = OracleStream(2, 1.0, s=s, w=0, seed=seed)
+        o.ingest(K, V)
+        idx = o.sample_idx
+        assert idx.min() >= 0 and idx.max() < n and o.m == 1 and o.mu == 2.0 * n
+        counts += np.bincount(idx * bins // n, minlength=bins)
+    expected = 3 * s / bins
+    chi2 = float(((counts - expected) ** 2 / expected).sum())
+    assert chi2 < 37.7, (chi2, counts)          # chi-square, 15 degrees of freedom, p = 0.001
+    assert counts[-1] > 0 and counts[0] > 0
