@@ -5,7 +5,8 @@
 //   1. distances of the 64 tokens to all representatives that exist at the
 //      start of the chunk are one dense (m x 64 x d) contraction on the matrix
 //      cores (representatives as the A operand, the 64 token keys as four B
-//      operands); every lane tracks best / runner-up for its token;
+//      operands); every lane tracks the three smallest distances of its token
+//      and the rows of the first two;
 //   2. distances between the 64 tokens themselves (one more 64 x 64 x d
 //      contraction) cover the representatives created inside the chunk;
 //   3. a resolve loop, one lane per token, replays the order: a token only
@@ -13,7 +14,10 @@
 //      creation (or one ambiguous token) to the next, so it runs a few
 //      iterations per chunk once the table has filled;
 //   4. ambiguous decisions (gap or threshold distance within the error bound
-//      of the matrix-core distances) are re-evaluated exactly in double;
+//      of the matrix-core distances) are re-evaluated exactly in double: as a
+//      rule only against the best and the runner-up (the third-smallest
+//      distance shows that no other row can be the nearest), else against the
+//      whole table;
 //   5. the sampling coins do not depend on the clustering: the chunks only
 //      leave each token's probability behind, and once per 1024 evicted
 //      tokens (or at the end of the call) one pass draws the coins per 4-slot
@@ -23,6 +27,8 @@
 // during the call come first from the ring, then from the call's own input;
 // the ring is rewritten once at the end.
 #pragma once
+#include <type_traits>
+
 #include "subgen_mfma_device.hpp"
 
 namespace sg {
@@ -30,6 +36,12 @@ namespace sg {
 constexpr int kChunkT = 64;  // tokens per chunk = one lane per token in the resolve loop
 #ifndef SG_COINSPAN
 #define SG_COINSPAN 1024
+#endif
+#ifdef SG_PHASE_PROFILE   // experiment: time per phase, summed over all workgroups (wavefront 0)
+__device__ unsigned long long g_phase[16];
+#define SG_PH(i) do { const long long t_ = clock64(); ph[i] += t_ - tprev; tprev = t_; } while (0)
+#else
+#define SG_PH(i) do { } while (0)
 #endif
 constexpr int kCoinSpan = SG_COINSPAN;  // evicted tokens per coin pass (a multiple of the chunk)
 
@@ -41,8 +53,8 @@ struct SmemIngest {
     // whose coins are still to be drawn (up to kCoinSpan)
     uint32_t plim[kCoinSpan];
     float vnall[kCoinSpan];
-    float wb1[kWaves][kChunkT], wb2[kWaves][kChunkT];
-    int wi1[kWaves][kChunkT];
+    float wb1[kWaves][kChunkT], wb2[kWaves][kChunkT], wb3[kWaves][kChunkT];
+    int wi1[kWaves][kChunkT], wi2[kWaves][kChunkT];
     float wnx[kWaves];
     float tt[kChunkT][kChunkT + 1];
     double wbest[kWaves];
@@ -58,16 +70,53 @@ struct SmemIngest {
     alignas(16) char kt[kChunkT * KS];
 };
 
-// merge candidate (d, idx) into best / runner-up; lower index wins exact ties of the approximate value
-__device__ __forceinline__ void cand_merge(float d, int idx, float &b1, int &i1, float &b2)
+// min(a, b) as the one instruction it is (fminf first quiets its operands with one more instruction each); a NaN
+// operand is ignored
+__device__ __forceinline__ float min_f32(const float a, const float b)
 {
-    if (d < b1 || (d == b1 && (uint32_t)idx < (uint32_t)i1)) {
-        b2 = b1;
-        b1 = d;
-        i1 = idx;
-    } else {
-        b2 = fminf(b2, d);
-    }
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// Candidate list of a token: nearest (b1, i1), runner-up (b2, i2) and the third-smallest value b3 of the approximate
+// distances.  Insert candidate (d, idx).  Equal values keep the order of arrival: the decision never rests on
+// that order, since equal approximations are within the error bound of each other and go to the exact comparison.
+__device__ __forceinline__ void top3_insert(const float d, const int idx, float &b1, int &i1, float &b2, int &i2, float &b3)
+{
+    const bool lt1 = d < b1, lt2 = d < b2;
+    b3 = __builtin_amdgcn_fmed3f(b2, b3, d);
+    int t2 = lt2 ? idx : i2;
+    asm("" : "+v"(t2));   // two plain selects (nested, the compiler turns them into branches)
+    i2 = lt1 ? i1 : t2;
+    b2 = __builtin_amdgcn_fmed3f(b1, b2, d);
+    i1 = lt1 ? idx : i1;
+    b1 = min_f32(b1, d);
+}
+
+// Lane exchanges of gfx950 that stay in the vector unit.  from_row_above: lanes of DPP row 0 get the value of the
+// same lane of row 1, row 2 gets row 3 (rows 1 and 3 get something else); from_upper_half: lanes 0..31 get lanes
+// 32..63.
+__device__ __forceinline__ uint32_t from_row_above(const uint32_t v) { return __builtin_amdgcn_permlane16_swap(v, v, false, false)[1]; }
+__device__ __forceinline__ uint32_t from_upper_half(const uint32_t v) { return __builtin_amdgcn_permlane32_swap(v, v, false, false)[1]; }
+template <bool HALF>
+__device__ __forceinline__ float lanes_above(const float v)
+{
+    const uint32_t b = __builtin_bit_cast(uint32_t, v);
+    return __builtin_bit_cast(float, HALF ? from_upper_half(b) : from_row_above(b));
+}
+template <bool HALF>
+__device__ __forceinline__ int lanes_above(const int v)
+{
+    return (int)(HALF ? from_upper_half((uint32_t)v) : from_row_above((uint32_t)v));
+}
+// lane l gets the value of lane l - 1, lane 0 gets `first` (a DPP wavefront shift)
+__device__ __forceinline__ double from_lane_below(const double v, const double first)
+{
+    const uint64_t b = __builtin_bit_cast(uint64_t, v), f = __builtin_bit_cast(uint64_t, first);
+    const uint32_t lo = __builtin_amdgcn_update_dpp((uint32_t)f, (uint32_t)b, 0x138, 0xf, 0xf, false);
+    const uint32_t hi = __builtin_amdgcn_update_dpp((uint32_t)(f >> 32), (uint32_t)(b >> 32), 0x138, 0xf, 0xf, false);
+    return __builtin_bit_cast(double, (uint64_t)lo | ((uint64_t)hi << 32));
 }
 
 template <int NK, bool RES>
@@ -167,8 +216,24 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             }
         }
     };
+#ifdef SG_PHASE_PROFILE
+    long long ph[16] = {0}, tprev = clock64();
+#endif
     int64_t span0 = ge0;   // first evicted token of the pending coin pass
     int span_fill = 0;     // tokens whose probabilities wait in LDS
+
+    constexpr int NP = T / RPB;   // passes of the lane groups over the 64 tokens
+    uint4 rk[NP], rv[NP];
+    auto fetch_rows = [&](const int64_t cc) __attribute__((always_inline)) {
+        const int ntc = (int)(ge1 - cc < T ? ge1 - cc : T);
+#pragma unroll
+        for (int it = 0; it < NP; ++it) {
+            const int jr = grp + it * RPB;
+            const int jj = jr < ntc ? jr : ntc - 1;
+            rk[it] = ld16(krow_of(cc + jj) + col * 16);
+            rv[it] = ld16(vrow_of(cc + jj) + col * 16);
+        }
+    };
 
     for (int64_t c0 = ge0; c0 < ge1; c0 += T) {
         const int nt = (int)(ge1 - c0 < T ? ge1 - c0 : T);
@@ -191,15 +256,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
 
         // ---- squared norms of the chunk's keys and values (double, exact products), one token per lane group
         {
-            constexpr int NP = T / RPB;   // passes of the lane groups over the 64 tokens
-            uint4 rk[NP], rv[NP];
-#pragma unroll
-            for (int it = 0; it < NP; ++it) {   // all row loads first
-                const int j = grp + it * RPB;
-                const int jj = j < nt ? j : nt - 1;
-                rk[it] = ld16(krow_of(c0 + jj) + col * 16);
-                rv[it] = ld16(vrow_of(c0 + jj) + col * 16);
-            }
+            fetch_rows(c0);
 #pragma unroll
             for (int it = 0; it < NP; ++it) {
                 float kf[8], vf[8];
@@ -224,11 +281,13 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 }
             }
         }
+        SG_PH(0);
         // ---- B operand (ts, kk): token 16 ts + n in column n, read from the LDS tile
         auto bop = [&](int ts, int kk) __attribute__((always_inline)) {
             return *reinterpret_cast<const uint4 *>(&sm.kt[(16 * ts + n16) * KS + (L + 4 * kk) * 16]);
         };
         __syncthreads();
+        SG_PH(1);
         float nkt[4];
 #pragma unroll
         for (int ts = 0; ts < 4; ++ts) nkt[ts] = sm.nk[16 * ts + n16];
@@ -252,79 +311,85 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             }
         }
 
-        // ---- distances to the representatives that exist at the start of the chunk
-        float b1[4], b2[4], nxmax = 0.f;
-        int i1[4];
+        SG_PH(2);
+        // ---- distances to the representatives that exist at the start of the chunk.  Per (token, row) the loop
+        //      spends nine vector instructions: e = ||x||^2 - 2 <x, k> (the token's own ||k||^2 is the same for
+        //      all rows and is added after the loop), the three smallest values (minimum; median of (minimum,
+        //      runner-up, e); median of (runner-up, third, e)) and the rows of the first two (a lane meets its
+        //      rows in increasing order, so strict comparisons keep the lowest row on equal e)
+        float b1[4], b2[4], b3[4], nxmax = 0.f;
+        int i1[4], i2[4];
 #pragma unroll
         for (int ts = 0; ts < 4; ++ts) {
             b1[ts] = INFINITY;
             b2[ts] = INFINITY;
+            b3[ts] = INFINITY;
             i1[ts] = -1;
+            i2[ts] = -1;
         }
-        for (int r0 = wave * 16; r0 < m0; r0 += 16 * kWaves) {
-            // the oldest request is this group; the queue moves up and takes one more request at its end
+        // one group of 16 rows from request slot `slot`, which then takes the request PF groups ahead
+        auto scan_group = [&](uint4(&qs)[NK], float4 &qns, const int r0) __attribute__((always_inline)) {
             uint4 a[NK];
 #pragma unroll
-            for (int kk = 0; kk < NK; ++kk) a[kk] = q[0][kk];
-            const float nxr[4] = {qn[0].x, qn[0].y, qn[0].z, qn[0].w};
-#pragma unroll
-            for (int pf = 0; pf + 1 < PF; ++pf) {
-#pragma unroll
-                for (int kk = 0; kk < NK; ++kk) q[pf][kk] = q[pf + 1][kk];
-                qn[pf] = qn[pf + 1];
-            }
-            request(q[PF - 1], qn[PF - 1], r0 + 16 * kWaves * PF);
+            for (int kk = 0; kk < NK; ++kk) a[kk] = qs[kk];
+            const float nxraw[4] = {qns.x, qns.y, qns.z, qns.w};
+            request(qs, qns, r0 + 16 * kWaves * PF);
             // the B operands do not change from group to group: without this the compiler keeps all of them
             // in registers over the loop, which is what the LDS tile is there to avoid
             asm volatile("" ::: "memory");
             const int row0 = r0 + 4 * L;
-            uint4 bq[NK];   // operands of the next token set, read while the current one is on the matrix cores
+            float nxr[4];
+            int rowi[4];
 #pragma unroll
-            for (int kk = 0; kk < NK; ++kk) bq[kk] = bop(0, kk);
+            for (int r = 0; r < 4; ++r) {
+                // rows past the table (the clamped loads of the last group) take part as +inf
+                const bool in = row0 + r < m0;
+                nxr[r] = in ? nxraw[r] : INFINITY;
+                nxmax = fmaxf(nxmax, in ? nxraw[r] : 0.f);
+                rowi[r] = row0 + r;
+            }
 #pragma unroll
             for (int ts = 0; ts < 4; ++ts) {
                 floatx4_t c = {0.f, 0.f, 0.f, 0.f};
-                uint4 b[NK];
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) b[kk] = bq[kk];
-                if (ts + 1 < 4) {
-#pragma unroll
-                    for (int kk = 0; kk < NK; ++kk) bq[kk] = bop(ts + 1, kk);
-                }
-#pragma unroll
-                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(a[kk], b[kk], c);
+                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(a[kk], bop(ts, kk), c);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    // rows past the table (the clamped loads of the last group) take part as +inf
-                    const float dt = row0 + r < m0 ? fmaf(-2.f, c[r], nxr[r] + nkt[ts]) : INFINITY;
-                    const bool first = dt < b1[ts];
-                    b2[ts] = first ? b1[ts] : fminf(b2[ts], dt);
-                    i1[ts] = first ? row0 + r : i1[ts];
-                    b1[ts] = first ? dt : b1[ts];
+                    const float e = fmaf(-2.f, c[r], nxr[r]);
+                    top3_insert(e, rowi[r], b1[ts], i1[ts], b2[ts], i2[ts], b3[ts]);
                 }
             }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) nxmax = fmaxf(nxmax, row0 + r < m0 ? nxr[r] : 0.f);
+        };
+        for (int r0 = wave * 16; r0 < m0; r0 += 16 * kWaves * PF) {
+            static_assert(PF == 2, "the loop alternates between two request slots");
+            scan_group(q[0], qn[0], r0);
+            if (r0 + 16 * kWaves < m0) scan_group(q[1], qn[1], r0 + 16 * kWaves);
         }
+        SG_PH(3);
 #pragma unroll
         for (int ts = 0; ts < 4; ++ts) {
-#pragma unroll
-            for (int o = 16; o < 64; o <<= 1) {
-                const float ob1 = __shfl_xor(b1[ts], o), ob2 = __shfl_xor(b2[ts], o);
-                const int oi1 = __shfl_xor(i1[ts], o);
-                if (ob1 < b1[ts] || (ob1 == b1[ts] && (uint32_t)oi1 < (uint32_t)i1[ts])) {
-                    b2[ts] = fminf(b1[ts], ob2);
-                    b1[ts] = ob1;
-                    i1[ts] = oi1;
-                } else {
-                    b2[ts] = fminf(b2[ts], ob1);
-                }
-            }
+            b1[ts] += nkt[ts];
+            b2[ts] += nkt[ts];
+            b3[ts] += nkt[ts];
+            // the four lanes of a token hold disjoint rows; lane L = 0 collects them: first from L = 1 (and L = 2
+            // from L = 3), then from L = 2
+            auto collect = [&](auto half) __attribute__((always_inline)) {
+                constexpr bool H = decltype(half)::value;
+                const float x1 = lanes_above<H>(b1[ts]), x2 = lanes_above<H>(b2[ts]), x3 = lanes_above<H>(b3[ts]);
+                const int xi1 = lanes_above<H>(i1[ts]), xi2 = lanes_above<H>(i2[ts]);
+                top3_insert(x1, xi1, b1[ts], i1[ts], b2[ts], i2[ts], b3[ts]);
+                top3_insert(x2, xi2, b1[ts], i1[ts], b2[ts], i2[ts], b3[ts]);
+                b3[ts] = min_f32(b3[ts], x3);
+            };
+            collect(std::false_type{});
+            collect(std::true_type{});
             if (L == 0) {
                 sm.wb1[wave][16 * ts + n16] = b1[ts];
                 sm.wb2[wave][16 * ts + n16] = b2[ts];
+                sm.wb3[wave][16 * ts + n16] = b3[ts];
                 sm.wi1[wave][16 * ts + n16] = i1[ts];
+                sm.wi2[wave][16 * ts + n16] = i2[ts];
             }
         }
 #pragma unroll
@@ -333,45 +398,37 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
         if constexpr (RES) {
             if (wave == 0) sm.tgt[lane] = -1;   // dropped tokens and the ragged tail keep -1
         }
+        SG_PH(4);
         __syncthreads();
+        SG_PH(5);
 
         // ---- resolve in token order: lane j = token j of the chunk; every wavefront runs the same loop
         //      (same LDS inputs, same results), wavefront 0 applies the side effects
         const int j = lane;
         const float nkj = sm.nk[j];
         const bool valid = j < nt && nkj < INFINITY;
-        float ob1 = sm.wb1[0][j], ob2 = sm.wb2[0][j];
-        int oi1 = sm.wi1[0][j];
-        float nxold = sm.wnx[0];
+        // the token's candidate list over the representatives of the chunk's start; the clusters that the chunk
+        // opens are inserted as they appear
+        float c1 = sm.wb1[0][j], c2 = sm.wb2[0][j], c3 = sm.wb3[0][j];
+        int ci = sm.wi1[0][j], ci2 = sm.wi2[0][j];
+        float nxl = sm.wnx[0];
 #pragma unroll
         for (int wv = 1; wv < kWaves; ++wv) {
-            const float x1 = sm.wb1[wv][j], x2 = sm.wb2[wv][j];
-            const int xi = sm.wi1[wv][j];
-            if (x1 < ob1 || (x1 == ob1 && (uint32_t)xi < (uint32_t)oi1)) {
-                ob2 = fminf(ob1, x2);
-                ob1 = x1;
-                oi1 = xi;
-            } else {
-                ob2 = fminf(ob2, x1);
-            }
-            nxold = fmaxf(nxold, sm.wnx[wv]);
+            top3_insert(sm.wb1[wv][j], sm.wi1[wv][j], c1, ci, c2, ci2, c3);
+            top3_insert(sm.wb2[wv][j], sm.wi2[wv][j], c1, ci, c2, ci2, c3);
+            c3 = min_f32(c3, sm.wb3[wv][j]);
+            nxl = fmaxf(nxl, sm.wnx[wv]);
         }
         uint64_t cmask = 0;   // tokens of this chunk that opened a cluster (uniform)
         int done = 0;         // tokens below `done` are final (uniform)
         const uint64_t below = j == 0 ? 0ull : (~0ull >> (64 - j));
+        // chunk position of the token that opened cluster idx >= m0
+        auto opener = [&](const int idx) {
+            uint64_t mm = cmask;
+            for (int q = idx - m0; q > 0; --q) mm &= mm - 1;
+            return __builtin_ctzll(mm);
+        };
         while (done < nt) {
-            float c1 = ob1, c2 = ob2, nxl = nxold;
-            int ci = oi1;
-            uint64_t rest = cmask;
-            while (rest) {   // uniform loop over the creators; a lane only sees those before it
-                const int l = __builtin_ctzll(rest);
-                rest &= rest - 1;
-                if (l < j) {
-                    cand_merge(sm.tt[l][j], m0 + __builtin_popcountll(cmask & (l == 0 ? 0ull : (~0ull >> (64 - l)))), c1,
-                               ci, c2);
-                    nxl = fmaxf(nxl, sm.nk[l]);
-                }
-            }
             const int mcur = m0 + __builtin_popcountll(cmask & below);   // clusters that exist when token j arrives
             const float emax = kDistEps * (nxl + nkj);
             const bool live = valid && j >= done;
@@ -383,23 +440,50 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             const int e = evmask ? __builtin_ctzll(evmask) : nt;   // first creation / ambiguous token
             // tokens before the event are final: they join (or are force-joined to) their nearest cluster
             if (wave == 0 && live && j < e) {
-                if (ci < 0) ci = 0;   // only with non-finite representatives (imported state)
-                if constexpr (RES) sm.tgt[j] = ci;
-                atomicAdd(&cnt[ci], 1);
+                const int cj = ci < 0 ? 0 : ci;   // < 0 only with non-finite representatives (imported state)
+                if constexpr (RES) sm.tgt[j] = cj;
+                atomicAdd(&cnt[cj], 1);
                 if (forced) atomicOr(&st.flags[sid], 1u);
-                if (st.assign != nullptr && c0 + j < st.assign_cap) st.assign[sid * (size_t)st.assign_cap + c0 + j] = ci;
+                if (st.assign != nullptr && c0 + j < st.assign_cap) st.assign[sid * (size_t)st.assign_cap + c0 + j] = cj;
             }
             if (e >= nt) break;
             const bool e_amb = (__ballot(amb && live) >> e) & 1ull;
             const int me = m0 + __builtin_popcountll(cmask);   // clusters that exist when token e arrives
             bool create = true;
             int target = me;
+#ifdef SG_PHASE_PROFILE
+            const long long ta_ = clock64();
+            if (e_amb) ph[13] += 1;
+#endif
             if (e_amb) {
-                __syncthreads();   // rows of this chunk's creators are visible to every wavefront
                 double best;
                 int bidx;
-                exact_nearest<LPR>(X, me, *reinterpret_cast<const uint4 *>(&sm.kt[e * KS + col * 16]), sm.wbest, sm.widx, best,
-                              bidx);
+                // every exact distance is at most emax away from its approximation, so the nearest
+                // representative is among those within 2 emax of the smallest approximation: when the third
+                // smallest is beyond that, these are the best and (perhaps) the runner-up, and their one or two
+                // exact distances decide; every wavefront evaluates them by itself
+                const bool few = c3 - c1 > 2.f * emax && ci >= 0;
+                if ((__ballot(few) >> e) & 1ull) {
+                    const int r1 = __shfl(ci, e), r2x = __shfl(ci2, e);
+                    const int r2 = (__ballot(c2 - c1 > 2.f * emax) >> e) & 1ull ? -1 : r2x;
+                    const int rsel = sub == 0 ? r1 : (sub == 1 ? r2 : -1);
+                    double dist = INFINITY;
+                    if (rsel >= 0) {
+                        // a row that this chunk opened is read from the LDS tile (its copy in the table was
+                        // written by another wavefront)
+                        const uint4 xr = rsel < m0 ? ld16(X + (size_t)rsel * ROWB + col * 16)
+                                                   : *reinterpret_cast<const uint4 *>(&sm.kt[opener(rsel) * KS + col * 16]);
+                        dist = exact_distance<LPR>(xr, *reinterpret_cast<const uint4 *>(&sm.kt[e * KS + col * 16]));
+                    }
+                    const double d1 = __shfl(dist, 0), d2 = __shfl(dist, LPR);
+                    const bool second = r2 >= 0 && (d2 < d1 || (d2 == d1 && r2 < r1));
+                    best = second ? d2 : d1;
+                    bidx = second ? r2 : r1;
+                } else {
+                    __syncthreads();   // rows of this chunk's creators are visible to every wavefront
+                    exact_nearest<LPR>(X, me, *reinterpret_cast<const uint4 *>(&sm.kt[e * KS + col * 16]), sm.wbest, sm.widx,
+                                       best, bidx);
+                }
                 const bool ejoin = bidx >= 0 && best <= st.delta2;
                 const Decision dec = decide_cluster(ejoin, bidx, me, st.Mcap);
                 const bool eforced = dec.forced;
@@ -413,6 +497,10 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                     }
                 }
             }
+#ifdef SG_PHASE_PROFILE
+            if (e_amb) ph[15] += clock64() - ta_;
+            ph[14] += 1;
+#endif
             if (create) {
                 if (tid < LPR)   // the new representative's row comes out of the LDS tile
                     st16(X + (size_t)me * ROWB + tid * 16, *reinterpret_cast<const uint4 *>(&sm.kt[e * KS + tid * 16]));
@@ -421,6 +509,10 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                     xn[me] = sm.nk[e];
                 }
                 cmask |= 1ull << e;
+                if (j > e) {   // the later tokens of the chunk see the new cluster
+                    top3_insert(sm.tt[e][j], me, c1, ci, c2, ci2, c3);
+                    nxl = fmaxf(nxl, sm.nk[e]);
+                }
             }
             if (tid == 0 && st.assign != nullptr && c0 + e < st.assign_cap)
                 st.assign[sid * (size_t)st.assign_cap + c0 + e] = target;
@@ -430,6 +522,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             done = e + 1;
         }
         m = m0 + __builtin_popcountll(cmask);
+        SG_PH(6);
 
         // ---- per-cluster reservoirs (UpdateSoftmaxNormalizer of Algorithm 1 as printed): a token that joins a
         //      cluster of (then) n members takes each of the t slots with probability 1/n; the opener of a
@@ -481,33 +574,35 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             }
         }
 
+        SG_PH(7);
         // ---- sampling: p_j from the running mu (sequential double adds, token order); the coins wait for the
         //      coin pass
         if (wave == 0) {
             const float vnj = sm.vn[j];
-            const double vd = (double)vnj;
-            const int vlo = (int)(__builtin_bit_cast(uint64_t, vd) & 0xffffffffull);
-            const int vhi = (int)(__builtin_bit_cast(uint64_t, vd) >> 32);
+            // mu before token j = ((mu + ||v_0||^2) + ...) + ||v_{j-1}||^2, added in this order: every lane adds the
+            // value of the lane below to that lane's sum, so after step l the lanes up to l are final
+            const double vd = j < nt ? (double)vnj : 0.0;
+            const double vbelow = from_lane_below(vd, 0.0);
             double muj = mu;
-            for (int l = 0; l < nt; ++l) {   // lane l's value through the scalar unit, no LDS round trip per step
-                const uint64_t bits = (uint64_t)(uint32_t)__builtin_amdgcn_readlane(vlo, l) |
-                                      ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(vhi, l) << 32);
-                if (l < j) muj += __builtin_bit_cast(double, bits);
-            }
+            for (int l = 1; l < nt; ++l) muj = from_lane_below(muj, muj) + vbelow;   // lane 0 keeps mu
             const float pj = coin_probability(muj, vnj);
             sm.plim[span_fill + j] = valid ? coin_limit(pj) : 0u;
             sm.vnall[span_fill + j] = vnj;
             const double mend = muj + (double)vnj;
             mu = __shfl(mend, nt - 1);
         }
+        SG_PH(8);
         span_fill += nt;
         if (span_fill + T > kCoinSpan || c0 + T >= ge1) {
             __syncthreads();
+            SG_PH(9);
             coin_pass(span0, span_fill);
+            SG_PH(10);
             span0 += span_fill;
             span_fill = 0;
         }
         __syncthreads();   // LDS is reused by the next chunk; new rows are visible
+        SG_PH(11);
     }
 
     // ---- the ring ends up holding the last min(n, w) tokens of the call
@@ -526,6 +621,11 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
         st.m[sid] = m;
         st.mu[sid] = mu;
     }
+#ifdef SG_PHASE_PROFILE
+    SG_PH(12);
+    if (tid == 0)
+        for (int i = 0; i < 16; ++i) atomicAdd(&g_phase[i], (unsigned long long)ph[i]);
+#endif
 }
 
 }  // namespace sg

@@ -77,6 +77,23 @@ struct SmemMfma {
     float wacc[kWaves][G][NK * 32];
 };
 
+// Exact squared distance of two bf16 rows in double precision: each of the LPR lanes of a row holds one 16-byte
+// chunk of both; all of them get the sum.
+template <int LPR>
+__device__ __forceinline__ double exact_distance(const uint4 &xrow, const uint4 &krow)
+{
+    float x[8], k[8];
+    unpack<true>(xrow, x);
+    unpack<true>(krow, k);
+    double dist = 0.0;
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        const double df = (double)x[v] - (double)k[v];
+        dist = fma(df, df, dist);
+    }
+    return group_sum<LPR>(dist);
+}
+
 // Exact nearest representative in double precision (lowest index on ties); block-uniform result.
 template <int LPR, int NW = kWaves>
 __device__ __forceinline__ void exact_nearest(const char *X, int m, const uint4 &ek, double *wbest, int *widx,
@@ -86,8 +103,6 @@ __device__ __forceinline__ void exact_nearest(const char *X, int m, const uint4 
     constexpr size_t ROWB = (size_t)LPR * 16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane % LPR, sub = lane / LPR;
-    float ekf[8];
-    unpack<true>(ek, ekf);
     best = INFINITY;
     bidx = -1;
     for (int r0 = wave * RPW; r0 < m; r0 += RPB * kUnroll) {
@@ -100,15 +115,7 @@ __device__ __forceinline__ void exact_nearest(const char *X, int m, const uint4 
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int r = r0 + u * RPB + sub;
-            float x[8];
-            unpack<true>(raw[u], x);
-            double dist = 0.0;
-#pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                const double df = (double)x[v] - (double)ekf[v];
-                dist = fma(df, df, dist);
-            }
-            dist = group_sum<LPR>(dist);
+            const double dist = exact_distance<LPR>(raw[u], ek);
             if (r < m && dist < best) {
                 best = dist;
                 bidx = r;
