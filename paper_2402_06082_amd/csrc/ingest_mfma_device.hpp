@@ -1,73 +1,82 @@
 // Chunked prefix ingest for bf16 rows on gfx950.
 //
 // A stream's tokens must be clustered in order (the greedy rule is order
-// dependent), but the arithmetic of 64 consecutive tokens can be batched:
-//   1. distances of the 64 tokens to all representatives that exist at the
-//      start of the chunk are one dense (m x 64 x d) contraction on the matrix
-//      cores (representatives as the A operand, the 64 token keys as four B
-//      operands); every lane tracks the three smallest distances of its token
-//      and the rows of the first two;
-//   2. distances between the 64 tokens themselves (one more 64 x 64 x d
-//      contraction) cover the representatives created inside the chunk;
-//   3. a resolve loop, one lane per token, replays the order: a token only
-//      sees the chunk's creators that precede it; the loop advances from one
+// dependent), but the arithmetic of T = 128 (or 64) consecutive tokens can be
+// batched:
+//   1. distances of the T tokens to all representatives that exist at the
+//      start of the chunk are one dense (m x T x d) contraction on the matrix
+//      cores (representatives as the A operand, the token keys as T / 16 B
+//      operands read from an LDS tile), so the table is read once per T
+//      tokens; every lane tracks the three smallest distances of its token,
+//      each with its row in the low mantissa bits;
+//   2. wavefront 0 replays the order, one lane per token (two tokens with
+//      T = 128: first the lower 64, then the upper 64): a token only sees the
+//      clusters that the chunk opened before it.  The loop advances from one
 //      creation (or one ambiguous token) to the next, so it runs a few
-//      iterations per chunk once the table has filled;
-//   4. ambiguous decisions (gap or threshold distance within the error bound
-//      of the matrix-core distances) are re-evaluated exactly in double: as a
+//      iterations per chunk once the table has filled; the distances of a
+//      new representative to the later tokens of the chunk are computed when
+//      it appears (packed dot products over the LDS tile);
+//   3. ambiguous decisions (gap or threshold distance within the error bound
+//      of the approximate distances) are re-evaluated exactly in double: as a
 //      rule only against the best and the runner-up (the third-smallest
 //      distance shows that no other row can be the nearest), else against the
 //      whole table;
-//   5. the sampling coins do not depend on the clustering: the chunks only
-//      leave each token's probability behind, and once per 1024 evicted
-//      tokens (or at the end of the call) one pass draws the coins per 4-slot
-//      block; the last accepting token of a slot wins (sequential overwrite
-//      semantics), so a slot is copied at most once per pass.
+//   4. the sampling coins do not depend on the clustering: the chunks only
+//      leave each token's probability behind, and once per 512 (1024 with
+//      T = 64) evicted tokens (or at the end of the call) one pass draws the
+//      coins per 4-slot block; the last accepting token of a slot wins
+//      (sequential overwrite semantics), so a slot is copied at most once
+//      per pass.
 // The window is handled by index arithmetic: the tokens that leave the window
 // during the call come first from the ring, then from the call's own input;
 // the ring is rewritten once at the end.
 #pragma once
 #include <type_traits>
 
+#include "subgen_dot2_device.hpp"
 #include "subgen_mfma_device.hpp"
 
 namespace sg {
 
-constexpr int kChunkT = 64;  // tokens per chunk = one lane per token in the resolve loop
-#ifndef SG_COINSPAN
-#define SG_COINSPAN 1024
-#endif
-#ifdef SG_PHASE_PROFILE   // experiment: time per phase, summed over all workgroups (wavefront 0)
+#ifdef SG_PHASE_PROFILE   // development aid: time per phase of wavefront 0, summed over all workgroups
 __device__ unsigned long long g_phase[16];
 #define SG_PH(i) do { const long long t_ = clock64(); ph[i] += t_ - tprev; tprev = t_; } while (0)
 #else
 #define SG_PH(i) do { } while (0)
 #endif
-constexpr int kCoinSpan = SG_COINSPAN;  // evicted tokens per coin pass (a multiple of the chunk)
 
-template <int NK>
+// per-cluster reservoirs (t >= 1): cluster of every token of the chunk, its coin probability 1/n_i, and which
+// reservoir slots it wins
+template <int T, bool RES>
+struct SmemReservoir {
+    int tgt[T];
+    float pr[T];
+    uint8_t win[T][16];
+};
+template <int T>
+struct SmemReservoir<T, false> {};
+
+template <int NK, int T, bool RES>
 struct SmemIngest {
-    alignas(16) float nk[kChunkT];
-    float vn[kChunkT];
+    // evicted tokens per coin pass (a multiple of the chunk); with 128-token chunks three workgroups per CU only
+    // fit with the shorter span
+    static constexpr int kSpan = T > 64 ? 512 : 1024;
+    alignas(16) float nk[T];
+    float vn[T];
     // coin bound (coin_limit: a word r is accepted iff r <= bound; 0 = never) and ||v||^2 of the evicted tokens
-    // whose coins are still to be drawn (up to kCoinSpan)
-    uint32_t plim[kCoinSpan];
-    float vnall[kCoinSpan];
-    float wb1[kWaves][kChunkT], wb2[kWaves][kChunkT], wb3[kWaves][kChunkT];
-    int wi1[kWaves][kChunkT], wi2[kWaves][kChunkT];
+    // whose coins are still to be drawn (up to kSpan)
+    uint32_t plim[kSpan];
+    float vnall[kSpan];
+    // candidate lists of the tokens, one per wavefront (each wavefront scans a quarter of the rows)
+    float wb1[kWaves][T], wb2[kWaves][T], wb3[kWaves][T];
+    int wi1[kWaves][T], wi2[kWaves][T];
     float wnx[kWaves];
-    float tt[kChunkT][kChunkT + 1];
-    double wbest[kWaves];
-    int widx[kWaves];
-    // per-cluster reservoirs (t >= 1): cluster of every token of the chunk, its coin probability 1/n_i, and
-    // which reservoir slots it wins
-    int tgt[kChunkT];
-    float pr[kChunkT];
-    uint8_t win[kChunkT][16];
+    int mnew;
+    SmemReservoir<T, RES> res;
     // the chunk's keys, one padded row per token (the pad spreads the 16 rows an operand read touches over
     // all banks): the B operands of every contraction of the chunk are read from here
     static constexpr int KS = NK * 64 + 16;
-    alignas(16) char kt[kChunkT * KS];
+    alignas(16) char kt[T * KS];
 };
 
 // min(a, b) as the one instruction it is (fminf first quiets its operands with one more instruction each); a NaN
@@ -76,6 +85,14 @@ __device__ __forceinline__ float min_f32(const float a, const float b)
 {
     float r;
     asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// median of three signed integers
+__device__ __forceinline__ int med3_i32(const int a, const int b, const int c)
+{
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
 
@@ -119,17 +136,20 @@ __device__ __forceinline__ double from_lane_below(const double v, const double f
     return __builtin_bit_cast(double, (uint64_t)lo | ((uint64_t)hi << 32));
 }
 
-template <int NK, bool RES>
+template <int NK, int T, bool RES>
 __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, const Call call)
 {
     static_assert(kWaves == 4, "the chunk layout assumes four wavefronts per workgroup");
-    constexpr int T = kChunkT;
+    static_assert(T == 64 || T == 128, "one or two tokens per lane of the resolving wavefront");
+    constexpr int H = T / 64;      // 64-token halves of a chunk
+    constexpr int NTS = T / 16;    // 16-token operand sets
     constexpr int CPR = 4 * NK, LPR = CPR;
     constexpr int RPW = 64 / LPR, RPB = RPW * kWaves;
     constexpr size_t ROWB = (size_t)NK * 64;
-    constexpr int KS = SmemIngest<NK>::KS;
+    constexpr int KS = SmemIngest<NK, T, RES>::KS;
+    constexpr int kCoinSpan = SmemIngest<NK, T, RES>::kSpan;
     constexpr int PF = 2;   // groups of 16 representatives in flight per wavefront (a third one spills)
-    __shared__ SmemIngest<NK> sm;
+    __shared__ SmemIngest<NK, T, RES> sm;
 
     const size_t sid = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -222,18 +242,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
     int64_t span0 = ge0;   // first evicted token of the pending coin pass
     int span_fill = 0;     // tokens whose probabilities wait in LDS
 
-    constexpr int NP = T / RPB;   // passes of the lane groups over the 64 tokens
-    uint4 rk[NP], rv[NP];
-    auto fetch_rows = [&](const int64_t cc) __attribute__((always_inline)) {
-        const int ntc = (int)(ge1 - cc < T ? ge1 - cc : T);
-#pragma unroll
-        for (int it = 0; it < NP; ++it) {
-            const int jr = grp + it * RPB;
-            const int jj = jr < ntc ? jr : ntc - 1;
-            rk[it] = ld16(krow_of(cc + jj) + col * 16);
-            rv[it] = ld16(vrow_of(cc + jj) + col * 16);
-        }
-    };
 
     for (int64_t c0 = ge0; c0 < ge1; c0 += T) {
         const int nt = (int)(ge1 - c0 < T ? ge1 - c0 : T);
@@ -254,15 +262,26 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
 #pragma unroll
         for (int pf = 0; pf < PF; ++pf) request(q[pf], qn[pf], (wave + kWaves * pf) * 16);
 
-        // ---- squared norms of the chunk's keys and values (double, exact products), one token per lane group
-        {
-            fetch_rows(c0);
+        // ---- squared norms of the chunk's keys and values (double, exact products), one token per lane group;
+        //      64 tokens per batch (a batch's rows are all requested before the first is used)
+#pragma unroll 1
+        for (int t0 = 0; t0 < T; t0 += 64) {
+            constexpr int NB = 64 / RPB;   // passes of the lane groups over a batch
+            uint4 rk[NB], rv[NB];
 #pragma unroll
-            for (int it = 0; it < NP; ++it) {
+            for (int it = 0; it < NB; ++it) {
+                const int jr = t0 + grp + it * RPB;
+                const int jj = jr < nt ? jr : nt - 1;
+                rk[it] = ld16(krow_of(c0 + jj) + col * 16);
+                rv[it] = ld16(vrow_of(c0 + jj) + col * 16);
+            }
+#pragma unroll
+            for (int it = 0; it < NB; ++it) {
+                const int jr = t0 + grp + it * RPB;
                 float kf[8], vf[8];
                 unpack<true>(rk[it], kf);
                 unpack<true>(rv[it], vf);
-                *reinterpret_cast<uint4 *>(&sm.kt[(grp + it * RPB) * KS + col * 16]) = rk[it];
+                *reinterpret_cast<uint4 *>(&sm.kt[jr * KS + col * 16]) = rk[it];
                 double a = 0.0, b = 0.0;
 #pragma unroll
                 for (int v = 0; v < 8; ++v) {
@@ -275,9 +294,9 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 // nothing and is never sampled; it is marked by ||k||^2 = +inf, ||v||^2 = 0
                 const bool bad = !token_is_finite((float)a, (float)b);
                 if (col == 0) {
-                    sm.nk[grp + it * RPB] = bad ? INFINITY : (float)a;
-                    sm.vn[grp + it * RPB] = bad ? 0.f : (float)b;
-                    if (bad && grp + it * RPB < nt) atomicOr(&st.flags[sid], 2u);
+                    sm.nk[jr] = bad ? INFINITY : (float)a;
+                    sm.vn[jr] = bad ? 0.f : (float)b;
+                    if (bad && jr < nt) atomicOr(&st.flags[sid], 2u);
                 }
             }
         }
@@ -288,241 +307,325 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
         };
         __syncthreads();
         SG_PH(1);
-        float nkt[4];
-#pragma unroll
-        for (int ts = 0; ts < 4; ++ts) nkt[ts] = sm.nk[16 * ts + n16];
 
-        // ---- token-token distances: wavefront `wave` takes rows 16 wave .. 16 wave + 15 (its A operand is
-        //      B set `wave`)
-        {
-            const float4 nkr = *reinterpret_cast<const float4 *>(&sm.nk[16 * wave + 4 * L]);
-            const float nkrow[4] = {nkr.x, nkr.y, nkr.z, nkr.w};
-            uint4 arow[NK];
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk) arow[kk] = bop(wave, kk);
-#pragma unroll
-            for (int ts = 0; ts < 4; ++ts) {
-                floatx4_t c = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(arow[kk], bop(ts, kk), c);
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    sm.tt[16 * wave + 4 * L + r][16 * ts + n16] = fmaf(-2.f, c[r], nkrow[r] + nkt[ts]);
-            }
-        }
-
-        SG_PH(2);
         // ---- distances to the representatives that exist at the start of the chunk.  Per (token, row) the loop
-        //      spends nine vector instructions: e = ||x||^2 - 2 <x, k> (the token's own ||k||^2 is the same for
-        //      all rows and is added after the loop), the three smallest values (minimum; median of (minimum,
-        //      runner-up, e); median of (runner-up, third, e)) and the rows of the first two (a lane meets its
-        //      rows in increasing order, so strict comparisons keep the lowest row on equal e)
-        float b1[4], b2[4], b3[4], nxmax = 0.f;
-        int i1[4], i2[4];
+        //      spends six vector instructions: e = ||x||^2 - 2 <x, k> + ||k||^2; the low bits of e are replaced by the
+        //      position of the row in the lane's sequence of rows (4 g + r: group g of the wavefront, row r of the
+        //      lane's four), and the three smallest of these keys are kept with integer minimum / median (as
+        //      signed integers the keys order like the distances; the few negative ones, all within the error
+        //      bound of zero, order among themselves in reverse, which the exact comparison sorts out).  The
+        //      key of a distance d is within 2^(KB-23) |d| of d (KB index bits).
+        const int KB = 32 - __builtin_clz((unsigned)(m0 > 64 ? (m0 + 63) >> 6 : 1) * 4u - 1u);   // positions < 4 groups
+        const int kmask = (1 << KB) - 1;
+        const float ek = ldexpf(1.0005f, KB - 23);
+        constexpr int kEmpty = 0x7f800000;   // +inf
+        int k1[NTS], k2[NTS], k3[NTS];
+        float nkt[NTS], nxmax = 0.f;
 #pragma unroll
-        for (int ts = 0; ts < 4; ++ts) {
-            b1[ts] = INFINITY;
-            b2[ts] = INFINITY;
-            b3[ts] = INFINITY;
-            i1[ts] = -1;
-            i2[ts] = -1;
+        for (int ts = 0; ts < NTS; ++ts) {
+            k1[ts] = kEmpty;
+            k2[ts] = kEmpty;
+            k3[ts] = kEmpty;
+            nkt[ts] = sm.nk[16 * ts + n16];
         }
-        // one group of 16 rows from request slot `slot`, which then takes the request PF groups ahead
+        const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+        // one group of 16 rows from a request slot
         auto scan_group = [&](uint4(&qs)[NK], float4 &qns, const int r0) __attribute__((always_inline)) {
-            uint4 a[NK];
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk) a[kk] = qs[kk];
             const float nxraw[4] = {qns.x, qns.y, qns.z, qns.w};
-            request(qs, qns, r0 + 16 * kWaves * PF);
             // the B operands do not change from group to group: without this the compiler keeps all of them
             // in registers over the loop, which is what the LDS tile is there to avoid
             asm volatile("" ::: "memory");
             const int row0 = r0 + 4 * L;
+            const int pos0 = (r0 - 16 * wave_s) >> 4;   // 4 g
             float nxr[4];
-            int rowi[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 // rows past the table (the clamped loads of the last group) take part as +inf
                 const bool in = row0 + r < m0;
                 nxr[r] = in ? nxraw[r] : INFINITY;
                 nxmax = fmaxf(nxmax, in ? nxraw[r] : 0.f);
-                rowi[r] = row0 + r;
             }
 #pragma unroll
-            for (int ts = 0; ts < 4; ++ts) {
+            for (int ts = 0; ts < NTS; ++ts) {
                 floatx4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(a[kk], bop(ts, kk), c);
+                for (int kk = 0; kk < NK; ++kk) c = mfma_bf16(qs[kk], bop(ts, kk), c);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float e = fmaf(-2.f, c[r], nxr[r]);
-                    top3_insert(e, rowi[r], b1[ts], i1[ts], b2[ts], i2[ts], b3[ts]);
+                    const float e = fmaf(-2.f, c[r], nxr[r]) + nkt[ts];
+                    const int key = (__builtin_bit_cast(int, e) & ~kmask) | (pos0 + r);
+                    k3[ts] = med3_i32(k2[ts], k3[ts], key);
+                    k2[ts] = med3_i32(k1[ts], k2[ts], key);
+                    k1[ts] = min(k1[ts], key);
                 }
             }
+            // the slot's rows are consumed: it takes the group PF groups ahead (in flight while the other slot's
+            // group is on the matrix cores)
+            request(qs, qns, r0 + 16 * kWaves * PF);
         };
         for (int r0 = wave * 16; r0 < m0; r0 += 16 * kWaves * PF) {
             static_assert(PF == 2, "the loop alternates between two request slots");
             scan_group(q[0], qn[0], r0);
             if (r0 + 16 * kWaves < m0) scan_group(q[1], qn[1], r0 + 16 * kWaves);
         }
-        SG_PH(3);
+        SG_PH(2);
+        // distance and row out of a key; an empty entry (or a row past the table) is (+inf, -1)
+        auto key_value = [&](const int key) { return __builtin_bit_cast(float, key & ~kmask); };
+        auto key_row = [&](const int key) {
+            const int pos = key & kmask;
+            return (key & ~kmask) == kEmpty ? -1 : ((pos >> 2) << 6) + 16 * wave + 4 * L + (pos & 3);
+        };
 #pragma unroll
-        for (int ts = 0; ts < 4; ++ts) {
-            b1[ts] += nkt[ts];
-            b2[ts] += nkt[ts];
-            b3[ts] += nkt[ts];
+        for (int ts = 0; ts < NTS; ++ts) {
+            float b1 = key_value(k1[ts]), b2 = key_value(k2[ts]), b3 = key_value(k3[ts]);
+            int i1 = key_row(k1[ts]), i2 = key_row(k2[ts]);
             // the four lanes of a token hold disjoint rows; lane L = 0 collects them: first from L = 1 (and L = 2
             // from L = 3), then from L = 2
             auto collect = [&](auto half) __attribute__((always_inline)) {
-                constexpr bool H = decltype(half)::value;
-                const float x1 = lanes_above<H>(b1[ts]), x2 = lanes_above<H>(b2[ts]), x3 = lanes_above<H>(b3[ts]);
-                const int xi1 = lanes_above<H>(i1[ts]), xi2 = lanes_above<H>(i2[ts]);
-                top3_insert(x1, xi1, b1[ts], i1[ts], b2[ts], i2[ts], b3[ts]);
-                top3_insert(x2, xi2, b1[ts], i1[ts], b2[ts], i2[ts], b3[ts]);
-                b3[ts] = min_f32(b3[ts], x3);
+                constexpr bool HALF = decltype(half)::value;
+                const float x1 = lanes_above<HALF>(b1), x2 = lanes_above<HALF>(b2), x3 = lanes_above<HALF>(b3);
+                const int xi1 = lanes_above<HALF>(i1), xi2 = lanes_above<HALF>(i2);
+                top3_insert(x1, xi1, b1, i1, b2, i2, b3);
+                top3_insert(x2, xi2, b1, i1, b2, i2, b3);
+                b3 = min_f32(b3, x3);
             };
             collect(std::false_type{});
             collect(std::true_type{});
             if (L == 0) {
-                sm.wb1[wave][16 * ts + n16] = b1[ts];
-                sm.wb2[wave][16 * ts + n16] = b2[ts];
-                sm.wb3[wave][16 * ts + n16] = b3[ts];
-                sm.wi1[wave][16 * ts + n16] = i1[ts];
-                sm.wi2[wave][16 * ts + n16] = i2[ts];
+                sm.wb1[wave][16 * ts + n16] = b1;
+                sm.wb2[wave][16 * ts + n16] = b2;
+                sm.wb3[wave][16 * ts + n16] = b3;
+                sm.wi1[wave][16 * ts + n16] = i1;
+                sm.wi2[wave][16 * ts + n16] = i2;
             }
         }
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) nxmax = fmaxf(nxmax, __shfl_xor(nxmax, o));
         if (lane == 0) sm.wnx[wave] = nxmax;
         if constexpr (RES) {
-            if (wave == 0) sm.tgt[lane] = -1;   // dropped tokens and the ragged tail keep -1
+            if (tid < T) sm.res.tgt[tid] = -1;   // dropped tokens and the ragged tail keep -1
         }
-        SG_PH(4);
+        SG_PH(3);
         __syncthreads();
-        SG_PH(5);
+        SG_PH(4);
 
-        // ---- resolve in token order: lane j = token j of the chunk; every wavefront runs the same loop
-        //      (same LDS inputs, same results), wavefront 0 applies the side effects
-        const int j = lane;
-        const float nkj = sm.nk[j];
-        const bool valid = j < nt && nkj < INFINITY;
-        // the token's candidate list over the representatives of the chunk's start; the clusters that the chunk
-        // opens are inserted as they appear
-        float c1 = sm.wb1[0][j], c2 = sm.wb2[0][j], c3 = sm.wb3[0][j];
-        int ci = sm.wi1[0][j], ci2 = sm.wi2[0][j];
-        float nxl = sm.wnx[0];
+        // ---- resolve in token order (wavefront 0): lane j holds token j of every 64-token half of the chunk
+        if (wave == 0) {
+            const int j = lane;
+            const uint64_t below = j == 0 ? 0ull : (~0ull >> (64 - j));
+            // the token's candidate list over the representatives of the chunk's start; the clusters that the
+            // chunk opens are inserted as they appear
+            float c1[H], c2[H], c3[H], nxl[H], nkj[H];
+            int ci[H], ci2[H];
 #pragma unroll
-        for (int wv = 1; wv < kWaves; ++wv) {
-            top3_insert(sm.wb1[wv][j], sm.wi1[wv][j], c1, ci, c2, ci2, c3);
-            top3_insert(sm.wb2[wv][j], sm.wi2[wv][j], c1, ci, c2, ci2, c3);
-            c3 = min_f32(c3, sm.wb3[wv][j]);
-            nxl = fmaxf(nxl, sm.wnx[wv]);
-        }
-        uint64_t cmask = 0;   // tokens of this chunk that opened a cluster (uniform)
-        int done = 0;         // tokens below `done` are final (uniform)
-        const uint64_t below = j == 0 ? 0ull : (~0ull >> (64 - j));
-        // chunk position of the token that opened cluster idx >= m0
-        auto opener = [&](const int idx) {
-            uint64_t mm = cmask;
-            for (int q = idx - m0; q > 0; --q) mm &= mm - 1;
-            return __builtin_ctzll(mm);
-        };
-        while (done < nt) {
-            const int mcur = m0 + __builtin_popcountll(cmask & below);   // clusters that exist when token j arrives
-            const float emax = kDistEps * (nxl + nkj);
-            const bool live = valid && j >= done;
-            const bool amb = distances_ambiguous(c1, c2, thr, emax, mcur);
-            const bool join = mcur > 0 && c1 <= thr;
-            const bool forced = decide_cluster(join, ci, mcur, st.Mcap).forced;
-            const bool event = live && (amb || (!join && !forced));
-            const uint64_t evmask = __ballot(event);
-            const int e = evmask ? __builtin_ctzll(evmask) : nt;   // first creation / ambiguous token
-            // tokens before the event are final: they join (or are force-joined to) their nearest cluster
-            if (wave == 0 && live && j < e) {
-                const int cj = ci < 0 ? 0 : ci;   // < 0 only with non-finite representatives (imported state)
-                if constexpr (RES) sm.tgt[j] = cj;
-                atomicAdd(&cnt[cj], 1);
-                if (forced) atomicOr(&st.flags[sid], 1u);
-                if (st.assign != nullptr && c0 + j < st.assign_cap) st.assign[sid * (size_t)st.assign_cap + c0 + j] = cj;
-            }
-            if (e >= nt) break;
-            const bool e_amb = (__ballot(amb && live) >> e) & 1ull;
-            const int me = m0 + __builtin_popcountll(cmask);   // clusters that exist when token e arrives
-            bool create = true;
-            int target = me;
-#ifdef SG_PHASE_PROFILE
-            const long long ta_ = clock64();
-            if (e_amb) ph[13] += 1;
-#endif
-            if (e_amb) {
-                double best;
-                int bidx;
-                // every exact distance is at most emax away from its approximation, so the nearest
-                // representative is among those within 2 emax of the smallest approximation: when the third
-                // smallest is beyond that, these are the best and (perhaps) the runner-up, and their one or two
-                // exact distances decide; every wavefront evaluates them by itself
-                const bool few = c3 - c1 > 2.f * emax && ci >= 0;
-                if ((__ballot(few) >> e) & 1ull) {
-                    const int r1 = __shfl(ci, e), r2x = __shfl(ci2, e);
-                    const int r2 = (__ballot(c2 - c1 > 2.f * emax) >> e) & 1ull ? -1 : r2x;
-                    const int rsel = sub == 0 ? r1 : (sub == 1 ? r2 : -1);
-                    double dist = INFINITY;
-                    if (rsel >= 0) {
-                        // a row that this chunk opened is read from the LDS tile (its copy in the table was
-                        // written by another wavefront)
-                        const uint4 xr = rsel < m0 ? ld16(X + (size_t)rsel * ROWB + col * 16)
-                                                   : *reinterpret_cast<const uint4 *>(&sm.kt[opener(rsel) * KS + col * 16]);
-                        dist = exact_distance<LPR>(xr, *reinterpret_cast<const uint4 *>(&sm.kt[e * KS + col * 16]));
-                    }
-                    const double d1 = __shfl(dist, 0), d2 = __shfl(dist, LPR);
-                    const bool second = r2 >= 0 && (d2 < d1 || (d2 == d1 && r2 < r1));
-                    best = second ? d2 : d1;
-                    bidx = second ? r2 : r1;
-                } else {
-                    __syncthreads();   // rows of this chunk's creators are visible to every wavefront
-                    exact_nearest<LPR>(X, me, *reinterpret_cast<const uint4 *>(&sm.kt[e * KS + col * 16]), sm.wbest, sm.widx,
-                                       best, bidx);
+            for (int h = 0; h < H; ++h) {
+                const int tok = 64 * h + j;
+                nkj[h] = sm.nk[tok];
+                c1[h] = sm.wb1[0][tok];
+                c2[h] = sm.wb2[0][tok];
+                c3[h] = sm.wb3[0][tok];
+                ci[h] = sm.wi1[0][tok];
+                ci2[h] = sm.wi2[0][tok];
+                nxl[h] = sm.wnx[0];
+#pragma unroll
+                for (int wv = 1; wv < kWaves; ++wv) {
+                    top3_insert(sm.wb1[wv][tok], sm.wi1[wv][tok], c1[h], ci[h], c2[h], ci2[h], c3[h]);
+                    top3_insert(sm.wb2[wv][tok], sm.wi2[wv][tok], c1[h], ci[h], c2[h], ci2[h], c3[h]);
+                    c3[h] = min_f32(c3[h], sm.wb3[wv][tok]);
+                    nxl[h] = fmaxf(nxl[h], sm.wnx[wv]);
                 }
-                const bool ejoin = bidx >= 0 && best <= st.delta2;
-                const Decision dec = decide_cluster(ejoin, bidx, me, st.Mcap);
-                const bool eforced = dec.forced;
-                create = dec.created;
-                if (!create) {
-                    bidx = dec.target;
-                    target = bidx;
-                    if (tid == 0) {
-                        atomicAdd(&cnt[bidx], 1);
-                        if (eforced) atomicOr(&st.flags[sid], 1u);
+            }
+            uint64_t cmask[H];   // tokens of each half that opened a cluster (uniform)
+#pragma unroll
+            for (int h = 0; h < H; ++h) cmask[h] = 0;
+            // chunk position of the token that opened cluster idx >= m0
+            auto opener = [&](const int idx) {
+                int q = idx - m0, tok0 = 0;
+                uint64_t mm = cmask[0];
+                if constexpr (H > 1) {
+                    const int n0h = __builtin_popcountll(cmask[0]);
+                    if (q >= n0h) {
+                        q -= n0h;
+                        mm = cmask[H - 1];
+                        tok0 = 64;
                     }
                 }
-            }
+                for (; q > 0; --q) mm &= mm - 1;
+                return tok0 + (int)__builtin_ctzll(mm);
+            };
+            // approximate squared distance of two tokens of the chunk (lane-wise: jtok differs per lane)
+            auto token_distance = [&](const int etok, const int jtok) {
+                float acc = 0.f;
+#pragma unroll 2
+                for (int ch = 0; ch < CPR; ++ch) {
+                    const uint4 a = *reinterpret_cast<const uint4 *>(&sm.kt[etok * KS + ch * 16]);
+                    const uint4 b = *reinterpret_cast<const uint4 *>(&sm.kt[jtok * KS + ch * 16]);
+                    acc = dot2_bf16(a.x, b.x, acc);
+                    acc = dot2_bf16(a.y, b.y, acc);
+                    acc = dot2_bf16(a.z, b.z, acc);
+                    acc = dot2_bf16(a.w, b.w, acc);
+                }
+                return fmaf(-2.f, acc, sm.nk[etok] + sm.nk[jtok]);
+            };
+            // row idx of the table as it stands inside the chunk: rows that the chunk opened come from the LDS tile
+            auto table_chunk = [&](const int idx) {
+                return idx < m0 ? ld16(X + (size_t)idx * ROWB + col * 16)
+                                : *reinterpret_cast<const uint4 *>(&sm.kt[opener(idx) * KS + col * 16]);
+            };
+            int base = m0;   // clusters that exist at the start of the half
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const int nth = nt - 64 * h < 0 ? 0 : (nt - 64 * h > 64 ? 64 : nt - 64 * h);
+                const bool valid = j < nth && nkj[h] < INFINITY;
+                int done = 0;   // tokens below `done` are final (uniform)
+                while (done < nth) {
+                    const int mcur = base + __builtin_popcountll(cmask[h] & below);   // clusters when token j arrives
+                    // error bound of the approximate distances, and the same plus the index bits of the keys
+                    // (relative to the value; a candidate that the chunk itself opened has none, it is treated
+                    // alike)
+                    const float emax = kDistEps * (nxl[h] + nkj[h]);
+                    const float emaxk = emax + ek * fmaxf(fabsf(c1[h]), c2[h] < INFINITY ? fabsf(c2[h]) : 0.f);
+                    const bool live = valid && j >= done;
+                    const bool amb = distances_ambiguous(c1[h], c2[h], thr, emaxk, mcur);
+                    const bool join = mcur > 0 && c1[h] <= thr;
+                    const bool forced = decide_cluster(join, ci[h], mcur, st.Mcap).forced;
+                    const bool event = live && (amb || (!join && !forced));
+                    const uint64_t evmask = __ballot(event);
+                    const int e = evmask ? __builtin_ctzll(evmask) : nth;   // first creation / ambiguous token
+                    // tokens before the event are final: they join (or are force-joined to) their nearest cluster
+                    if (live && j < e) {
+                        const int cj = ci[h] < 0 ? 0 : ci[h];   // < 0 only with non-finite representatives (imported state)
+                        if constexpr (RES) sm.res.tgt[64 * h + j] = cj;
+                        atomicAdd(&cnt[cj], 1);
+                        if (forced) atomicOr(&st.flags[sid], 1u);
+                        if (st.assign != nullptr && c0 + 64 * h + j < st.assign_cap)
+                            st.assign[sid * (size_t)st.assign_cap + c0 + 64 * h + j] = cj;
+                    }
+                    if (e >= nth) break;
+                    const int etok = 64 * h + e;
+                    const bool e_amb = (__ballot(amb && live) >> e) & 1ull;
+                    const int me = base + __builtin_popcountll(cmask[h]);   // clusters that exist when token e arrives
+                    bool create = true;
+                    int target = me;
 #ifdef SG_PHASE_PROFILE
-            if (e_amb) ph[15] += clock64() - ta_;
-            ph[14] += 1;
+                    const long long ta_ = clock64();
+                    if (e_amb) ph[13] += 1;
 #endif
-            if (create) {
-                if (tid < LPR)   // the new representative's row comes out of the LDS tile
-                    st16(X + (size_t)me * ROWB + tid * 16, *reinterpret_cast<const uint4 *>(&sm.kt[e * KS + tid * 16]));
-                if (tid == 0) {
-                    atomicAdd(&cnt[me], 1);
-                    xn[me] = sm.nk[e];
+                    if (e_amb) {
+                        const uint4 ekey = *reinterpret_cast<const uint4 *>(&sm.kt[etok * KS + col * 16]);
+                        double best;
+                        int bidx;
+                        // every exact distance is at most the bound away from its approximation, so the nearest
+                        // representative is among those within twice the bound of the smallest approximation:
+                        // when the third smallest is beyond that, these are the best and (perhaps) the
+                        // runner-up, and their one or two exact distances decide
+                        const bool few = ci[h] >= 0 && (c3[h] == INFINITY ||
+                                                        c3[h] - c1[h] > 2.f * emax + ek * (fabsf(c1[h]) + fabsf(c3[h])));
+                        if ((__ballot(few) >> e) & 1ull) {
+                            const int r1 = __shfl(ci[h], e), r2x = __shfl(ci2[h], e);
+                            const int r2 = (__ballot(c2[h] - c1[h] > 2.f * emaxk) >> e) & 1ull ? -1 : r2x;
+                            const int rsel = sub == 0 ? r1 : (sub == 1 ? r2 : -1);
+                            double dist = INFINITY;
+                            if (rsel >= 0) dist = exact_distance<LPR>(table_chunk(rsel), ekey);
+                            const double d1 = __shfl(dist, 0), d2 = __shfl(dist, LPR);
+                            const bool second = r2 >= 0 && (d2 < d1 || (d2 == d1 && r2 < r1));
+                            best = second ? d2 : d1;
+                            bidx = second ? r2 : r1;
+                        } else {
+                            // every row, RPW at a time (rare)
+                            best = INFINITY;
+                            bidx = -1;
+                            for (int r0 = 0; r0 < me; r0 += RPW) {
+                                const int r = r0 + sub;
+                                const double dist = exact_distance<LPR>(table_chunk(r < me ? r : me - 1), ekey);
+                                if (r < me && dist < best) {
+                                    best = dist;
+                                    bidx = r;
+                                }
+                            }
+#pragma unroll
+                            for (int o = LPR; o < 64; o <<= 1) {
+                                const double ob = __shfl_xor(best, o);
+                                const int oi = __shfl_xor(bidx, o);
+                                if (ob < best || (ob == best && (uint32_t)oi < (uint32_t)bidx)) {
+                                    best = ob;
+                                    bidx = oi;
+                                }
+                            }
+                        }
+                        const bool ejoin = bidx >= 0 && best <= st.delta2;
+                        const Decision dec = decide_cluster(ejoin, bidx, me, st.Mcap);
+                        create = dec.created;
+                        if (!create) {
+                            target = dec.target;
+                            if (lane == 0) {
+                                atomicAdd(&cnt[target], 1);
+                                if (dec.forced) atomicOr(&st.flags[sid], 1u);
+                            }
+                        }
+                    }
+#ifdef SG_PHASE_PROFILE
+                    if (e_amb) ph[15] += clock64() - ta_;
+                    ph[14] += 1;
+#endif
+                    if (create) {
+                        if (lane < LPR)   // the new representative's row comes out of the LDS tile
+                            st16(X + (size_t)me * ROWB + lane * 16, *reinterpret_cast<const uint4 *>(&sm.kt[etok * KS + lane * 16]));
+                        if (lane == 0) {
+                            atomicAdd(&cnt[me], 1);
+                            xn[me] = sm.nk[etok];
+                        }
+                        cmask[h] |= 1ull << e;
+                        // the later tokens of the chunk see the new cluster
+                        const float nke = sm.nk[etok];
+#pragma unroll
+                        for (int hh = 0; hh < H; ++hh) {
+                            if (hh < h) continue;
+                            const float d = token_distance(etok, 64 * hh + j);
+                            if (hh > h || j > e) {
+                                top3_insert(d, me, c1[hh], ci[hh], c2[hh], ci2[hh], c3[hh]);
+                                nxl[hh] = fmaxf(nxl[hh], nke);
+                            }
+                        }
+                    }
+                    if (lane == 0 && st.assign != nullptr && c0 + etok < st.assign_cap)
+                        st.assign[sid * (size_t)st.assign_cap + c0 + etok] = target;
+                    if constexpr (RES) {
+                        if (lane == 0) sm.res.tgt[etok] = target;
+                    }
+                    done = e + 1;
                 }
-                cmask |= 1ull << e;
-                if (j > e) {   // the later tokens of the chunk see the new cluster
-                    top3_insert(sm.tt[e][j], me, c1, ci, c2, ci2, c3);
-                    nxl = fmaxf(nxl, sm.nk[e]);
+                base += __builtin_popcountll(cmask[h]);
+            }
+            m = base;
+            SG_PH(5);
+
+            // ---- sampling: p_j from the running mu (sequential double adds, token order); the coins wait for the
+            //      coin pass
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const int nth = nt - 64 * h < 0 ? 0 : (nt - 64 * h > 64 ? 64 : nt - 64 * h);
+                if (nth > 0) {
+                    const float vnj = sm.vn[64 * h + j];
+                    // mu before token j = ((mu + ||v_0||^2) + ...) + ||v_{j-1}||^2, added in this order: every lane
+                    // adds the value of the lane below to that lane's sum, so after step l the lanes up to l are
+                    // final
+                    const double vd = j < nth ? (double)vnj : 0.0;
+                    const double vbelow = from_lane_below(vd, 0.0);
+                    double muj = mu;
+                    for (int l = 1; l < nth; ++l) muj = from_lane_below(muj, muj) + vbelow;   // lane 0 keeps mu
+                    const float pj = coin_probability(muj, vnj);
+                    const bool valid = j < nth && nkj[h] < INFINITY;
+                    sm.plim[span_fill + 64 * h + j] = valid ? coin_limit(pj) : 0u;
+                    sm.vnall[span_fill + 64 * h + j] = vnj;
+                    const double mend = muj + vd;
+                    mu = __shfl(mend, nth - 1);
                 }
             }
-            if (tid == 0 && st.assign != nullptr && c0 + e < st.assign_cap)
-                st.assign[sid * (size_t)st.assign_cap + c0 + e] = target;
-            if constexpr (RES) {
-                if (tid == 0) sm.tgt[e] = target;
-            }
-            done = e + 1;
+            if (lane == 0) sm.mnew = m;
+            SG_PH(6);
         }
-        m = m0 + __builtin_popcountll(cmask);
-        SG_PH(6);
 
         // ---- per-cluster reservoirs (UpdateSoftmaxNormalizer of Algorithm 1 as printed): a token that joins a
         //      cluster of (then) n members takes each of the t slots with probability 1/n; the opener of a
@@ -532,20 +635,20 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             char *const R = st.R + sid * (size_t)st.Mcap * TT * ROWB;
             __syncthreads();   // every token's cluster is in LDS, the counts of the chunk are in memory
             if (tid < T) {
-                const int c = tid < nt ? sm.tgt[tid] : -1;
+                const int c = tid < nt ? sm.res.tgt[tid] : -1;
                 float prj = -1.f;
                 if (c >= 0) {
                     int later = 0;
-                    for (int l = tid + 1; l < nt; ++l) later += sm.tgt[l] == c;
+                    for (int l = tid + 1; l < nt; ++l) later += sm.res.tgt[l] == c;
                     const int nj = atomicAdd(&cnt[c], 0) - later;   // members when this token arrived (itself included)
                     prj = 1.0f / (float)nj;
                 }
-                sm.pr[tid] = prj;
+                sm.res.pr[tid] = prj;
             }
             __syncthreads();
             for (int it = tid; it < T * TB; it += kWG) {
                 const int jj = it / TB, b = it % TB;
-                const float prj = sm.pr[jj];
+                const float prj = sm.res.pr[jj];
                 uint32_t wbits = 0;
                 if (prj > 0.f) {
                     const uint64_t ge = (uint64_t)(c0 + jj);
@@ -555,16 +658,16 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                     for (int i = 0; i < 4; ++i)
                         if (4 * b + i < TT && coin_accepts(r[i], prj)) wbits |= 1u << i;
                 }
-                sm.win[jj][b] = (uint8_t)wbits;
+                sm.res.win[jj][b] = (uint8_t)wbits;
             }
             __syncthreads();
             for (int it = tid; it < T * TT; it += kWG) {
                 const int jj = it / TT, sl = it % TT;
-                if (!((sm.win[jj][sl >> 2] >> (sl & 3)) & 1)) continue;
-                const int c = sm.tgt[jj];
+                if (!((sm.res.win[jj][sl >> 2] >> (sl & 3)) & 1)) continue;
+                const int c = sm.res.tgt[jj];
                 bool last = true;
                 for (int l = jj + 1; l < nt; ++l)
-                    if (sm.tgt[l] == c && ((sm.win[l][sl >> 2] >> (sl & 3)) & 1)) last = false;
+                    if (sm.res.tgt[l] == c && ((sm.res.win[l][sl >> 2] >> (sl & 3)) & 1)) last = false;
                 if (last) {
                     const char *ks = krow_of(c0 + jj);
                     char *dst = R + ((size_t)c * TT + sl) * ROWB;
@@ -575,22 +678,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
         }
 
         SG_PH(7);
-        // ---- sampling: p_j from the running mu (sequential double adds, token order); the coins wait for the
-        //      coin pass
-        if (wave == 0) {
-            const float vnj = sm.vn[j];
-            // mu before token j = ((mu + ||v_0||^2) + ...) + ||v_{j-1}||^2, added in this order: every lane adds the
-            // value of the lane below to that lane's sum, so after step l the lanes up to l are final
-            const double vd = j < nt ? (double)vnj : 0.0;
-            const double vbelow = from_lane_below(vd, 0.0);
-            double muj = mu;
-            for (int l = 1; l < nt; ++l) muj = from_lane_below(muj, muj) + vbelow;   // lane 0 keeps mu
-            const float pj = coin_probability(muj, vnj);
-            sm.plim[span_fill + j] = valid ? coin_limit(pj) : 0u;
-            sm.vnall[span_fill + j] = vnj;
-            const double mend = muj + (double)vnj;
-            mu = __shfl(mend, nt - 1);
-        }
         SG_PH(8);
         span_fill += nt;
         if (span_fill + T > kCoinSpan || c0 + T >= ge1) {
@@ -602,6 +689,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             span_fill = 0;
         }
         __syncthreads();   // LDS is reused by the next chunk; new rows are visible
+        m = sm.mnew;
         SG_PH(11);
     }
 

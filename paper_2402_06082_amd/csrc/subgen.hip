@@ -570,6 +570,10 @@ int subgen_step(subgen_ctx *c, const void *K_t, const void *V_t, const void *Q_t
     return rc;
 }
 
+#ifndef SG_INGEST_T
+#define SG_INGEST_T 128   // tokens per chunk of the matrix-core ingest (64 with per-cluster reservoirs)
+#endif
+
 int subgen_ingest_prefix(subgen_ctx *c, const void *K, const void *V, int64_t n, int64_t stream_stride,
                          int64_t token_stride)
 {
@@ -590,15 +594,15 @@ int subgen_ingest_prefix(subgen_ctx *c, const void *K, const void *V, int64_t n,
         call.n_seen = c->n_seen;
         const dim3 grid((unsigned)c->S);
         if (c->st.t > 0 && c->ingest_mfma && c->LPR == 8)
-            hipLaunchKernelGGL((sg::ingest_mfma_kernel<2, true>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+            hipLaunchKernelGGL((sg::ingest_mfma_kernel<2, 64, true>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
         else if (c->st.t > 0 && c->ingest_mfma && c->LPR == 16)
-            hipLaunchKernelGGL((sg::ingest_mfma_kernel<4, true>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+            hipLaunchKernelGGL((sg::ingest_mfma_kernel<4, 64, true>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
         else if (c->st.t > 0)
             launch_res(c, MODE_UPDATE, call, c->G);
         else if (c->mfma && c->LPR == 8)
-            hipLaunchKernelGGL((sg::ingest_mfma_kernel<2, false>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+            hipLaunchKernelGGL((sg::ingest_mfma_kernel<2, SG_INGEST_T, false>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
         else if (c->mfma && c->LPR == 16)
-            hipLaunchKernelGGL((sg::ingest_mfma_kernel<4, false>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
+            hipLaunchKernelGGL((sg::ingest_mfma_kernel<4, SG_INGEST_T, false>), grid, dim3(sg::kWG), 0, c->stream, c->st, call);
         else if (c->dtype == SUBGEN_BF16) launch_ingest_lpr<true>(c->LPR, grid, c->stream, c->st, call);
         else launch_ingest_lpr<false>(c->LPR, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();
