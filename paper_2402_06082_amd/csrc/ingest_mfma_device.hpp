@@ -38,12 +38,6 @@
 
 namespace sg {
 
-#ifdef SG_PHASE_PROFILE   // development aid: time per phase of wavefront 0, summed over all workgroups
-__device__ unsigned long long g_phase[16];
-#define SG_PH(i) do { const long long t_ = clock64(); ph[i] += t_ - tprev; tprev = t_; } while (0)
-#else
-#define SG_PH(i) do { } while (0)
-#endif
 
 // per-cluster reservoirs (t >= 1): cluster of every token of the chunk, its coin probability 1/n_i, and which
 // reservoir slots it wins
@@ -236,9 +230,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             }
         }
     };
-#ifdef SG_PHASE_PROFILE
-    long long ph[16] = {0}, tprev = clock64();
-#endif
     int64_t span0 = ge0;   // first evicted token of the pending coin pass
     int span_fill = 0;     // tokens whose probabilities wait in LDS
 
@@ -300,13 +291,11 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 }
             }
         }
-        SG_PH(0);
         // ---- B operand (ts, kk): token 16 ts + n in column n, read from the LDS tile
         auto bop = [&](int ts, int kk) __attribute__((always_inline)) {
             return *reinterpret_cast<const uint4 *>(&sm.kt[(16 * ts + n16) * KS + (L + 4 * kk) * 16]);
         };
         __syncthreads();
-        SG_PH(1);
 
         // ---- distances to the representatives that exist at the start of the chunk.  Per (token, row) the loop
         //      spends six vector instructions: e = ||x||^2 - 2 <x, k> + ||k||^2; the low bits of e are replaced by the
@@ -369,7 +358,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             scan_group(q[0], qn[0], r0);
             if (r0 + 16 * kWaves < m0) scan_group(q[1], qn[1], r0 + 16 * kWaves);
         }
-        SG_PH(2);
         // distance and row out of a key; an empty entry (or a row past the table) is (+inf, -1)
         auto key_value = [&](const int key) { return __builtin_bit_cast(float, key & ~kmask); };
         auto key_row = [&](const int key) {
@@ -406,9 +394,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
         if constexpr (RES) {
             if (tid < T) sm.res.tgt[tid] = -1;   // dropped tokens and the ragged tail keep -1
         }
-        SG_PH(3);
         __syncthreads();
-        SG_PH(4);
 
         // ---- resolve in token order (wavefront 0): lane j holds token j of every 64-token half of the chunk
         if (wave == 0) {
@@ -457,7 +443,7 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
             // approximate squared distance of two tokens of the chunk (lane-wise: jtok differs per lane)
             auto token_distance = [&](const int etok, const int jtok) {
                 float acc = 0.f;
-#pragma unroll 2
+#pragma unroll 4   // (a full unroll makes the compiler spill the scan's registers)
                 for (int ch = 0; ch < CPR; ++ch) {
                     const uint4 a = *reinterpret_cast<const uint4 *>(&sm.kt[etok * KS + ch * 16]);
                     const uint4 b = *reinterpret_cast<const uint4 *>(&sm.kt[jtok * KS + ch * 16]);
@@ -508,10 +494,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                     const int me = base + __builtin_popcountll(cmask[h]);   // clusters that exist when token e arrives
                     bool create = true;
                     int target = me;
-#ifdef SG_PHASE_PROFILE
-                    const long long ta_ = clock64();
-                    if (e_amb) ph[13] += 1;
-#endif
                     if (e_amb) {
                         const uint4 ekey = *reinterpret_cast<const uint4 *>(&sm.kt[etok * KS + col * 16]);
                         double best;
@@ -565,10 +547,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                             }
                         }
                     }
-#ifdef SG_PHASE_PROFILE
-                    if (e_amb) ph[15] += clock64() - ta_;
-                    ph[14] += 1;
-#endif
                     if (create) {
                         if (lane < LPR)   // the new representative's row comes out of the LDS tile
                             st16(X + (size_t)me * ROWB + lane * 16, *reinterpret_cast<const uint4 *>(&sm.kt[etok * KS + lane * 16]));
@@ -599,7 +577,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 base += __builtin_popcountll(cmask[h]);
             }
             m = base;
-            SG_PH(5);
 
             // ---- sampling: p_j from the running mu (sequential double adds, token order); the coins wait for the
             //      coin pass
@@ -624,7 +601,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 }
             }
             if (lane == 0) sm.mnew = m;
-            SG_PH(6);
         }
 
         // ---- per-cluster reservoirs (UpdateSoftmaxNormalizer of Algorithm 1 as printed): a token that joins a
@@ -676,21 +652,15 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 }
             }
         }
-
-        SG_PH(7);
-        SG_PH(8);
         span_fill += nt;
         if (span_fill + T > kCoinSpan || c0 + T >= ge1) {
             __syncthreads();
-            SG_PH(9);
             coin_pass(span0, span_fill);
-            SG_PH(10);
             span0 += span_fill;
             span_fill = 0;
         }
         __syncthreads();   // LDS is reused by the next chunk; new rows are visible
         m = sm.mnew;
-        SG_PH(11);
     }
 
     // ---- the ring ends up holding the last min(n, w) tokens of the call
@@ -709,11 +679,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
         st.m[sid] = m;
         st.mu[sid] = mu;
     }
-#ifdef SG_PHASE_PROFILE
-    SG_PH(12);
-    if (tid == 0)
-        for (int i = 0; i < 16; ++i) atomicAdd(&g_phase[i], (unsigned long long)ph[i]);
-#endif
 }
 
 }  // namespace sg

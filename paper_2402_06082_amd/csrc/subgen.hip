@@ -918,12 +918,3 @@ int subgen_last_hip_error(const subgen_ctx *c) { return c ? c->last_hip : 0; }
 
 }  // extern "C"
 
-#ifdef SG_PHASE_PROFILE
-extern "C" int subgen_debug_phases(unsigned long long *out, int reset)
-{
-    unsigned long long z[16] = {0};
-    if (hipMemcpyFromSymbol(out, HIP_SYMBOL(sg::g_phase), sizeof(z)) != hipSuccess) return -1;
-    if (reset && hipMemcpyToSymbol(HIP_SYMBOL(sg::g_phase), z, sizeof(z)) != hipSuccess) return -1;
-    return 0;
-}
-#endif
