@@ -73,36 +73,12 @@ struct SmemIngest {
     alignas(16) char kt[T * KS];
 };
 
-// min(a, b) as the one instruction it is (fminf first quiets its operands with one more instruction each); a NaN
-// operand is ignored
-__device__ __forceinline__ float min_f32(const float a, const float b)
-{
-    float r;
-    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-
 // median of three signed integers
 __device__ __forceinline__ int med3_i32(const int a, const int b, const int c)
 {
     int r;
     asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
-}
-
-// Candidate list of a token: nearest (b1, i1), runner-up (b2, i2) and the third-smallest value b3 of the approximate
-// distances.  Insert candidate (d, idx).  Equal values keep the order of arrival: the decision never rests on
-// that order, since equal approximations are within the error bound of each other and go to the exact comparison.
-__device__ __forceinline__ void top3_insert(const float d, const int idx, float &b1, int &i1, float &b2, int &i2, float &b3)
-{
-    const bool lt1 = d < b1, lt2 = d < b2;
-    b3 = __builtin_amdgcn_fmed3f(b2, b3, d);
-    int t2 = lt2 ? idx : i2;
-    asm("" : "+v"(t2));   // two plain selects (nested, the compiler turns them into branches)
-    i2 = lt1 ? i1 : t2;
-    b2 = __builtin_amdgcn_fmed3f(b1, b2, d);
-    i1 = lt1 ? idx : i1;
-    b1 = min_f32(b1, d);
 }
 
 // Lane exchanges of gfx950 that stay in the vector unit.  from_row_above: lanes of DPP row 0 get the value of the

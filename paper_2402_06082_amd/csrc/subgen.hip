@@ -142,6 +142,14 @@ bool mfma_supported(int dtype, int LPR, int G) { return dtype == SUBGEN_BF16 && 
 
 // rows of 64 or 128 elements: the update alone scans the representatives straight from HBM; attend and step
 // stage the rows through LDS tiles and run the value products on the matrix cores as well
+// wavefronts per workgroup of the LDS-tiled kernels: the fused step runs four workgroups of two wavefronts per CU
+// (its serial update phases overlap with three other streams instead of one), attend alone two of four
+#ifndef SG_TILE_WAVES_ATT
+#define SG_TILE_WAVES_ATT 4
+#endif
+#ifndef SG_TILE_WAVES_UPD
+#define SG_TILE_WAVES_UPD 2
+#endif
 template <int NK, int G>
 void launch_tile_mode(Mode mode, dim3 grid, hipStream_t s, const State &st, const Call &call)
 {
@@ -150,10 +158,10 @@ void launch_tile_mode(Mode mode, dim3 grid, hipStream_t s, const State &st, cons
             hipLaunchKernelGGL((sg::decode_mfma_kernel<NK, 1, true, false>), grid, dim3(sg::kWG), 0, s, st, call);
             break;
         case MODE_ATTEND:
-            hipLaunchKernelGGL((sg::decode_tile_kernel<NK, G, false>), grid, dim3(sg::kWG), 0, s, st, call);
+            hipLaunchKernelGGL((sg::decode_tile_kernel<NK, G, false, SG_TILE_WAVES_ATT>), grid, dim3(64 * SG_TILE_WAVES_ATT), 0, s, st, call);
             break;
         case MODE_STEP:
-            hipLaunchKernelGGL((sg::decode_tile_kernel<NK, G, true>), grid, dim3(sg::kWG), 0, s, st, call);
+            hipLaunchKernelGGL((sg::decode_tile_kernel<NK, G, true, SG_TILE_WAVES_UPD>), grid, dim3(64 * SG_TILE_WAVES_UPD), 0, s, st, call);
             break;
     }
 }

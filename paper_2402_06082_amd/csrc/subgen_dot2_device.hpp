@@ -34,8 +34,8 @@ struct SmemDot2 {
     alignas(16) uint4 ekrow[16], evrow[16];   // the evicted (key, value) rows, for the sampling copies
     alignas(16) uint4 nkrow[16], nvrow[16];   // the new token's rows (they enter the ring at the end of the step)
     uint32_t accm[NW == 8 ? 256 : 1];         // slots that took the evicted token in this step (hoisted variant)
-    float wb1[NW], wb2[NW], wnx[NW];
-    int wi1[NW];
+    float wb1[NW], wb2[NW], wb3[NW], wnx[NW];
+    int wi1[NW], wi2[NW];
     double wbest[NW];
     int widx[NW];
     float bx;
@@ -135,8 +135,8 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
 
     // ---- one pass over the representatives: approximate squared distance to the evicted key and
     //      count-weighted exp(<q, x_i>) for the softmax normaliser
-    float b1 = INFINITY, b2 = INFINITY, nxmax = 0.f;
-    int i1 = -1;
+    Cand3 cd;   // nearest representatives of the evicted key by approximate distance
+    float nxmax = 0.f;
     // (key, value) row pairs: request a batch into registers / consume it (sampled pairs and window)
     const float *const svn_base = st.svn + sid * (size_t)st.sS;
     const int fill = (int)(n_after < st.w ? n_after : st.w);
@@ -198,14 +198,7 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
                     if (evict) {
                         const float dk = row_sum16(dot8_bf16(raw[u], ek));
                         if (valid) {
-                            const float dt = fmaf(-2.f, dk, nx[u] + nk);
-                            if (dt < b1) {
-                                b2 = b1;
-                                b1 = dt;
-                                i1 = r;
-                            } else if (dt < b2) {
-                                b2 = dt;
-                            }
+                            cd.insert(fmaf(-2.f, dk, nx[u] + nk), r);
                             nxmax = fmaxf(nxmax, nx[u]);
                         }
                     }
@@ -220,53 +213,42 @@ __device__ __forceinline__ void token_step_dot2(const State &st, const size_t si
     uint4 xr = make_uint4(0, 0, 0, 0);
     if constexpr (UPD) {
         if (evict) {
-            // ---- best / runner-up of the approximate distances over the workgroup
+            // ---- the nearest candidates over the workgroup
 #pragma unroll
             for (int o = 16; o < 64; o <<= 1) {
-                const float ob1 = __shfl_xor(b1, o), ob2 = __shfl_xor(b2, o);
-                const int oi1 = __shfl_xor(i1, o);
-                if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
-                    b2 = fminf(b1, ob2);
-                    b1 = ob1;
-                    i1 = oi1;
-                } else {
-                    b2 = fminf(b2, ob1);
-                }
+                const float ob1 = __shfl_xor(cd.b1, o), ob2 = __shfl_xor(cd.b2, o), ob3 = __shfl_xor(cd.b3, o);
+                const int oi1 = __shfl_xor(cd.i1, o), oi2 = __shfl_xor(cd.i2, o);
+                cd.merge(ob1, oi1, ob2, oi2, ob3);
                 nxmax = fmaxf(nxmax, __shfl_xor(nxmax, o));
             }
             if (lane == 0) {
-                sm.wb1[wave] = b1;
-                sm.wb2[wave] = b2;
-                sm.wi1[wave] = i1;
+                sm.wb1[wave] = cd.b1;
+                sm.wb2[wave] = cd.b2;
+                sm.wb3[wave] = cd.b3;
+                sm.wi1[wave] = cd.i1;
+                sm.wi2[wave] = cd.i2;
                 sm.wnx[wave] = nxmax;
             }
             lds_barrier();
-            b1 = sm.wb1[0]; b2 = sm.wb2[0]; i1 = sm.wi1[0]; nxmax = sm.wnx[0];
+            cd.b1 = sm.wb1[0]; cd.b2 = sm.wb2[0]; cd.b3 = sm.wb3[0]; cd.i1 = sm.wi1[0]; cd.i2 = sm.wi2[0];
+            nxmax = sm.wnx[0];
 #pragma unroll
             for (int wv = 1; wv < NW; ++wv) {
-                const float ob1 = sm.wb1[wv], ob2 = sm.wb2[wv];
-                const int oi1 = sm.wi1[wv];
-                if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
-                    b2 = fminf(b1, ob2);
-                    b1 = ob1;
-                    i1 = oi1;
-                } else {
-                    b2 = fminf(b2, ob1);
-                }
+                cd.merge(sm.wb1[wv], sm.wi1[wv], sm.wb2[wv], sm.wi2[wv], sm.wb3[wv]);
                 nxmax = fmaxf(nxmax, sm.wnx[wv]);
             }
             // ---- decide from D~ when the error bound allows it, else re-evaluate exactly
             const float thr = (float)st.delta2;
             const float emax = kDistEps * (nxmax + nk);
             bool join;
-            int bidx = i1;
-            const bool ambiguous = distances_ambiguous(b1, b2, thr, emax, m);
+            int bidx = cd.i1;
+            const bool ambiguous = distances_ambiguous(cd.b1, cd.b2, thr, emax, m);
             if (ambiguous) {
                 double best;
-                exact_nearest<LPR, NW>(X, m, ek, sm.wbest, sm.widx, best, bidx);
+                exact_decide<LPR, NW>(X, m, ek, cd, emax, sm.wbest, sm.widx, best, bidx);
                 join = bidx >= 0 && best <= st.delta2;
             } else {
-                join = m > 0 && b1 <= thr;
+                join = m > 0 && cd.b1 <= thr;
             }
             const Decision dec = decide_cluster(join, bidx, m, st.Mcap);
             const bool forced = dec.forced, created = dec.created;

@@ -67,14 +67,50 @@ template <int NK, int G>
 struct SmemMfma {
     alignas(16) uint4 ekrow[NK * 4], evrow[NK * 4];   // the evicted (key, value) rows, for the sampling copies
     // approximate nearest-center candidates per wavefront
-    float wb1[kWaves], wb2[kWaves], wnx[kWaves];
-    int wi1[kWaves];
+    float wb1[kWaves], wb2[kWaves], wb3[kWaves], wnx[kWaves];
+    int wi1[kWaves], wi2[kWaves];
     // exact re-evaluation
     double wbest[kWaves];
     int widx[kWaves];
     float bx[G];
     float wmx[kWaves][G], wden[kWaves][G];
     float wacc[kWaves][G][NK * 32];
+};
+
+// min(a, b) as the one instruction it is (fminf first quiets its operands with one more instruction each); a NaN
+// operand is ignored
+__device__ __forceinline__ float min_f32(const float a, const float b)
+{
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// Candidate list of a token: nearest (b1, i1), runner-up (b2, i2) and the third-smallest value b3 of the approximate
+// distances.  Insert candidate (d, idx).  Equal values keep the order of arrival: the decision never rests on
+// that order, since equal approximations are within the error bound of each other and go to the exact comparison.
+__device__ __forceinline__ void top3_insert(const float d, const int idx, float &b1, int &i1, float &b2, int &i2, float &b3)
+{
+    const bool lt1 = d < b1, lt2 = d < b2;
+    b3 = __builtin_amdgcn_fmed3f(b2, b3, d);
+    int t2 = lt2 ? idx : i2;
+    asm("" : "+v"(t2));   // two plain selects (nested, the compiler turns them into branches)
+    i2 = lt1 ? i1 : t2;
+    b2 = __builtin_amdgcn_fmed3f(b1, b2, d);
+    i1 = lt1 ? idx : i1;
+    b1 = min_f32(b1, d);
+}
+struct Cand3 {
+    float b1 = INFINITY, b2 = INFINITY, b3 = INFINITY;
+    int i1 = -1, i2 = -1;
+    __device__ __forceinline__ void insert(const float d, const int idx) { top3_insert(d, idx, b1, i1, b2, i2, b3); }
+    // another list over other rows
+    __device__ __forceinline__ void merge(const float ob1, const int oi1, const float ob2, const int oi2, const float ob3)
+    {
+        insert(ob1, oi1);
+        insert(ob2, oi2);
+        b3 = min_f32(b3, ob3);
+    }
 };
 
 // Exact squared distance of two bf16 rows in double precision: each of the LPR lanes of a row holds one 16-byte
@@ -148,6 +184,31 @@ __device__ __forceinline__ void exact_nearest(const char *X, int m, const uint4 
         }
     }
     __syncthreads();
+}
+
+// The exact decision for an ambiguous token: every exact distance is at most emax away from its approximation, so
+// the nearest representative is among those within 2 emax of the smallest approximation.  When the third-smallest
+// approximation is beyond that, these are the best and (perhaps) the runner-up, and their one or two exact
+// distances decide (every wavefront evaluates them by itself: no barrier); otherwise the whole table is
+// re-evaluated.  `cd` is the same in every lane of the workgroup.  Block-uniform result.
+template <int LPR, int NW = kWaves>
+__device__ __forceinline__ void exact_decide(const char *X, const int m, const uint4 &ek, const Cand3 &cd, const float emax,
+                                             double *wbest, int *widx, double &best, int &bidx)
+{
+    constexpr size_t ROWB = (size_t)LPR * 16;
+    const int lane = threadIdx.x & 63, col = lane % LPR, sub = lane / LPR;
+    if (cd.i1 >= 0 && (cd.b3 == INFINITY || cd.b3 - cd.b1 > 2.f * emax)) {
+        const int r2 = cd.b2 - cd.b1 > 2.f * emax ? -1 : cd.i2;
+        const int rsel = sub == 0 ? cd.i1 : (sub == 1 ? r2 : -1);
+        double dist = INFINITY;
+        if (rsel >= 0) dist = exact_distance<LPR>(ld16(X + (size_t)rsel * ROWB + col * 16), ek);
+        const double d1 = __shfl(dist, 0), d2 = __shfl(dist, LPR);
+        const bool second = r2 >= 0 && (d2 < d1 || (d2 == d1 && r2 < cd.i1));
+        best = second ? d2 : d1;
+        bidx = second ? r2 : cd.i1;
+    } else {
+        exact_nearest<LPR, NW>(X, m, ek, wbest, widx, best, bidx);
+    }
 }
 
 // broadcast lane g of every quad (DPP quad_perm [g,g,g,g])
@@ -289,8 +350,8 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
 
     // ---- one pass over the representatives, 16 rows per wavefront step; the loads of the next step are
     //      issued before the arithmetic of the current one (two register sets, ping-pong)
-    float b1 = INFINITY, b2 = INFINITY, nxmax = 0.f;
-    int i1 = -1;
+    Cand3 cd;   // nearest representatives of the evicted key by approximate distance (key-role lanes)
+    float nxmax = 0.f;
     if ((UPD && evict) || ATT) {
         struct Group {
             uint4 a[NK];
@@ -330,14 +391,7 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         if (row0 + r < m) {
-                            const float dt = fmaf(-2.f, c[r], nxr[r] + nk);
-                            if (dt < b1) {
-                                b2 = b1;
-                                b1 = dt;
-                                i1 = row0 + r;
-                            } else if (dt < b2) {
-                                b2 = dt;
-                            }
+                            cd.insert(fmaf(-2.f, c[r], nxr[r] + nk), row0 + r);
                             nxmax = fmaxf(nxmax, nxr[r]);
                         }
                     }
@@ -361,53 +415,42 @@ __device__ __forceinline__ void token_step_mfma(const State &st, const size_t si
 
     if constexpr (UPD) {
         if (evict) {
-            // ---- best / runner-up of the approximate distances: over the four lane rows, then the wavefronts
+            // ---- the nearest candidates: over the four lane rows, then the wavefronts
 #pragma unroll
             for (int o = 16; o < 64; o <<= 1) {
-                const float ob1 = __shfl_xor(b1, o), ob2 = __shfl_xor(b2, o);
-                const int oi1 = __shfl_xor(i1, o);
-                if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
-                    b2 = fminf(b1, ob2);
-                    b1 = ob1;
-                    i1 = oi1;
-                } else {
-                    b2 = fminf(b2, ob1);
-                }
+                const float ob1 = __shfl_xor(cd.b1, o), ob2 = __shfl_xor(cd.b2, o), ob3 = __shfl_xor(cd.b3, o);
+                const int oi1 = __shfl_xor(cd.i1, o), oi2 = __shfl_xor(cd.i2, o);
+                cd.merge(ob1, oi1, ob2, oi2, ob3);
                 nxmax = fmaxf(nxmax, __shfl_xor(nxmax, o));
             }
             if (lane == KR) {   // a key-role lane of lane row 0
-                sm.wb1[wave] = b1;
-                sm.wb2[wave] = b2;
-                sm.wi1[wave] = i1;
+                sm.wb1[wave] = cd.b1;
+                sm.wb2[wave] = cd.b2;
+                sm.wb3[wave] = cd.b3;
+                sm.wi1[wave] = cd.i1;
+                sm.wi2[wave] = cd.i2;
                 sm.wnx[wave] = nxmax;
             }
             __syncthreads();
-            b1 = sm.wb1[0]; b2 = sm.wb2[0]; i1 = sm.wi1[0]; nxmax = sm.wnx[0];
+            cd.b1 = sm.wb1[0]; cd.b2 = sm.wb2[0]; cd.b3 = sm.wb3[0]; cd.i1 = sm.wi1[0]; cd.i2 = sm.wi2[0];
+            nxmax = sm.wnx[0];
 #pragma unroll
             for (int wv = 1; wv < kWaves; ++wv) {
-                const float ob1 = sm.wb1[wv], ob2 = sm.wb2[wv];
-                const int oi1 = sm.wi1[wv];
-                if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
-                    b2 = fminf(b1, ob2);
-                    b1 = ob1;
-                    i1 = oi1;
-                } else {
-                    b2 = fminf(b2, ob1);
-                }
+                cd.merge(sm.wb1[wv], sm.wi1[wv], sm.wb2[wv], sm.wi2[wv], sm.wb3[wv]);
                 nxmax = fmaxf(nxmax, sm.wnx[wv]);
             }
             // ---- decide from D~ when the error bound allows it, else re-evaluate exactly
             const float thr = (float)st.delta2;
             const float emax = kDistEps * (nxmax + nk);
             bool join;
-            int bidx = i1;
-            const bool ambiguous = distances_ambiguous(b1, b2, thr, emax, m);
+            int bidx = cd.i1;
+            const bool ambiguous = distances_ambiguous(cd.b1, cd.b2, thr, emax, m);
             if (ambiguous) {
                 double best;
-                exact_nearest<LPR>(X, m, ek, sm.wbest, sm.widx, best, bidx);
+                exact_decide<LPR>(X, m, ek, cd, emax, sm.wbest, sm.widx, best, bidx);
                 join = bidx >= 0 && best <= st.delta2;
             } else {
-                join = m > 0 && b1 <= thr;
+                join = m > 0 && cd.b1 <= thr;
             }
             const Decision dec = decide_cluster(join, bidx, m, st.Mcap);
             const bool forced = dec.forced, created = dec.created;

@@ -27,11 +27,13 @@
 namespace sg {
 
 constexpr int kTileRows = 32;
-constexpr int kTiles = 4;                       // tiles staged per iteration = wavefronts
+constexpr int kTiles = 4;                       // tiles staged per iteration of a four-wavefront workgroup
 constexpr int kSuper = kTileRows * kTiles;      // rows staged per iteration
 
-template <int NK, int G>
+// NWV wavefronts per workgroup = tiles staged per iteration
+template <int NK, int G, int NWV>
 struct SmemTile {
+    static constexpr int kWaves = NWV, kTiles = NWV, kSuper = kTileRows * NWV;
     static constexpr int KS = NK * 64 + 16;   // key tile row stride (bytes): 16-byte operand reads hit distinct banks
     static constexpr int VS = NK * 64 + 32;   // value tile row stride: the transposing reads hit distinct banks
     alignas(16) char kt[kTiles][kTileRows * KS];
@@ -40,18 +42,20 @@ struct SmemTile {
     alignas(16) float xnrow[kSuper];          // ||x_i||^2 of each staged representative (update)
     alignas(16) uint4 ekrow[NK * 4], evrow[NK * 4];   // the evicted (key, value) rows, for the sampling copies
     alignas(16) uint4 qrow[G][NK * 4];                // the queries in plain row layout (extra normaliser term)
-    float wb1[kWaves], wb2[kWaves], wnx[kWaves];
-    int wi1[kWaves];
+    float wb1[kWaves], wb2[kWaves], wb3[kWaves], wnx[kWaves];
+    int wi1[kWaves], wi2[kWaves];
     double wbest[kWaves];
     int widx[kWaves];
     float bx[G];
     float wmx[kWaves][16], wden[kWaves][16];
 };
 
-template <int NK, int G, bool UPD>
-__global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, const Call call)
+template <int NK, int G, bool UPD, int NWV>
+__global__ __launch_bounds__(64 * NWV, 2) void decode_tile_kernel(const State st, const Call call)
 {
-    static_assert(kWaves == kTiles, "one tile per wavefront and iteration");
+    // workgroup shape of this kernel (these names hide the library-wide ones): NWV wavefronts, one tile per
+    // wavefront and iteration
+    constexpr int kWG = 64 * NWV, kWaves = NWV, kSuper = kTileRows * NWV;
     static_assert(G + 8 <= 16, "the queries and the eight key copies share the 16 operand columns");
     constexpr int CPR = 4 * NK;              // 16-byte chunks per row
     constexpr int LPR = CPR;                 // lanes per row in the plain row layout (copies, norms)
@@ -59,9 +63,9 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
     constexpr size_t ROWB = (size_t)NK * 64;
     constexpr int D = NK * 32;
     constexpr int NCB = NK * 2;              // 16-column blocks of the output
-    constexpr int KS = SmemTile<NK, G>::KS, VS = SmemTile<NK, G>::VS;
+    constexpr int KS = SmemTile<NK, G, NWV>::KS, VS = SmemTile<NK, G, NWV>::VS;
     constexpr int LD = kSuper * CPR / kWG;   // 16-byte loads per thread and operand per iteration
-    __shared__ SmemTile<NK, G> sm;
+    __shared__ SmemTile<NK, G, NWV> sm;
 
     const size_t sid = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -189,8 +193,8 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
     floatx4_t acc[NCB];                // O[column 4L + r][output column 16 cb + n16]
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) acc[cb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-    float b1 = INFINITY, b2 = INFINITY, nxmax = 0.f;   // approximate nearest representative (key column)
-    int i1 = -1;
+    Cand3 cd;   // nearest representatives of the evicted key by approximate distance (key columns)
+    float nxmax = 0.f;
 
     // full: global memory written by other lanes of the workgroup since the last full barrier is read after it
     auto stage = [&](auto kind_c, const int nrows, const int r0, const float mus, const bool full) {
@@ -249,14 +253,7 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
                 const float nx = jr == 0 ? xs.x : (jr == 1 ? xs.y : (jr == 2 ? xs.z : xs.w));
                 const int row = trow + (kj < 4 ? 0 : 16) + 4 * L + jr;   // ascending from tile to tile
                 if (row < nrows) {
-                    const float dt = fmaf(-2.f, sc, nx + nk);
-                    if (dt < b1) {
-                        b2 = b1;
-                        b1 = dt;
-                        i1 = row;
-                    } else if (dt < b2) {
-                        b2 = dt;
-                    }
+                    cd.insert(fmaf(-2.f, sc, nx + nk), row);
                     nxmax = fmaxf(nxmax, nx);
                 }
             }
@@ -365,59 +362,49 @@ __global__ __launch_bounds__(kWG, 2) void decode_tile_kernel(const State st, con
     };
     if constexpr (UPD) {
         if (evict) {
-            // ---- best / runner-up of the approximate distances: over the lanes (the other columns hold +inf):
-            //      the 16 lanes of a DPP row by rotations, then the four rows; then the wavefronts
-            auto merge = [&](const float ob1, const float ob2, const int oi1, const float onx)
-                             __attribute__((always_inline)) {
-                if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
-                    b2 = fminf(b1, ob2);
-                    b1 = ob1;
-                    i1 = oi1;
-                } else {
-                    b2 = fminf(b2, ob1);
-                }
+            // ---- the nearest candidates: over the lanes (the other columns hold +inf): the 16 lanes of a DPP row
+            //      by rotations, then the four rows; then the wavefronts
+            auto merge = [&](const float ob1, const int oi1, const float ob2, const int oi2, const float ob3,
+                             const float onx) __attribute__((always_inline)) {
+                cd.merge(ob1, oi1, ob2, oi2, ob3);
                 nxmax = fmaxf(nxmax, onx);
             };
-            merge(row_ror<8>(b1), row_ror<8>(b2), row_ror<8>(i1), row_ror<8>(nxmax));
-            merge(row_ror<4>(b1), row_ror<4>(b2), row_ror<4>(i1), row_ror<4>(nxmax));
-            merge(row_ror<2>(b1), row_ror<2>(b2), row_ror<2>(i1), row_ror<2>(nxmax));
-            merge(row_ror<1>(b1), row_ror<1>(b2), row_ror<1>(i1), row_ror<1>(nxmax));
+            merge(row_ror<8>(cd.b1), row_ror<8>(cd.i1), row_ror<8>(cd.b2), row_ror<8>(cd.i2), row_ror<8>(cd.b3), row_ror<8>(nxmax));
+            merge(row_ror<4>(cd.b1), row_ror<4>(cd.i1), row_ror<4>(cd.b2), row_ror<4>(cd.i2), row_ror<4>(cd.b3), row_ror<4>(nxmax));
+            merge(row_ror<2>(cd.b1), row_ror<2>(cd.i1), row_ror<2>(cd.b2), row_ror<2>(cd.i2), row_ror<2>(cd.b3), row_ror<2>(nxmax));
+            merge(row_ror<1>(cd.b1), row_ror<1>(cd.i1), row_ror<1>(cd.b2), row_ror<1>(cd.i2), row_ror<1>(cd.b3), row_ror<1>(nxmax));
 #pragma unroll
             for (int o = 16; o < 64; o <<= 1)
-                merge(__shfl_xor(b1, o), __shfl_xor(b2, o), __shfl_xor(i1, o), __shfl_xor(nxmax, o));
+                merge(__shfl_xor(cd.b1, o), __shfl_xor(cd.i1, o), __shfl_xor(cd.b2, o), __shfl_xor(cd.i2, o),
+                      __shfl_xor(cd.b3, o), __shfl_xor(nxmax, o));
             if (lane == 0) {
-                sm.wb1[wave] = b1;
-                sm.wb2[wave] = b2;
-                sm.wi1[wave] = i1;
+                sm.wb1[wave] = cd.b1;
+                sm.wb2[wave] = cd.b2;
+                sm.wb3[wave] = cd.b3;
+                sm.wi1[wave] = cd.i1;
+                sm.wi2[wave] = cd.i2;
                 sm.wnx[wave] = nxmax;
             }
             lds_barrier();
-            b1 = sm.wb1[0]; b2 = sm.wb2[0]; i1 = sm.wi1[0]; nxmax = sm.wnx[0];
+            cd.b1 = sm.wb1[0]; cd.b2 = sm.wb2[0]; cd.b3 = sm.wb3[0]; cd.i1 = sm.wi1[0]; cd.i2 = sm.wi2[0];
+            nxmax = sm.wnx[0];
 #pragma unroll
             for (int wv = 1; wv < kWaves; ++wv) {
-                const float ob1 = sm.wb1[wv], ob2 = sm.wb2[wv];
-                const int oi1 = sm.wi1[wv];
-                if (ob1 < b1 || (ob1 == b1 && (uint32_t)oi1 < (uint32_t)i1)) {
-                    b2 = fminf(b1, ob2);
-                    b1 = ob1;
-                    i1 = oi1;
-                } else {
-                    b2 = fminf(b2, ob1);
-                }
+                cd.merge(sm.wb1[wv], sm.wi1[wv], sm.wb2[wv], sm.wi2[wv], sm.wb3[wv]);
                 nxmax = fmaxf(nxmax, sm.wnx[wv]);
             }
             // ---- decide from D~ when the error bound allows it, else re-evaluate exactly
             const float thr = (float)st.delta2;
             const float emax = kDistEps * (nxmax + nk);
             bool join;
-            int bidx = i1;
-            const bool ambiguous = distances_ambiguous(b1, b2, thr, emax, m);
+            int bidx = cd.i1;
+            const bool ambiguous = distances_ambiguous(cd.b1, cd.b2, thr, emax, m);
             if (ambiguous) {
                 double best;
-                exact_nearest<LPR>(X, m, ek, sm.wbest, sm.widx, best, bidx);
+                exact_decide<LPR, NWV>(X, m, ek, cd, emax, sm.wbest, sm.widx, best, bidx);
                 join = bidx >= 0 && best <= st.delta2;
             } else {
-                join = m > 0 && b1 <= thr;
+                join = m > 0 && cd.b1 <= thr;
             }
             const Decision dec = decide_cluster(join, bidx, m, st.Mcap);
             const bool forced = dec.forced, created = dec.created;
