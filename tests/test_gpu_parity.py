@@ -512,6 +512,49 @@ def test_matrix_core_path_exact_decisions_on_lattice_keys(g, d, kernel_path):
         assert np.array_equal(ing.export_state(sid).assign, sg.export_state(sid).assign)
 
 
+@pytest.mark.parametrize("g,d,kernel_path", [(1, 128, 0), (4, 128, 0), (1, 64, 0), (1, 256, 0), (1, 128, 1)])
+def test_twin_representatives_decided_by_two_exact_distances(g, d, kernel_path):
+    """Every site of the key distribution holds two representatives a little more than delta apart, and the tokens
+    fall almost half-way between them: the gap between the nearest and the second nearest representative is within
+    the error bound of the approximate distances for a large share of the tokens (and far from a third one), so the
+    kernels decide from the exact distances to just these two.  Assignments must equal the oracle's (fp64)."""
+    b = binding()
+    S, sites, n_prefix, steps, s, w = 6, 5, 900, 150, 24, 16
+    delta, a, sigma = 2.0, 1.02, 0.01
+    gen = torch.Generator(device="cpu").manual_seed(4321 + d + g)
+    n = n_prefix + steps
+    C = torch.randn(S, sites, d, generator=gen)
+    C = 8.0 * C / C.norm(dim=-1, keepdim=True)
+    U = torch.randn(S, sites, d, generator=gen)
+    U = U / U.norm(dim=-1, keepdim=True)
+    site = torch.randint(0, sites, (S, n), generator=gen)
+    K = torch.gather(C, 1, site[..., None].expand(S, n, d)) + sigma * torch.randn(S, n, d, generator=gen)
+    for j in range(sites):        # the first 2 * sites tokens are the twins themselves
+        K[:, 2 * j] = C[:, j] + a * U[:, j]
+        K[:, 2 * j + 1] = C[:, j] - a * U[:, j]
+    V = torch.randn(S, n, d, generator=gen)
+    Q = torch.randn(S, steps, g, d, generator=gen) / d ** 0.5
+    K, V, Q = (t.to(torch.bfloat16).to(DEV) for t in (K, V, Q))
+    sg = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, q_per_stream=g, assign_log_tokens=n, seed=5, device=DEV,
+                  kernel_path=kernel_path, split_workgroups=1)
+    oset = OracleSet(list(range(S)), d, delta, s, w, seed=5)
+    for lo, hi in [(0, 7), (7, 300), (300, 301), (301, n_prefix)]:        # ragged chunks, also across the twins
+        sg.ingest_prefix(K[:, lo:hi], V[:, lo:hi])
+        oset.ingest(K[:, lo:hi], V[:, lo:hi])
+    outs = torch.stack([sg.step(K[:, n_prefix + t].contiguous(), V[:, n_prefix + t].contiguous(), Q[:, t].contiguous())
+                        for t in range(steps)])
+    oset.decode(K[:, n_prefix:], V[:, n_prefix:], Q)
+    forced = oset.reconcile(sg)
+    assert forced <= 2, forced        # margins below 1e-5 relative are possible here, but rare
+    assert rel_l2(outs.cpu().numpy(), oset.reference()).max() <= REL_L2_TOL
+    for o in oset.oracles:
+        assert o.m == 2 * sites
+        thr, gap = o.margins()
+        # squared-distance gaps below the kernels' bound 2 * 2^-14 (||x||^2 + ||k||^2) ~ 0.016 at distances ~ 1.0
+        # (0.0075 relative on the distance) are what this test is about
+        assert (gap < 0.005).sum() > 100
+
+
 @pytest.mark.parametrize("device_counter", [False, True])
 @pytest.mark.parametrize("cfgname,g", [("cfg2", 1), ("cfg5", 4), ("cfg1b", 1)])
 def test_export_import_resumes_bit_identically(cfgname, g, device_counter):
