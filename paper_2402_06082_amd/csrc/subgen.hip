@@ -298,7 +298,8 @@ int launch_decode(subgen_ctx *c, Mode mode, const Call &call, int G)
     // those go to the matrix cores.
     // (a query alone, with streams enough to fill the chip, is 3 % faster on the LDS-tiled kernel below: it has no
     // update whose serial part would need the row path's higher occupancy to hide)
-    if (mfma && G == 1 && c->LPR == 16 && (mode != MODE_ATTEND || c->wide)) {
+    // (the update alone looks up one key, however many queries the context has: it takes the row path as well)
+    if (mfma && c->LPR == 16 && (mode == MODE_UPDATE || (G == 1 && (mode != MODE_ATTEND || c->wide)))) {
         if (c->wide) launch_dot2<8>(mode, grid, c->stream, c->st, call);   // few streams: wide workgroups, hoisted loads
         else launch_dot2<4>(mode, grid, c->stream, c->st, call);
         const hipError_t e = hipGetLastError();
