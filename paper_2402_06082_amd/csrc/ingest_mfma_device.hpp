@@ -31,6 +31,7 @@
 // during the call come first from the ring, then from the call's own input;
 // the ring is rewritten once at the end.
 #pragma once
+#include <cstddef>
 #include <type_traits>
 
 #include "subgen_dot2_device.hpp"
@@ -158,50 +159,58 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
     double mu = st.mu[sid];
     const float thr = (float)st.delta2;
 
-    // ---- coin pass over the evicted tokens [g0, g0 + cnt) whose probabilities are in LDS: every lane takes one
-    //      4-slot block (and one sub-range of the tokens, so that all lanes have coins to draw) and walks its
-    //      tokens from the oldest to the newest; the last accept per slot is the one that stays
-    auto coin_pass = [&](int64_t g0, int cnt) {
-        const int nblk = (st.s + 3) >> 2;
-        int nsplit = 1;
-        while (nsplit < 16 && nblk * nsplit * 2 <= kWG) nsplit *= 2;
-        const int per = kCoinSpan / nsplit;
-        for (int item = tid; item < ((nblk * nsplit + kWG - 1) / kWG) * kWG; item += kWG) {
-            const int blk = item / nsplit, part = item % nsplit;
-            int last[4] = {-1, -1, -1, -1};
-            if (blk < nblk) {
-                const int lo = part * per, hi = (part + 1) * per < cnt ? (part + 1) * per : cnt;
+    // ---- coin pass over the evicted tokens [g0, g0 + cnt) whose probabilities are in LDS.  A wavefront takes 64
+    //      consecutive 4-slot blocks (one per lane) and one sub-range of the tokens, so the token is the same in
+    //      all its lanes and everything of the Philox rounds that depends on the token alone runs on the scalar
+    //      unit; every lane walks the tokens from the oldest to the newest and keeps the newest accept per slot.
+    //      The sub-ranges meet in LDS (maximum per slot; the candidate lists of the scan are dead by now and lend
+    //      their memory), then one lane per accepted slot copies the rows.
+    auto coin_pass = [&](const int64_t g0, const int cnt) {
+        using Sm = SmemIngest<NK, T, RES>;
+        constexpr int kLastCap = 5 * kWaves * T;   // slots per segment
+        static_assert(offsetof(Sm, wi2) + sizeof(sm.wi2) - offsetof(Sm, wb1) == kLastCap * sizeof(int),
+                      "the candidate lists are one block of memory");
+        int *const lastbuf = reinterpret_cast<int *>(&sm.wb1[0][0]);
+        const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+        for (int seg0 = 0; seg0 < st.s; seg0 += kLastCap) {
+            const int nslot = st.s - seg0 < kLastCap ? st.s - seg0 : kLastCap;
+            const int nb = (nslot + 3) >> 2, ngrp = (nb + 63) >> 6;
+            int nparts = 1;   // sub-ranges of the tokens, so that all wavefronts have coins to draw
+            while (ngrp * nparts * 2 <= kWaves) nparts *= 2;
+            const int per = (cnt + nparts - 1) / nparts;
+            if (seg0 > 0) __syncthreads();   // the copies of the segment before this one have read the buffer
+            for (int i = tid; i < nslot; i += kWG) lastbuf[i] = -1;
+            __syncthreads();
+            for (int u = wave_s; u < ngrp * nparts; u += kWaves) {
+                const int blk = (u % ngrp) * 64 + lane, part = u / ngrp;
+                const int lo = part * per, hi = lo + per < cnt ? lo + per : cnt;
+                int last[4] = {-1, -1, -1, -1};
                 for (int jj = lo; jj < hi; ++jj) {   // oldest first: a later accept overwrites an earlier one
                     const uint32_t lim = sm.plim[jj];
                     if (lim != 0u) {
-                        const uint64_t ge = (uint64_t)(g0 + jj);
                         uint32_t r[4];
-                        coin_block(st, sid, (int64_t)ge, (uint32_t)blk, false, r);
+                        coin_block(st, sid, g0 + jj, (uint32_t)((seg0 >> 2) + blk), false, r);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) last[i] = r[i] <= lim ? jj : last[i];
                     }
                 }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (last[i] >= 0 && 4 * blk + i < nslot) atomicMax(&lastbuf[4 * blk + i], last[i]);
             }
-            // the largest token index over the sub-ranges wins
-            for (int o = 1; o < nsplit; o <<= 1) {
+            __syncthreads();
+            for (int sl = tid; sl < nslot; sl += kWG) {
+                const int l = lastbuf[sl];
+                if (l >= 0) {
+                    const int slot = seg0 + sl;
+                    const char *ks = krow_of(g0 + l), *vs = vrow_of(g0 + l);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) last[i] = max(last[i], __shfl_xor(last[i], o));
-            }
-            if (blk < nblk) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int slot = blk * 4 + i;
-                    const int owner = nsplit >= 4 ? i : (i % nsplit);   // spread the row copies over the lanes
-                    if (part == owner && last[i] >= 0 && slot < st.s) {
-                        const char *ks = krow_of(g0 + last[i]), *vs = vrow_of(g0 + last[i]);
-#pragma unroll
-                        for (int ch = 0; ch < CPR; ++ch) {
-                            st16(Ks + (size_t)slot * ROWB + ch * 16, ld16(ks + ch * 16));
-                            st16(Vs + (size_t)slot * ROWB + ch * 16, ld16(vs + ch * 16));
-                        }
-                        st.sidx[sid * (size_t)st.sS + slot] = (int32_t)(g0 + last[i]);
-                        st.svn[sid * (size_t)st.sS + slot] = sm.vnall[last[i]];
+                    for (int ch = 0; ch < CPR; ++ch) {
+                        st16(Ks + (size_t)slot * ROWB + ch * 16, ld16(ks + ch * 16));
+                        st16(Vs + (size_t)slot * ROWB + ch * 16, ld16(vs + ch * 16));
                     }
+                    st.sidx[sid * (size_t)st.sS + slot] = (int32_t)(g0 + l);
+                    st.svn[sid * (size_t)st.sS + slot] = sm.vnall[l];
                 }
             }
         }
