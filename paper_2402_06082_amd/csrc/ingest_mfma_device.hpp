@@ -22,8 +22,7 @@
 //      distance shows that no other row can be the nearest), else against the
 //      whole table;
 //   4. the sampling coins do not depend on the clustering: the chunks only
-//      leave each token's probability behind, and once per 512 (1024 with
-//      T = 64) evicted tokens (or at the end of the call) one pass draws the
+//      leave each token's probability behind, and once per 1024 evicted tokens (or at the end of the call) one pass draws the
 //      coins per 4-slot block; the last accepting token of a slot wins
 //      (sequential overwrite semantics), so a slot is copied at most once
 //      per pass.
@@ -53,15 +52,13 @@ struct SmemReservoir<T, false> {};
 
 template <int NK, int T, bool RES>
 struct SmemIngest {
-    // evicted tokens per coin pass (a multiple of the chunk); with 128-token chunks three workgroups per CU only
-    // fit with the shorter span
-    static constexpr int kSpan = T > 64 ? 512 : 1024;
+    // evicted tokens per coin pass (a multiple of the chunk)
+    static constexpr int kSpan = 1024;
     alignas(16) float nk[T];
     float vn[T];
-    // coin bound (coin_limit: a word r is accepted iff r <= bound; 0 = never) and ||v||^2 of the evicted tokens
-    // whose coins are still to be drawn (up to kSpan)
+    // coin bound (coin_limit: a word r is accepted iff r <= bound; 0 = never) of the evicted tokens whose coins are
+    // still to be drawn (up to kSpan)
     uint32_t plim[kSpan];
-    float vnall[kSpan];
     // candidate lists of the tokens, one per wavefront (each wavefront scans a quarter of the rows)
     float wb1[kWaves][T], wb2[kWaves][T], wb3[kWaves][T];
     int wi1[kWaves][T], wi2[kWaves][T];
@@ -204,13 +201,27 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                 if (l >= 0) {
                     const int slot = seg0 + sl;
                     const char *ks = krow_of(g0 + l), *vs = vrow_of(g0 + l);
+                    // ||v||^2 of the token once more, with the additions in the order of the chunk's norms (eight
+                    // products per 16-byte piece, then the pieces pairwise): the same double, the same float
+                    double piece[CPR];
 #pragma unroll
                     for (int ch = 0; ch < CPR; ++ch) {
                         st16(Ks + (size_t)slot * ROWB + ch * 16, ld16(ks + ch * 16));
-                        st16(Vs + (size_t)slot * ROWB + ch * 16, ld16(vs + ch * 16));
+                        const uint4 v16 = ld16(vs + ch * 16);
+                        st16(Vs + (size_t)slot * ROWB + ch * 16, v16);
+                        float vf[8];
+                        unpack<true>(v16, vf);
+                        double b = 0.0;
+#pragma unroll
+                        for (int v = 0; v < 8; ++v) b = fma((double)vf[v], (double)vf[v], b);
+                        piece[ch] = b;
                     }
+#pragma unroll
+                    for (int o = 1; o < CPR; o <<= 1)
+#pragma unroll
+                        for (int ch = 0; ch < CPR; ch += 2 * o) piece[ch] += piece[ch + o];
                     st.sidx[sid * (size_t)st.sS + slot] = (int32_t)(g0 + l);
-                    st.svn[sid * (size_t)st.sS + slot] = sm.vnall[l];
+                    st.svn[sid * (size_t)st.sS + slot] = (float)piece[0];
                 }
             }
         }
@@ -580,7 +591,6 @@ __global__ __launch_bounds__(kWG, 3) void ingest_mfma_kernel(const State st, con
                     const float pj = coin_probability(muj, vnj);
                     const bool valid = j < nth && nkj[h] < INFINITY;
                     sm.plim[span_fill + 64 * h + j] = valid ? coin_limit(pj) : 0u;
-                    sm.vnall[span_fill + 64 * h + j] = vnj;
                     const double mend = muj + vd;
                     mu = __shfl(mend, nth - 1);
                 }
