@@ -33,6 +33,14 @@
 
 namespace sg {
 
+// max(a, b, c) as the one instruction it is (fmaxf first quiets each operand with an instruction of its own)
+__device__ __forceinline__ float max3_f32(const float a, const float b, const float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 struct ManyCall {
     const char *Q;   // [S][Gm][d] bf16
     float *out;      // [S][Gm][d] fp32
@@ -181,10 +189,23 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
                 uint4 ah[QW], al[QW];
 #pragma unroll
                 for (int w2 = 0; w2 < QW; ++w2) {
-                    // ---- lazy softmax reference (rows beyond nrows repeat the last row, so every score is a real one)
-                    float lm = fmaxf(fmaxf(fmaxf(c0[w2][0], c0[w2][1]), fmaxf(c0[w2][2], c0[w2][3])),
-                                     fmaxf(fmaxf(c1[w2][0], c1[w2][1]), fmaxf(c1[w2][2], c1[w2][3])));
-                    if (__any(lm > mx[w2] + kLazy || mx[w2] == -INFINITY)) {
+                    // ---- exponents a = (c - mx) log2(e), one fused multiply-add per score, and the lazy softmax
+                    //      reference: mx is only raised when a score exceeds it by kLazy (rows beyond nrows repeat
+                    //      the last row, so every score is a real one).  (The three-operand maximum is inline
+                    //      assembly: it reads the products of the multiply-adds, never a matrix-core result, whose
+                    //      read hazard the compiler only covers for its own instructions.)
+                    constexpr float kLog2e = 1.4426950408889634f;
+                    const float cs[8] = {c0[w2][0], c0[w2][1], c0[w2][2], c0[w2][3], c1[w2][0], c1[w2][1], c1[w2][2], c1[w2][3]};
+                    float ax[8];
+                    {
+                        const float mxl = -mx[w2] * kLog2e;   // +inf before the first row
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) ax[i] = fmaf(cs[i], kLog2e, mxl);
+                    }
+                    const float am = max3_f32(max3_f32(ax[0], ax[1], ax[2]), max3_f32(ax[3], ax[4], ax[5]),
+                                              max3_f32(ax[6], ax[7], ax[7]));
+                    if (__any(am > kLazy * kLog2e || mx[w2] == -INFINITY)) {
+                        float lm = fmaxf(fmaxf(fmaxf(cs[0], cs[1]), fmaxf(cs[2], cs[3])), fmaxf(fmaxf(cs[4], cs[5]), fmaxf(cs[6], cs[7])));
                         lm = fmaxf(lm, __shfl_xor(lm, 16));
                         lm = fmaxf(lm, __shfl_xor(lm, 32));
                         float scale = 1.f;
@@ -201,12 +222,14 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
                         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
                             for (int r = 0; r < 4; ++r) acc[w2][cb][r] *= sr[r];
+                        const float mxl = -mx[w2] * kLog2e;
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) ax[i] = fmaf(cs[i], kLog2e, mxl);
                     }
+                    const float ws[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
                     float e[8];
-                    e[0] = w0.x * __expf(c0[w2][0] - mx[w2]); e[1] = w0.y * __expf(c0[w2][1] - mx[w2]);
-                    e[2] = w0.z * __expf(c0[w2][2] - mx[w2]); e[3] = w0.w * __expf(c0[w2][3] - mx[w2]);
-                    e[4] = w1.x * __expf(c1[w2][0] - mx[w2]); e[5] = w1.y * __expf(c1[w2][1] - mx[w2]);
-                    e[6] = w1.z * __expf(c1[w2][2] - mx[w2]); e[7] = w1.w * __expf(c1[w2][3] - mx[w2]);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) e[i] = ws[i] * __builtin_amdgcn_exp2f(ax[i]);
                     if constexpr (TODEN) den[w2] += ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
                     if constexpr (HASV) {
                         // ---- weights as bf16 hi + lo, in contraction-slot order (slot j <-> e[j])

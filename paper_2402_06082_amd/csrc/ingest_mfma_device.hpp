@@ -71,7 +71,7 @@ struct SmemIngest {
     alignas(16) char kt[T * KS];
 };
 
-// median of three signed integers
+// median of three signed integers (inline assembly: operands must not be matrix-core results, see min_f32)
 __device__ __forceinline__ int med3_i32(const int a, const int b, const int c)
 {
     int r;

@@ -78,7 +78,8 @@ struct SmemMfma {
 };
 
 // min(a, b) as the one instruction it is (fminf first quiets its operands with one more instruction each); a NaN
-// operand is ignored
+// operand is ignored.  Inline assembly: never hand it a matrix-core result directly (the compiler covers the read
+// hazard of v_mfma results only for instructions of its own); results of ordinary vector instructions are fine.
 __device__ __forceinline__ float min_f32(const float a, const float b)
 {
     float r;
