@@ -512,6 +512,45 @@ def test_matrix_core_path_exact_decisions_on_lattice_keys(g, d, kernel_path):
         assert np.array_equal(ing.export_state(sid).assign, sg.export_state(sid).assign)
 
 
+@pytest.mark.parametrize("seed", range(30))
+def test_chunked_ingest_random_sweep(seed):
+    """Seeded random contexts for the chunked prefix ingest: row size, sample budget (also not a multiple of 4, also
+    beyond 64 blocks), window (none, shorter and longer than a chunk), table capacity (sometimes so small that
+    tokens are force-joined), call lengths cut at random places (a call shorter than the window, chunks of one
+    token, ragged 128-token chunks), cluster spread around delta.  State equal to the oracle's after every call."""
+    b = binding()
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([64, 128]))
+    S = int(rng.integers(1, 6))
+    s = int(rng.choice([1, 3, 4, 7, 64, 130, 257, 300]))
+    w = int(rng.choice([0, 1, 5, 64, 127, 128, 200]))
+    n = int(rng.integers(1, 1400))
+    comps = int(rng.choice([1, 3, 20, 60]))
+    spread = float(rng.choice([0.05, 0.2, 0.5]))
+    max_centers = int(rng.choice([0, 0, 0, 5, 40]))
+    gen = torch.Generator(device="cpu").manual_seed(int(rng.integers(1 << 30)))
+    cent = torch.randn(S, comps, d, generator=gen) * 2.0
+    comp = torch.randint(0, comps, (S, n), generator=gen)
+    K = torch.gather(cent, 1, comp[..., None].expand(S, n, d)) + spread * torch.randn(S, n, d, generator=gen)
+    V = torch.randn(S, n, d, generator=gen) * torch.exp(0.5 * torch.randn(S, n, 1, generator=gen))
+    if seed % 3 == 0:
+        V[:, n // 2] = 0.0                                    # a token that can never be sampled
+    K, V = K.to(torch.bfloat16).to(DEV), V.to(torch.bfloat16).to(DEV)
+    delta = spread * (2 * d) ** 0.5 * float(rng.choice([0.8, 1.0, 1.3]))
+    sg = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, seed=seed, device=DEV, assign_log_tokens=n,
+                  max_centers=max_centers)
+    oset = OracleSet(list(range(S)), d, delta, s, w, seed=seed, max_centers=max_centers)
+    cuts = sorted(set([0, n] + [int(x) for x in rng.integers(0, n + 1, size=int(rng.integers(0, 6)))]))
+    forced = 0
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        sg.ingest_prefix(K[:, lo:hi], V[:, lo:hi])
+        oset.ingest(K[:, lo:hi], V[:, lo:hi])
+        forced = oset.reconcile(sg)
+    assert forced <= 1, forced
+    print(f"seed {seed}: d={d} S={S} s={s} w={w} n={n} comps={comps} Mcap={max_centers} cuts={cuts} "
+          f"m={[o.m for o in oset.oracles]}")
+
+
 @pytest.mark.parametrize("g,d,kernel_path", [(1, 128, 0), (4, 128, 0), (1, 64, 0), (1, 256, 0), (1, 128, 1)])
 def test_twin_representatives_decided_by_two_exact_distances(g, d, kernel_path):
     """Every site of the key distribution holds two representatives a little more than delta apart, and the tokens
