@@ -551,6 +551,60 @@ def test_chunked_ingest_random_sweep(seed):
           f"m={[o.m for o in oset.oracles]}")
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_decode_steps_random_sweep(seed):
+    """Seeded random contexts for the decode entry points: row size, queries per stream, kernel family (row path,
+    LDS tiles, matrix-core kernels, split workgroups, generic), sample budget, window, table capacity, fused steps or
+    update + attend.  Outputs and state against the oracle, near-tie protocol included."""
+    b = binding()
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([64, 128, 128, 256]))
+    g = int(rng.choice([1, 1, 2, 4])) if d < 256 else int(rng.choice([1, 2]))
+    S = int(rng.integers(1, 5))
+    s = int(rng.choice([1, 5, 32, 100, 260]))
+    w = int(rng.choice([0, 1, 7, 40, 130]))
+    n0 = int(rng.integers(0, 500))
+    steps = int(rng.integers(20, 90))
+    comps = int(rng.choice([1, 4, 30]))
+    spread = float(rng.choice([0.1, 0.3]))
+    max_centers = int(rng.choice([0, 0, 0, 6, 50]))
+    kernel_path = int(rng.choice([0, 0, 0, 1, 2]))
+    split = int(rng.choice([0, 1, 1, 3]))
+    fused = bool(rng.integers(0, 2))
+    gen = torch.Generator(device="cpu").manual_seed(int(rng.integers(1 << 30)))
+    n = n0 + steps
+    cent = torch.randn(S, comps, d, generator=gen) * 2.0
+    comp = torch.randint(0, comps, (S, n), generator=gen)
+    K = torch.gather(cent, 1, comp[..., None].expand(S, n, d)) + spread * torch.randn(S, n, d, generator=gen)
+    V = torch.randn(S, n, d, generator=gen) * torch.exp(0.5 * torch.randn(S, n, 1, generator=gen))
+    Q = torch.randn(S, steps, g, d, generator=gen) / d ** 0.5
+    K, V, Q = (t.to(torch.bfloat16).to(DEV) for t in (K, V, Q))
+    delta = spread * (2 * d) ** 0.5 * float(rng.choice([0.8, 1.0, 1.3]))
+    sg = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, q_per_stream=g, seed=seed, device=DEV,
+                  assign_log_tokens=n, max_centers=max_centers, kernel_path=kernel_path, split_workgroups=split)
+    oset = OracleSet(list(range(S)), d, delta, s, w, seed=seed, max_centers=max_centers)
+    if n0 > 0:
+        sg.ingest_prefix(K[:, :n0], V[:, :n0])
+        oset.ingest(K[:, :n0], V[:, :n0])
+    outs = torch.empty(steps, S, g, d, dtype=torch.float32, device=DEV)
+    have = n0
+    for t in range(steps):
+        kt, vt, qt = K[:, n0 + t].contiguous(), V[:, n0 + t].contiguous(), Q[:, t].contiguous()
+        if fused:
+            sg.step(kt, vt, qt, outs[t])
+        else:
+            sg.update(kt, vt)
+            sg.attend(qt, outs[t])
+        have += 1
+    oset.decode(K[:, n0:], V[:, n0:], Q)
+    assert oset.reconcile(sg) <= 1
+    ref = oset.reference()
+    got = outs.cpu().numpy()
+    assert np.isfinite(got).all()
+    err = rel_l2(got, ref)
+    assert err.max() <= REL_L2_TOL, (err.max(), dict(d=d, g=g, S=S, s=s, w=w, n0=n0, kp=kernel_path, split=split))
+
+
 @pytest.mark.parametrize("g,d,kernel_path", [(1, 128, 0), (4, 128, 0), (1, 64, 0), (1, 256, 0), (1, 128, 1)])
 def test_twin_representatives_decided_by_two_exact_distances(g, d, kernel_path):
     """Every site of the key distribution holds two representatives a little more than delta apart, and the tokens
