@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # runs of this script, each scaled by what the counter reads for a plain 1 GiB device copy
 # (profiles/step_kernel_cfg3.txt, profiles/step_kernel_cfg4.txt, profiles/step_kernel_cfg5.txt): a constant
 # taken from those runs, not measured in the run that prints it.  Workloads without a measurement report null.
-MEASURED_TRAFFIC_BYTES = {"cfg3": 4.0395e9, "cfg4": 5.3677e9, "cfg5": 4.0379e9}
+MEASURED_TRAFFIC_BYTES = {"cfg3": 4.0308e9, "cfg4": 5.3487e9, "cfg5": 4.0311e9}
 
 
 def algorithmic_bytes(cfg, streams, total_centers, t=0):
