@@ -41,6 +41,17 @@ __device__ __forceinline__ float max3_f32(const float a, const float b, const fl
     return r;
 }
 
+// v * f in the register of v.  The rescaling of the accumulators sits in a rarely taken branch; written as plain
+// multiplications the compiler puts the products into a second set of registers and copies the whole first set on
+// the common path.  (The operands are accumulators of matrix-core instructions issued before this tile's score
+// contraction, whose results have been consumed by then: in-order completion covers the read hazard that the
+// compiler does not insert for inline assembly.)
+__device__ __forceinline__ float scaled_in_place(float v, const float f)
+{
+    asm volatile("v_mul_f32 %0, %0, %1" : "+v"(v) : "v"(f));
+    return v;
+}
+
 struct ManyCall {
     const char *Q;   // [S][Gm][d] bf16
     float *out;      // [S][Gm][d] fp32
@@ -300,6 +311,325 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
                 num = fmaf(accbuf[((size_t)wv * 16 + qn) * D + c], sc, num);
             }
             put_out(st, call.out, (sid * (size_t)call.Gm + q) * D + c, num / dn);
+        }
+    }
+}
+
+// ---- The same block of queries, 128-element bf16 rows, 33 or more queries (every wavefront owns its queries for
+//      all rows): the rows go from HBM straight into LDS (global_load_lds_dwordx4: lane i's 16 bytes land at
+//      M0 + 16 i), so no register holds a row in flight, nothing is stored to LDS by hand, and one barrier per
+//      stage is enough.  A stage is two halves of 32 rows x 256 bytes in one of three buffers: the next two stages
+//      are in flight while one is consumed, across the three kinds of rows (the pipeline never drains between
+//      them).  Representatives fill both halves with keys (64 rows per stage); sampled pairs and window rows put
+//      32 keys in the first half and their 32 values in the second.  Rows are unpadded; instead the 16-byte
+//      pieces of a row are permuted on the way in (the loading lane picks the global piece for its LDS slot):
+//      keys by piece ^ (row mod 16), values by piece ^ 2 (row mod 8), which keeps the operand reads of both
+//      contractions free of bank conflicts.  The per-row weights of the whole stream are computed once, up
+//      front, into LDS.
+constexpr int kDmaHalf = 32 * 256;           // bytes of 32 rows
+constexpr int kDmaStage = 2 * kDmaHalf;
+// rows with weights in LDS (representatives padded to 64, sampled pairs to 32) that fit beside three stage buffers
+// with two workgroups per CU: 3 x 16 KB + 28 KB = 76 KB of the CU's 160 KB each
+constexpr int kDmaBufs = 3;
+constexpr int kDmaRows = 7168;
+
+// NB stage buffers; WCAP = rows of one stream (each kind padded to whole stages) whose weights fit
+template <int NB, int WCAP>
+struct SmemManyDma {
+    alignas(16) char buf[NB][kDmaStage];
+    alignas(16) float w[WCAP];
+};
+
+// one direct load: 16 bytes per lane from `g` to LDS byte address lds + 16 lane (lds is wave-uniform); counted by
+// vmcnt like any load.  (The compiler does not know of these loads: the waits for them are written out below.)
+template <bool NT>
+__device__ __forceinline__ void dma16(const char *base, const uint32_t off, const uint32_t lds)
+{
+    // base (wave-uniform) + off (per lane, unsigned 32 bits)
+    if constexpr (NT)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(off), "s"(base), "s"(lds) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads()   // until at most N of this wavefront's loads are outstanding
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <bool NT, int QW, int NB, int WCAP, int OCC>
+__global__ __launch_bounds__(kWG, OCC) void attend_many_dma_kernel(const State st, const ManyCall call)
+{
+    static_assert(NB == 2 || NB == 3, "two or three stage buffers");
+    static_assert(kWaves == 4 && kWG == 256, "four wavefronts, each with its own QW tiles of 16 queries");
+    constexpr int NK = 4, NCB = 8, D = 128;
+    constexpr size_t ROWB = 256;
+    constexpr int LPS = 4;   // direct loads per wavefront and stage
+    __shared__ SmemManyDma<NB, WCAP> sm;
+
+    const int xcd = blockIdx.x & 7;
+    const size_t j = blockIdx.x >> 3;
+    const size_t sid = (j / call.tiles) * 8 + xcd;
+    const int tile = (int)(j % call.tiles);
+    if (sid >= (size_t)call.streams) return;   // padding of the stream count to a multiple of 8 (whole workgroup leaves)
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n16 = lane & 15, L = lane >> 4;
+
+    const char *const X = st.X + sid * (size_t)st.Mcap * ROWB;
+    const char *const Ks = st.Ks + sid * (size_t)st.s * ROWB;
+    const char *const Vs = st.Vs + sid * (size_t)st.s * ROWB;
+    const char *const Kw = st.Kw + sid * (size_t)st.w * ROWB;
+    const char *const Vw = st.Vw + sid * (size_t)st.w * ROWB;
+    const int m = st.m[sid];
+    const int64_t n_seen = tokens_seen(st, call.n_seen);
+    const int64_t n_evicted = st.w == 0 ? n_seen : (n_seen > st.w ? n_seen - st.w : 0);
+    const int fill = (int)(n_seen < st.w ? n_seen : st.w);
+
+    // stages: n0 of 64 representatives, n1 of 32 sampled pairs, n2 of 32 window rows
+    const int n0 = (m + 63) >> 6, n1 = n_evicted > 0 ? (st.s + 31) >> 5 : 0, n2 = (fill + 31) >> 5;
+    const int NS = n0 + n1 + n2;
+    const int W1 = n0 * 64, W2 = W1 + n1 * 32;   // where the weights of the sampled pairs start; rows with weights
+    if (W2 > WCAP) return;   // (the host has checked the context's capacity against WCAP: never taken)
+
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)&sm.buf[0][0];
+    // this lane's slots of the wavefront's two 1 KB pieces of a half: row of the half and 16-byte position in LDS;
+    // the global piece that belongs there, as an offset from the half's first row (keys / values)
+    const int prow = lane >> 4, ppc = lane & 15;
+    uint32_t koff[2], voff_g[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = (wave * 2 + i) * 4 + prow;
+        koff[i] = (uint32_t)(row * 256 + ((ppc ^ (row & 15)) << 4));
+        voff_g[i] = (uint32_t)(row * 256 + ((ppc ^ ((row & 7) << 1)) << 4));
+    }
+    auto issue = [&](const int stg, const int b) __attribute__((always_inline)) {
+        const char *ba, *bb;
+        int ra0, rb0, nrows;
+        bool bkeys = false;
+        if (stg < n0) {
+            ba = bb = X; ra0 = stg * 64; rb0 = ra0 + 32; nrows = m; bkeys = true;
+        } else if (stg < n0 + n1) {
+            ba = Ks; bb = Vs; ra0 = rb0 = (stg - n0) * 32; nrows = st.s;
+        } else {
+            ba = Kw; bb = Vw; ra0 = rb0 = (stg - n0 - n1) * 32; nrows = fill;
+        }
+        const uint32_t la = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)b * kDmaStage + (uint32_t)wave * 2048u);
+        if (rb0 + 32 <= nrows) {
+            // whole halves: the lane's offsets are the loop-invariant ones
+            const char *pa = ba + (size_t)ra0 * ROWB, *pb = bb + (size_t)rb0 * ROWB;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                dma16<NT>(pa, koff[i], la + i * 1024);
+                dma16<NT>(pb, bkeys ? koff[i] : voff_g[i], la + kDmaHalf + i * 1024);
+            }
+        } else {
+            // the last rows of a kind: rows past the end repeat the last one
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int row = (wave * 2 + i) * 4 + prow;   // row of the half
+                int ra = ra0 + row, rb = rb0 + row;
+                ra = ra < nrows ? ra : nrows - 1;
+                rb = rb < nrows ? rb : nrows - 1;
+                const int ca = ppc ^ (row & 15);
+                const int cb = bkeys ? ca : ppc ^ ((row & 7) << 1);
+                dma16<NT>(ba, (uint32_t)(ra * 256 + ca * 16), la + i * 1024);
+                dma16<NT>(bb, (uint32_t)(rb * 256 + cb * 16), la + kDmaHalf + i * 1024);
+            }
+        }
+    };
+    if (NS > 0) issue(0, 0);
+    if (NB > 2 && NS > 1) issue(1, 1);
+
+    // the wavefront's QW tiles of 16 queries as the B operands of the score contraction
+    const int q0 = (tile * 4 + wave) * QW * 16;
+    uint4 Bq[QW][NK];
+#pragma unroll
+    for (int w2 = 0; w2 < QW; ++w2) {
+        const int q = q0 + w2 * 16 + n16 < call.Gm ? q0 + w2 * 16 + n16 : call.Gm - 1;
+        const char *qp = call.Q + (sid * (size_t)call.Gm + q) * ROWB;
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) Bq[w2][kk] = ld16(qp + (L + 4 * kk) * 16);
+    }
+
+    // ---- weights of the rows: n_i for representatives, mu / (s ||v_j||^2) for sampled pairs, 0 for the padding of
+    //      each kind to whole stages (window rows weigh 1: no array)
+    {
+        const int32_t *const cnt = st.cnt + sid * (size_t)st.McapS;
+        const float *const svn = st.svn + sid * (size_t)st.sS;
+        const float mus = (float)(st.mu[sid] / (double)st.s);
+        for (int i = tid; i < W2; i += kWG) {
+            float wv = 0.f;
+            if (i < W1) {
+                if (i < m) wv = (float)cnt[i];
+            } else if (i - W1 < st.s) {
+                const float vn = svn[i - W1];
+                wv = vn > 0.f ? mus / vn : 0.f;
+            }
+            sm.w[i] = wv;
+        }
+    }
+
+    float mx[QW], den[QW];             // per query n16 of tile w2; mx is the same in the four lanes of a query
+    floatx4_t acc[QW][NCB];            // O[query 4L + r][column 16 cb + n16]
+#pragma unroll
+    for (int w2 = 0; w2 < QW; ++w2) {
+        mx[w2] = -INFINITY;
+        den[w2] = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) acc[w2][cb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // operand offsets inside a half (see the permutations above)
+    const int aoff = n16 * 256 + ((L ^ (n16 & 3)) << 4) + ((n16 >> 2) << 6);      // key piece L of row n16; ^ (kk << 6)
+    const int vrow = 4 * L + (n16 >> 2);
+    const int voff = vrow * 256 + ((vrow & 7) << 5) + (n16 & 3) * 8;               // ^ (cb << 5)
+
+    // one tile of 32 rows: scores from the keys at `A`, weights, and (HASV) the products with the values at `B`
+    auto tile32 = [&](auto hasv_c, auto toden_c, const char *A, const char *B, const float4 w0, const float4 w1) __attribute__((always_inline)) {
+        constexpr bool HASV = decltype(hasv_c)::value, TODEN = decltype(toden_c)::value;
+        floatx4_t c0[QW], c1[QW];
+#pragma unroll
+        for (int w2 = 0; w2 < QW; ++w2) c0[w2] = c1[w2] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) {
+            const uint4 a0 = *reinterpret_cast<const uint4 *>(A + (aoff ^ (kk << 6)));
+            const uint4 a1 = *reinterpret_cast<const uint4 *>(A + 4096 + (aoff ^ (kk << 6)));
+#pragma unroll
+            for (int w2 = 0; w2 < QW; ++w2) {
+                c0[w2] = mfma_bf16(a0, Bq[w2][kk], c0[w2]);
+                c1[w2] = mfma_bf16(a1, Bq[w2][kk], c1[w2]);
+            }
+        }
+        uint4 ah[QW], al[QW];
+#pragma unroll
+        for (int w2 = 0; w2 < QW; ++w2) {
+            __builtin_amdgcn_sched_barrier(0);   // one query tile's weights at a time: bounds the live registers
+            // exponents a = (c - mx) log2(e), one fused multiply-add per score; the reference mx is only raised when
+            // a score exceeds it by kLazy (rows beyond the end repeat the last row, so every score is a real one).
+            // (The three-operand maximum is inline assembly: it reads the products of the multiply-adds, never a
+            // matrix-core result, whose read hazard the compiler only covers for its own instructions.)
+            constexpr float kLog2e = 1.4426950408889634f;
+            const float cs[8] = {c0[w2][0], c0[w2][1], c0[w2][2], c0[w2][3], c1[w2][0], c1[w2][1], c1[w2][2], c1[w2][3]};
+            float ax[8];
+            {
+                const float mxl = -mx[w2] * kLog2e;   // +inf before the first row
+#pragma unroll
+                for (int i = 0; i < 8; ++i) ax[i] = fmaf(cs[i], kLog2e, mxl);
+            }
+            const float am = max3_f32(max3_f32(ax[0], ax[1], ax[2]), max3_f32(ax[3], ax[4], ax[5]),
+                                      max3_f32(ax[6], ax[7], ax[7]));
+            if (__any(am > kLazy * kLog2e || mx[w2] == -INFINITY)) {
+                float lm = fmaxf(fmaxf(fmaxf(cs[0], cs[1]), fmaxf(cs[2], cs[3])), fmaxf(fmaxf(cs[4], cs[5]), fmaxf(cs[6], cs[7])));
+                lm = fmaxf(lm, __shfl_xor(lm, 16));
+                lm = fmaxf(lm, __shfl_xor(lm, 32));
+                float scale = 1.f;
+                if (lm > mx[w2] + kLazy || mx[w2] == -INFINITY) {
+                    scale = __expf(mx[w2] - lm);   // mx = -inf gives 0
+                    den[w2] *= scale;
+                    mx[w2] = lm;
+                }
+                float sr[4];   // the accumulators hold queries 4L + r: their factors come from those queries' lanes
+#pragma unroll
+                for (int r = 0; r < 4; ++r) sr[r] = __shfl(scale, 4 * L + r);
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[w2][cb][r] = scaled_in_place(acc[w2][cb][r], sr[r]);
+                const float mxl = -mx[w2] * kLog2e;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) ax[i] = fmaf(cs[i], kLog2e, mxl);
+            }
+            const float ws[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+            float e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) e[i] = ws[i] * __builtin_amdgcn_exp2f(ax[i]);
+            if constexpr (TODEN) den[w2] += ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+            if constexpr (HASV) {
+                // weights as bf16 hi + lo, in contraction-slot order (slot j <-> e[j])
+                ah[w2].x = pack_bf16(e[0], e[1]); ah[w2].y = pack_bf16(e[2], e[3]);
+                ah[w2].z = pack_bf16(e[4], e[5]); ah[w2].w = pack_bf16(e[6], e[7]);
+                al[w2].x = pack_bf16(e[0] - bf16_lo(ah[w2].x), e[1] - bf16_hi(ah[w2].x));
+                al[w2].y = pack_bf16(e[2] - bf16_lo(ah[w2].y), e[3] - bf16_hi(ah[w2].y));
+                al[w2].z = pack_bf16(e[4] - bf16_lo(ah[w2].z), e[5] - bf16_hi(ah[w2].z));
+                al[w2].w = pack_bf16(e[6] - bf16_lo(ah[w2].w), e[7] - bf16_hi(ah[w2].w));
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (HASV) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                const char *v0 = B + (voff ^ (cb << 5));
+                const u32x2_t b0 = lds_read_tr16(v0), b1 = lds_read_tr16(v0 + 4096);
+                const uint4 b = make_uint4(b0[0], b0[1], b1[0], b1[1]);
+#pragma unroll
+                for (int w2 = 0; w2 < QW; ++w2) {
+                    acc[w2][cb] = mfma_bf16(ah[w2], b, acc[w2][cb]);
+                    acc[w2][cb] = mfma_bf16(al[w2], b, acc[w2][cb]);
+                }
+            }
+        }
+    };
+
+    // every load the compiler knows of (queries, weights) is complete from here on: it then places no wait of its
+    // own inside the loop, where it would also wait for the direct loads of the stages ahead
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+
+    using T = std::true_type;
+    using F = std::false_type;
+    int b = 0;
+    for (int it = 0; it < NS; ++it) {
+        // this wavefront's loads of stage `it` have landed (those of the next stage may still be in flight) ...
+        if (NB > 2 && it + 1 < NS) wait_loads<LPS>();
+        else wait_loads<0>();
+        lds_barrier();   // ... and so have everybody's; the buffer of stage it - 1 is free (also orders the weights)
+        if (it + NB - 1 < NS) issue(it + NB - 1, b == 0 ? NB - 1 : b - 1);
+        // (the buffer's offset is made opaque: otherwise the operand addresses of all three buffers are kept in
+        // registers across the loop)
+        uint32_t boff = (uint32_t)b * kDmaStage;
+        asm volatile("" : "+v"(boff));
+        const char *A = &sm.buf[0][0] + boff, *B = A + kDmaHalf;
+        // the weights of this lane's rows 4L..4L+3 and 16+4L..16+4L+3 of a tile
+        auto weights = [&](const int at, float4 &w0, float4 &w1) __attribute__((always_inline)) {
+            w0 = *reinterpret_cast<const float4 *>(&sm.w[at + 4 * L]);
+            w1 = *reinterpret_cast<const float4 *>(&sm.w[at + 16 + 4 * L]);
+        };
+        float4 w0, w1;
+        if (it < n0) {
+            weights(it * 64, w0, w1);
+            tile32(F{}, T{}, A, A, w0, w1);
+            if (it * 64 + 32 < m) {
+                weights(it * 64 + 32, w0, w1);
+                tile32(F{}, T{}, B, B, w0, w1);
+            }
+        } else if (it < n0 + n1) {
+            weights(W1 + (it - n0) * 32, w0, w1);
+            tile32(T{}, F{}, A, B, w0, w1);
+        } else {
+            const int left = fill - (it - n0 - n1) * 32 - 4 * L;   // window rows from this lane's first one on
+            w0 = make_float4(left > 0 ? 1.f : 0.f, left > 1 ? 1.f : 0.f, left > 2 ? 1.f : 0.f, left > 3 ? 1.f : 0.f);
+            w1 = make_float4(left > 16 ? 1.f : 0.f, left > 17 ? 1.f : 0.f, left > 18 ? 1.f : 0.f, left > 19 ? 1.f : 0.f);
+            tile32(T{}, T{}, A, B, w0, w1);
+        }
+        b = b == NB - 1 ? 0 : b + 1;
+    }
+
+    // ---- every wavefront owns its queries: normalise and store straight from the accumulators (16 lanes write 64
+    //      consecutive bytes of one query's row)
+#pragma unroll
+    for (int w2 = 0; w2 < QW; ++w2) {
+        float dsum = den[w2];
+        dsum += __shfl_xor(dsum, 16);
+        dsum += __shfl_xor(dsum, 32);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float dn = __shfl(dsum, 4 * L + r);
+            const int q = q0 + w2 * 16 + 4 * L + r;
+            if (q < call.Gm) {
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+                    put_out(st, call.out, (sid * (size_t)call.Gm + q) * D + cb * 16 + n16, acc[w2][cb][r] / dn);
+            }
         }
     }
 }

@@ -532,7 +532,15 @@ int subgen_attend_many(subgen_ctx *c, const void *Q, int32_t n_queries, void *ou
         const int64_t blocks = (c->S + 7) / 8 * 8 * (int64_t)mc.tiles;
         if (blocks > 0x7fffffffLL) return SUBGEN_ECAPACITY;
         const dim3 grid((unsigned)blocks), wg(sg::kWG);
-        if (NK == 2) {
+        // 128-element rows and more than 32 queries: the kernel that brings the rows into LDS without registers; it
+        // keeps the weights of a stream's representatives and sampled pairs in LDS, which bounds their number
+        const int64_t wrows = ((int64_t)c->st.Mcap + 63) / 64 * 64 + ((int64_t)c->st.s + 31) / 32 * 32;
+        if (NK == 4 && QT == 4 && wrows <= sg::kDmaRows) {
+            constexpr int NB = sg::kDmaBufs, WC = sg::kDmaRows;
+            if (QW == 1) hipLaunchKernelGGL((sg::attend_many_dma_kernel<true, 1, NB, WC, 2>), grid, wg, 0, c->stream, c->st, mc);
+            else if (mc.tiles == 1) hipLaunchKernelGGL((sg::attend_many_dma_kernel<true, 2, NB, WC, 2>), grid, wg, 0, c->stream, c->st, mc);
+            else hipLaunchKernelGGL((sg::attend_many_dma_kernel<false, 2, NB, WC, 2>), grid, wg, 0, c->stream, c->st, mc);
+        } else if (NK == 2) {
             if (QT == 1) hipLaunchKernelGGL((sg::attend_many_kernel<2, 1, true>), grid, wg, 0, c->stream, c->st, mc);
             else if (QT == 2) hipLaunchKernelGGL((sg::attend_many_kernel<2, 2, true>), grid, wg, 0, c->stream, c->st, mc);
             else if (QW == 1) hipLaunchKernelGGL((sg::attend_many_kernel<2, 4, true>), grid, wg, 0, c->stream, c->st, mc);

@@ -351,6 +351,37 @@ def test_attend_many_matches_the_oracle_query_by_query(dtype, d, kernel_path, t,
     assert e.value.code == -1
 
 
+@pytest.mark.parametrize("max_centers", [2048, 8192])
+def test_attend_many_with_large_and_small_center_capacity(max_centers):
+    """subgen_attend_many on 128-element rows with more than 32 queries: contexts whose capacity fits the LDS weight
+    array of the direct-to-LDS kernel take it, larger ones the register-staged kernel; both against the oracle, with
+    a window that wraps, row counts off the tile sizes and query counts around the 64 / 128 per workgroup."""
+    b = binding()
+    d, s, w, n, S = 128, 200, 70, 900, 5
+    gen = torch.Generator(device="cpu").manual_seed(max_centers)
+    cent = torch.randn(S, 60, d, generator=gen) * 2.0
+    comp = torch.randint(0, 60, (S, n), generator=gen)
+    K = torch.gather(cent, 1, comp[..., None].expand(S, n, d)) + 0.2 * torch.randn(S, n, d, generator=gen)
+    V = torch.randn(S, n, d, generator=gen) * torch.exp(0.5 * torch.randn(S, n, 1, generator=gen))
+    K, V = K.to(torch.bfloat16).to(DEV), V.to(torch.bfloat16).to(DEV)
+    delta = 0.2 * (2 * d) ** 0.5 * 0.95
+    sg = b.SubGen(S, d, delta, s, w, dtype=torch.bfloat16, seed=6, device=DEV, max_centers=max_centers)
+    oracles = make_oracles(S, d, delta, s, w, seed=6, max_centers=max_centers)
+    sg.ingest_prefix(K, V)
+    Kc, Vc = to_f32_np(K), to_f32_np(V)
+    for i, o in enumerate(oracles):
+        o.ingest(Kc[i], Vc[i])
+    assert compare_state(sg, oracles) == 0
+    for nq in (40, 64, 127, 129, 260):
+        Q = (torch.randn(S, nq, d, generator=gen) / d ** 0.5 * 2.0).to(torch.bfloat16).to(DEV)
+        out = sg.attend_many(Q).cpu().numpy()
+        Qc = to_f32_np(Q)
+        ref = np.stack([[o.attend(Qc[i, h]) for h in range(nq)] for i, o in enumerate(oracles)])
+        assert np.isfinite(out).all()
+        assert rel_l2(out, ref).max() <= REL_L2_TOL, (nq, rel_l2(out, ref).max())
+    assert compare_state(sg, oracles) == 0
+
+
 @pytest.mark.parametrize("dtype,d,g,streams", [(torch.bfloat16, 128, 1, 3), (torch.bfloat16, 128, 1, 130),
                                                (torch.bfloat16, 128, 4, 3), (torch.float32, 64, 2, 3)])
 def test_captured_step_replays_like_eager_steps(dtype, d, g, streams):
