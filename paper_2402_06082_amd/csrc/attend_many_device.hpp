@@ -485,8 +485,12 @@ __global__ __launch_bounds__(kWG, OCC) void attend_many_dma_kernel(const State s
     const int vrow = 4 * L + (n16 >> 2);
     const int voff = vrow * 256 + ((vrow & 7) << 5) + (n16 & 3) * 8;               // ^ (cb << 5)
 
-    // one tile of 32 rows: scores from the keys at `A`, weights, and (HASV) the products with the values at `B`
-    auto tile32 = [&](auto hasv_c, auto toden_c, const char *A, const char *B, const float4 w0, const float4 w1) __attribute__((always_inline)) {
+    // One tile of 32 rows in two parts.  scores_weights: scores from the keys at `A`, weights e, the normaliser's
+    // share, (HASV) the weights as bf16 operands ah + al; returns whether a reference was raised, with the factors of
+    // the accumulators in rescale[].  products: the products of ah + al with the values at `B`.
+    uint4 ah[QW], al[QW];
+    float rescale[QW];     // factor of the accumulators of query n16 (1 unless its reference was raised)
+    auto scores_weights = [&](auto hasv_c, auto toden_c, const char *A, const float4 w0, const float4 w1) __attribute__((always_inline)) -> bool {
         constexpr bool HASV = decltype(hasv_c)::value, TODEN = decltype(toden_c)::value;
         floatx4_t c0[QW], c1[QW];
 #pragma unroll
@@ -501,10 +505,11 @@ __global__ __launch_bounds__(kWG, OCC) void attend_many_dma_kernel(const State s
                 c1[w2] = mfma_bf16(a1, Bq[w2][kk], c1[w2]);
             }
         }
-        uint4 ah[QW], al[QW];
+        bool raised = false;
 #pragma unroll
         for (int w2 = 0; w2 < QW; ++w2) {
             __builtin_amdgcn_sched_barrier(0);   // one query tile's weights at a time: bounds the live registers
+            rescale[w2] = 1.f;
             // exponents a = (c - mx) log2(e), one fused multiply-add per score; the reference mx is only raised when
             // a score exceeds it by kLazy (rows beyond the end repeat the last row, so every score is a real one).
             // (The three-operand maximum is inline assembly: it reads the products of the multiply-adds, never a
@@ -523,19 +528,12 @@ __global__ __launch_bounds__(kWG, OCC) void attend_many_dma_kernel(const State s
                 float lm = fmaxf(fmaxf(fmaxf(cs[0], cs[1]), fmaxf(cs[2], cs[3])), fmaxf(fmaxf(cs[4], cs[5]), fmaxf(cs[6], cs[7])));
                 lm = fmaxf(lm, __shfl_xor(lm, 16));
                 lm = fmaxf(lm, __shfl_xor(lm, 32));
-                float scale = 1.f;
                 if (lm > mx[w2] + kLazy || mx[w2] == -INFINITY) {
-                    scale = __expf(mx[w2] - lm);   // mx = -inf gives 0
-                    den[w2] *= scale;
+                    rescale[w2] = __expf(mx[w2] - lm);   // mx = -inf gives 0
+                    den[w2] *= rescale[w2];
                     mx[w2] = lm;
                 }
-                float sr[4];   // the accumulators hold queries 4L + r: their factors come from those queries' lanes
-#pragma unroll
-                for (int r = 0; r < 4; ++r) sr[r] = __shfl(scale, 4 * L + r);
-#pragma unroll
-                for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[w2][cb][r] = scaled_in_place(acc[w2][cb][r], sr[r]);
+                raised = true;
                 const float mxl = -mx[w2] * kLog2e;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) ax[i] = fmaf(cs[i], kLog2e, mxl);
@@ -556,18 +554,41 @@ __global__ __launch_bounds__(kWG, OCC) void attend_many_dma_kernel(const State s
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (HASV) {
+        return raised;
+    };
+    auto products = [&](const char *B) __attribute__((always_inline)) {
+        // two column blocks at a time, all hi products before the lo ones: the two products into one accumulator
+        // are then four (QW = 2) or two matrix-core instructions apart instead of back to back
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-                const char *v0 = B + (voff ^ (cb << 5));
+        for (int cb = 0; cb < NCB; cb += 2) {
+            uint4 bv[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const char *v0 = B + (voff ^ ((cb + u) << 5));
                 const u32x2_t b0 = lds_read_tr16(v0), b1 = lds_read_tr16(v0 + 4096);
-                const uint4 b = make_uint4(b0[0], b0[1], b1[0], b1[1]);
-#pragma unroll
-                for (int w2 = 0; w2 < QW; ++w2) {
-                    acc[w2][cb] = mfma_bf16(ah[w2], b, acc[w2][cb]);
-                    acc[w2][cb] = mfma_bf16(al[w2], b, acc[w2][cb]);
-                }
+                bv[u] = make_uint4(b0[0], b0[1], b1[0], b1[1]);
             }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int w2 = 0; w2 < QW; ++w2) acc[w2][cb + u] = mfma_bf16(ah[w2], bv[u], acc[w2][cb + u]);
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int w2 = 0; w2 < QW; ++w2) acc[w2][cb + u] = mfma_bf16(al[w2], bv[u], acc[w2][cb + u]);
+        }
+    };
+    // the accumulators of a tile that raised a reference: O[query 4L + r] takes the factor of that query's lanes
+    auto rescale_accumulators = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int w2 = 0; w2 < QW; ++w2) {
+            float sr[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sr[r] = __shfl(rescale[w2], 4 * L + r);
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[w2][cb][r] *= sr[r];
         }
     };
 
@@ -577,41 +598,76 @@ __global__ __launch_bounds__(kWG, OCC) void attend_many_dma_kernel(const State s
 
     using T = std::true_type;
     using F = std::false_type;
+    // Start of a stage: its rows are in LDS for everybody, the buffer of the stage before it is free, the stage
+    // NB - 1 ahead is requested into that buffer.  Returns the stage's first half.
     int b = 0;
-    for (int it = 0; it < NS; ++it) {
+    auto next_stage = [&](const int it) __attribute__((always_inline)) -> const char * {
         // this wavefront's loads of stage `it` have landed (those of the next stage may still be in flight) ...
         if (NB > 2 && it + 1 < NS) wait_loads<LPS>();
         else wait_loads<0>();
         lds_barrier();   // ... and so have everybody's; the buffer of stage it - 1 is free (also orders the weights)
         if (it + NB - 1 < NS) issue(it + NB - 1, b == 0 ? NB - 1 : b - 1);
-        // (the buffer's offset is made opaque: otherwise the operand addresses of all three buffers are kept in
+        // (the buffer's offset is made opaque: otherwise the operand addresses of all buffers are kept in
         // registers across the loop)
         uint32_t boff = (uint32_t)b * kDmaStage;
         asm volatile("" : "+v"(boff));
-        const char *A = &sm.buf[0][0] + boff, *B = A + kDmaHalf;
-        // the weights of this lane's rows 4L..4L+3 and 16+4L..16+4L+3 of a tile
-        auto weights = [&](const int at, float4 &w0, float4 &w1) __attribute__((always_inline)) {
-            w0 = *reinterpret_cast<const float4 *>(&sm.w[at + 4 * L]);
-            w1 = *reinterpret_cast<const float4 *>(&sm.w[at + 16 + 4 * L]);
-        };
-        float4 w0, w1;
-        if (it < n0) {
-            weights(it * 64, w0, w1);
-            tile32(F{}, T{}, A, A, w0, w1);
-            if (it * 64 + 32 < m) {
-                weights(it * 64 + 32, w0, w1);
-                tile32(F{}, T{}, B, B, w0, w1);
-            }
-        } else if (it < n0 + n1) {
-            weights(W1 + (it - n0) * 32, w0, w1);
-            tile32(T{}, F{}, A, B, w0, w1);
-        } else {
-            const int left = fill - (it - n0 - n1) * 32 - 4 * L;   // window rows from this lane's first one on
-            w0 = make_float4(left > 0 ? 1.f : 0.f, left > 1 ? 1.f : 0.f, left > 2 ? 1.f : 0.f, left > 3 ? 1.f : 0.f);
-            w1 = make_float4(left > 16 ? 1.f : 0.f, left > 17 ? 1.f : 0.f, left > 18 ? 1.f : 0.f, left > 19 ? 1.f : 0.f);
-            tile32(T{}, T{}, A, B, w0, w1);
-        }
         b = b == NB - 1 ? 0 : b + 1;
+        return &sm.buf[0][0] + boff;
+    };
+    // the weights of this lane's rows 4L..4L+3 and 16+4L..16+4L+3 of a tile
+    auto weights = [&](const int at, float4 &w0, float4 &w1) __attribute__((always_inline)) {
+        w0 = *reinterpret_cast<const float4 *>(&sm.w[at + 4 * L]);
+        w1 = *reinterpret_cast<const float4 *>(&sm.w[at + 16 + 4 * L]);
+    };
+    // One loop per kind of row, each around a single copy of the tile code, and the rare tile that raises a reference
+    // is finished outside the loop of the common ones: with the kinds (or the rescaling) in branches of one loop the
+    // accumulators end every iteration in other registers than they started in and are copied back, 64 to 130
+    // moves per stage.
+    int it = 0;
+    for (; it < n0; ++it) {
+        const char *A = next_stage(it);
+#pragma unroll 1
+        for (int h = 0; h < 2; ++h) {
+            if (it * 64 + 32 * h >= m) break;
+            float4 w0, w1;
+            weights(it * 64 + 32 * h, w0, w1);
+            scores_weights(F{}, T{}, A + h * kDmaHalf, w0, w1);   // (the accumulators are still zero: nothing to rescale)
+        }
+    }
+    while (it < n0 + n1) {
+        const char *A = nullptr;
+        bool raised = false;
+        for (; it < n0 + n1; ++it) {
+            A = next_stage(it);
+            float4 w0, w1;
+            weights(W1 + (it - n0) * 32, w0, w1);
+            raised = scores_weights(T{}, F{}, A, w0, w1);
+            if (raised) break;
+            products(A + kDmaHalf);
+        }
+        if (raised) {
+            rescale_accumulators();
+            products(A + kDmaHalf);
+            ++it;
+        }
+    }
+    while (it < NS) {
+        const char *A = nullptr;
+        bool raised = false;
+        for (; it < NS; ++it) {
+            A = next_stage(it);
+            const int left = fill - (it - n0 - n1) * 32 - 4 * L;   // window rows from this lane's first one on
+            const float4 w0 = make_float4(left > 0 ? 1.f : 0.f, left > 1 ? 1.f : 0.f, left > 2 ? 1.f : 0.f, left > 3 ? 1.f : 0.f);
+            const float4 w1 = make_float4(left > 16 ? 1.f : 0.f, left > 17 ? 1.f : 0.f, left > 18 ? 1.f : 0.f, left > 19 ? 1.f : 0.f);
+            raised = scores_weights(T{}, T{}, A, w0, w1);
+            if (raised) break;
+            products(A + kDmaHalf);
+        }
+        if (raised) {
+            rescale_accumulators();
+            products(A + kDmaHalf);
+            ++it;
+        }
     }
 
     // ---- every wavefront owns its queries: normalise and store straight from the accumulators (16 lanes write 64
