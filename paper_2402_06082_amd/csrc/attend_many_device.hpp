@@ -544,13 +544,19 @@ __global__ __launch_bounds__(kWG, OCC) void attend_many_dma_kernel(const State s
             for (int i = 0; i < 8; ++i) e[i] = ws[i] * __builtin_amdgcn_exp2f(ax[i]);
             if constexpr (TODEN) den[w2] += ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
             if constexpr (HASV) {
-                // weights as bf16 hi + lo, in contraction-slot order (slot j <-> e[j])
-                ah[w2].x = pack_bf16(e[0], e[1]); ah[w2].y = pack_bf16(e[2], e[3]);
-                ah[w2].z = pack_bf16(e[4], e[5]); ah[w2].w = pack_bf16(e[6], e[7]);
-                al[w2].x = pack_bf16(e[0] - bf16_lo(ah[w2].x), e[1] - bf16_hi(ah[w2].x));
-                al[w2].y = pack_bf16(e[2] - bf16_lo(ah[w2].y), e[3] - bf16_hi(ah[w2].y));
-                al[w2].z = pack_bf16(e[4] - bf16_lo(ah[w2].z), e[5] - bf16_hi(ah[w2].z));
-                al[w2].w = pack_bf16(e[6] - bf16_lo(ah[w2].w), e[7] - bf16_hi(ah[w2].w));
+                // weights as bf16 hi + lo, in contraction-slot order (slot j <-> e[j]): hi = the upper half of
+                // the fp32 word (truncated; one AND gives it as a float, one byte permute packs a pair), lo = the
+                // exact remainder rounded to bf16: together 16 mantissa bits
+                uint32_t hp[4], lp[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t b0 = __float_as_uint(e[2 * i]), b1 = __float_as_uint(e[2 * i + 1]);
+                    hp[i] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
+                    lp[i] = pack_bf16(e[2 * i] - __uint_as_float(b0 & 0xffff0000u),
+                                      e[2 * i + 1] - __uint_as_float(b1 & 0xffff0000u));
+                }
+                ah[w2] = make_uint4(hp[0], hp[1], hp[2], hp[3]);
+                al[w2] = make_uint4(lp[0], lp[1], lp[2], lp[3]);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
