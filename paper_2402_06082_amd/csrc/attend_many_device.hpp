@@ -345,11 +345,15 @@ struct SmemManyDma {
 template <bool NT>
 __device__ __forceinline__ void dma16(const char *base, const uint32_t off, const uint32_t lds)
 {
-    // base (wave-uniform) + off (per lane, unsigned 32 bits)
+    // base (wave-uniform) + off (per lane, unsigned 32 bits); M0 carries the LDS address and is put back afterwards
+    // (the compiler keeps no account of M0 across inline assembly)
+    uint32_t m0_saved;
     if constexpr (NT)
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(off), "s"(base), "s"(lds) : "memory", "m0");
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt\n\ts_mov_b32 m0, %0"
+                     : "=&s"(m0_saved) : "v"(off), "s"(base), "s"(lds) : "memory");
     else
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds) : "memory", "m0");
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+                     : "=&s"(m0_saved) : "v"(off), "s"(base), "s"(lds) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_loads()   // until at most N of this wavefront's loads are outstanding
