@@ -324,8 +324,8 @@ __global__ __launch_bounds__(kWG, 2) void attend_many_kernel(const State st, con
 //      32 keys in the first half and their 32 values in the second.  Rows are unpadded; instead the 16-byte
 //      pieces of a row are permuted on the way in (the loading lane picks the global piece for its LDS slot):
 //      keys by piece ^ (row mod 16), values by piece ^ 2 (row mod 8), which keeps the operand reads of both
-//      contractions free of bank conflicts.  The per-row weights of the whole stream are computed once, up
-//      front, into LDS.
+//      contractions free of bank conflicts.  The weights of all representatives and sampled pairs of the stream
+//      are computed once, up front, into LDS (window rows weigh 1).
 constexpr int kDmaHalf = 32 * 256;           // bytes of 32 rows
 constexpr int kDmaStage = 2 * kDmaHalf;
 // rows with weights in LDS (representatives padded to 64, sampled pairs to 32) that fit beside three stage buffers
@@ -340,7 +340,7 @@ struct SmemManyDma {
     alignas(16) float w[WCAP];
 };
 
-// one direct load: 16 bytes per lane from `g` to LDS byte address lds + 16 lane (lds is wave-uniform); counted by
+// one direct load: 16 bytes per lane from base + off to LDS byte address lds + 16 lane (lds is wave-uniform); counted by
 // vmcnt like any load.  (The compiler does not know of these loads: the waits for them are written out below.)
 template <bool NT>
 __device__ __forceinline__ void dma16(const char *base, const uint32_t off, const uint32_t lds)
