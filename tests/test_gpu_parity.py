@@ -907,7 +907,7 @@ def test_bf16_outputs_are_the_fp32_outputs_rounded_once(dtype, d, g, kernel_path
         assert rel_l2(to_f32_np(c), ref).max() <= REL_L2_TOL and rel_l2(to_f32_np(a), ref).max() <= tol, tt
     qt = Q[:, n - 1].contiguous()
     assert torch.equal(lo.attend(qt), hi.attend(qt).to(torch.bfloat16))
-    for nq in (3, 21):                                  # grouped decode kernels and the matrix-core block kernel
+    for nq in (3, 21, 70):                              # grouped decode kernels and the matrix-core block kernels
         Qm = (torch.randn(S, nq, d, generator=gen) / d ** 0.5).to(dtype).to(DEV)
         am = lo.attend_many(Qm)
         assert am.dtype == torch.bfloat16 and torch.equal(am, hi.attend_many(Qm).to(torch.bfloat16)), nq
